@@ -1,0 +1,386 @@
+/*
+ * PiKV decode-step oracle: plain, slow, direct CPU arithmetic in double precision.
+ *
+ * THIS IS TEST INFRASTRUCTURE, NOT THE PRODUCT.  Only the test-suite, the smoke check
+ * and the benchmark's "cpu_baseline" leg may call it.  It shares no code, header,
+ * table or helper with the HIP library and knows nothing about how the GPU path
+ * blocks, splits or reorders the work.
+ *
+ * What it computes (PiKV, arxiv 2508.06526):
+ *   route    - Section 3.2: R(q) is a 0/1 mask over E experts with exactly k ones;
+ *              Table 1 row "TopK softmax" (optionally with an additive per-expert
+ *              penalty, the "Penalty Term" column of the same table).
+ *   attend   - Algorithm 1, the f_attn step: attention of the query over the cache
+ *              entries of the selected expert shards only; Section 3.3: entries may be
+ *              stored as width-d' codes and decoded (here: rank-r linear decoder,
+ *              Table 2 rows LoRA / LoRA++ without the bias) before use.
+ *   utility  - Section 3.4 / Table 3 row H2O: u_i = a_i, the attention mass an entry
+ *              received, accumulated over steps (decay 1) or with a decay < 1.
+ *   evict    - Algorithm 1, the scheduling step under bounded memory (Section 3.4):
+ *              keep the `capacity` highest-utility entries of a shard.
+ *   append   - Algorithm 1, Insert: constant-time write of one new entry per selected
+ *              shard into a fixed-capacity buffer (Section 3.1, storage invariants).
+ *
+ * Every sum is a double; inputs (float or bfloat16 bit patterns) are widened exactly;
+ * each output is rounded to float once.  No online softmax, no split reductions, no
+ * absorbed projections: a reader can check each loop against the definitions above.
+ *
+ * Pins (tests marked "not gpu"): softmax/sigmoid closed forms, brute-force sorts,
+ * k = E routed attention == dense attention computed by an independent numpy routine,
+ * constant-V / zero-q special cases, GQA replication, crop-decoder == zero padding,
+ * utility mass conservation, brute-force eviction.  Nothing in the paper prints a
+ * worked numeric example, so the choice between readings of the paper (which vector is
+ * routed, how gates enter, utility granularity, decay form) is pinned by the task
+ * statement only; the arithmetic of each reading is pinned as listed.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+enum { ORACLE_F32 = 0, ORACLE_BF16 = 1 };
+enum { ORACLE_COMBINE_LSE = 0, ORACLE_COMBINE_LOCAL = 1 };
+
+static double load_elem(const void *base, int64_t i, int dtype) {
+    if (dtype == ORACLE_F32) return (double)((const float *)base)[i];
+    uint32_t bits = (uint32_t)((const uint16_t *)base)[i] << 16;
+    float f;
+    memcpy(&f, &bits, sizeof f);
+    return (double)f;
+}
+
+static size_t elem_size(int dtype) { return dtype == ORACLE_F32 ? 4u : 2u; }
+
+/* ------------------------------------------------------------------ route */
+/* Section 3.2, Table 1 "TopK softmax": logits = x W_r (+ penalty), p = softmax over
+ * all E experts, the mask g has ones at the k largest logits (ties: lower expert index
+ * first), listed in descending order; gate weights are p renormalised over the k.     */
+typedef struct { double logit; int e; } route_key;
+
+static int route_cmp(const void *a, const void *b) {
+    const route_key *x = a, *y = b;
+    if (x->logit > y->logit) return -1;
+    if (x->logit < y->logit) return 1;
+    return (x->e > y->e) - (x->e < y->e);
+}
+
+int pikv_oracle_route(const void *x, const void *W_r, const float *bias, int rows, int d_r,
+                      int E, int k, int dtype, int32_t *topk_idx, float *gates,
+                      float *probs, double *logits) {
+    if (rows < 0 || d_r < 1 || E < 1 || k < 1 || k > E) return -1;
+    route_key *key = malloc(sizeof(route_key) * (size_t)E);
+    double *p = malloc(sizeof(double) * (size_t)E);
+    if (!key || !p) { free(key); free(p); return -2; }
+    for (int r = 0; r < rows; ++r) {
+        for (int e = 0; e < E; ++e) {
+            double acc = 0.0;
+            for (int j = 0; j < d_r; ++j)
+                acc += load_elem(x, (int64_t)r * d_r + j, dtype) *
+                       load_elem(W_r, (int64_t)j * E + e, dtype);
+            if (bias) acc += (double)bias[e];
+            if (isnan(acc)) acc = -INFINITY;
+            key[e].logit = acc;
+            key[e].e = e;
+            if (logits) logits[(int64_t)r * E + e] = acc;
+        }
+        double mx = -INFINITY;
+        for (int e = 0; e < E; ++e) if (key[e].logit > mx) mx = key[e].logit;
+        double den = 0.0;
+        for (int e = 0; e < E; ++e) { p[e] = exp(key[e].logit - mx); den += p[e]; }
+        for (int e = 0; e < E; ++e) {
+            p[e] /= den;
+            if (probs) probs[(int64_t)r * E + e] = (float)p[e];
+        }
+        qsort(key, (size_t)E, sizeof(route_key), route_cmp);
+        double sel = 0.0;
+        for (int j = 0; j < k; ++j) sel += p[key[j].e];
+        for (int j = 0; j < k; ++j) {
+            topk_idx[(int64_t)r * k + j] = key[j].e;
+            gates[(int64_t)r * k + j] = (float)(p[key[j].e] / sel);
+        }
+    }
+    free(key);
+    free(p);
+    return 0;
+}
+
+/* ----------------------------------------------------------------- attend */
+/* One (sequence b, query head h): attention over the selected shards, then the
+ * per-entry probabilities.  Row r of a shard's K for kv head hk is
+ * K[hk*stride_h + r*stride_s + 0..w), w = D (dense) or rank (codes).                  */
+static void entry_vector(const void *shard, int hk, int row, int64_t stride_h,
+                         int64_t stride_s, int D, int rank, const void *U, int dtype,
+                         double *out /*[D]*/) {
+    int64_t base = (int64_t)hk * stride_h + (int64_t)row * stride_s;
+    if (rank == 0) {
+        for (int d = 0; d < D; ++d) out[d] = load_elem(shard, base + d, dtype);
+        return;
+    }
+    /* Section 3.3: decoder D(.) of a rank-r code, x_d = sum_c code_c * U[hk][c][d].   */
+    for (int d = 0; d < D; ++d) {
+        double acc = 0.0;
+        for (int c = 0; c < rank; ++c)
+            acc += load_elem(shard, base + c, dtype) *
+                   load_elem(U, ((int64_t)hk * rank + c) * D + d, dtype);
+        out[d] = acc;
+    }
+}
+
+int pikv_oracle_attend(int B, int Hq, int Hkv, int D, int E, int S, int rank, int dtype,
+                       int64_t stride_h, int64_t stride_s, int route_rows_per_seq,
+                       const void *q, const void *const *K_shards,
+                       const void *const *V_shards, const void *U_K, const void *U_V,
+                       const int32_t *n_valid, const int32_t *topk_idx, const float *gates,
+                       int k, int combine, double scale, float *y, float *row_max,
+                       float *row_norm, double *prob /*[B,Hq,k,S] or NULL*/, double decay,
+                       float *utility /*[B,E,S] or NULL*/) {
+    if (B < 0 || Hq < 1 || Hkv < 1 || Hq % Hkv || D < 1 || E < 1 || S < 1 || k < 1 || k > E)
+        return -1;
+    if (route_rows_per_seq != 1 && route_rows_per_seq != Hq) return -1;
+    if (rank < 0 || (rank > 0 && (!U_K || !U_V))) return -1;
+    if (!(scale > 0.0)) scale = 1.0 / sqrt((double)D);
+    const int G = Hq / Hkv;
+    const int64_t per_head = (int64_t)k * S;
+    double *pbuf = prob;
+    if (!pbuf) {
+        pbuf = malloc(sizeof(double) * (size_t)B * Hq * per_head);
+        if (!pbuf) return -2;
+    }
+    int fail = 0;
+#pragma omp parallel for collapse(2) schedule(dynamic)
+    for (int b = 0; b < B; ++b) {
+        for (int h = 0; h < Hq; ++h) {
+            const int hk = h / G;
+            const int row = b * route_rows_per_seq + (route_rows_per_seq == 1 ? 0 : h);
+            const int32_t *sel = topk_idx + (int64_t)row * k;
+            const float *gsel = gates ? gates + (int64_t)row * k : NULL;
+            double *p = pbuf + ((int64_t)b * Hq + h) * per_head;
+            double *kv = malloc(sizeof(double) * (size_t)D);
+            double *o = malloc(sizeof(double) * (size_t)k * D);   /* o_e, per shard */
+            double *m = malloc(sizeof(double) * (size_t)k);
+            double *Z = malloc(sizeof(double) * (size_t)k);
+            if (!kv || !o || !m || !Z) {
+                fail = 1;
+                free(kv); free(o); free(m); free(Z);
+                continue;
+            }
+            for (int64_t i = 0; i < per_head; ++i) p[i] = 0.0;
+            /* per-shard softmax attention: s_i, m_e, Z_e, o_e */
+            for (int j = 0; j < k; ++j) {
+                const int e = sel[j];
+                const int n = n_valid[(int64_t)b * E + e];
+                m[j] = -INFINITY;
+                Z[j] = 0.0;
+                for (int d = 0; d < D; ++d) o[(int64_t)j * D + d] = 0.0;
+                if (n <= 0) continue;
+                const void *Ks = K_shards[(int64_t)b * E + e];
+                const void *Vs = V_shards[(int64_t)b * E + e];
+                double *s = p + (int64_t)j * S;          /* scores, reused for e^{s-m} */
+                for (int i = 0; i < n; ++i) {
+                    entry_vector(Ks, hk, i, stride_h, stride_s, D, rank, U_K, dtype, kv);
+                    double dot = 0.0;
+                    for (int d = 0; d < D; ++d)
+                        dot += load_elem(q, ((int64_t)b * Hq + h) * D + d, dtype) * kv[d];
+                    s[i] = scale * dot;
+                    if (s[i] > m[j]) m[j] = s[i];
+                }
+                for (int i = 0; i < n; ++i) {
+                    s[i] = exp(s[i] - m[j]);
+                    Z[j] += s[i];
+                }
+                for (int i = 0; i < n; ++i) {
+                    entry_vector(Vs, hk, i, stride_h, stride_s, D, rank, U_V, dtype, kv);
+                    for (int d = 0; d < D; ++d) o[(int64_t)j * D + d] += s[i] * kv[d];
+                }
+                for (int d = 0; d < D; ++d) o[(int64_t)j * D + d] /= Z[j];
+            }
+            /* combine the non-empty selected shards */
+            float *yo = y + ((int64_t)b * Hq + h) * D;
+            for (int d = 0; d < D; ++d) yo[d] = 0.0f;
+            double M = -INFINITY;
+            int any = 0;
+            for (int j = 0; j < k; ++j)
+                if (Z[j] > 0.0) { any = 1; if (m[j] > M) M = m[j]; }
+            double norm = 0.0;
+            if (any) {
+                double *acc = kv;                         /* reuse as [D] accumulator  */
+                for (int d = 0; d < D; ++d) acc[d] = 0.0;
+                if (combine == ORACLE_COMBINE_LSE) {
+                    /* joint softmax over the union of the shards, each entry weighted
+                     * by its shard's gate: p_i = g_e e^{s_i-M} / Zn                    */
+                    for (int j = 0; j < k; ++j)
+                        if (Z[j] > 0.0) norm += (gsel ? (double)gsel[j] : 1.0) * Z[j] * exp(m[j] - M);
+                    for (int j = 0; j < k; ++j) {
+                        if (!(Z[j] > 0.0)) continue;
+                        const double g = gsel ? (double)gsel[j] : 1.0;
+                        const double w = g * Z[j] * exp(m[j] - M) / norm;
+                        for (int d = 0; d < D; ++d) acc[d] += w * o[(int64_t)j * D + d];
+                        const int n = n_valid[(int64_t)b * E + sel[j]];
+                        double *pj = p + (int64_t)j * S;
+                        for (int i = 0; i < n; ++i) pj[i] = g * pj[i] * exp(m[j] - M) / norm;
+                    }
+                } else {
+                    /* per-shard softmax, outputs mixed by the renormalised gates      */
+                    for (int j = 0; j < k; ++j)
+                        if (Z[j] > 0.0) norm += gsel ? (double)gsel[j] : 1.0;
+                    for (int j = 0; j < k; ++j) {
+                        if (!(Z[j] > 0.0)) continue;
+                        const double gh = (gsel ? (double)gsel[j] : 1.0) / norm;
+                        for (int d = 0; d < D; ++d) acc[d] += gh * o[(int64_t)j * D + d];
+                        const int n = n_valid[(int64_t)b * E + sel[j]];
+                        double *pj = p + (int64_t)j * S;
+                        for (int i = 0; i < n; ++i) pj[i] = gh * pj[i] / Z[j];
+                    }
+                }
+                for (int d = 0; d < D; ++d) yo[d] = (float)acc[d];
+            }
+            if (row_max) row_max[(int64_t)b * Hq + h] = any ? (float)M : -INFINITY;
+            if (row_norm) row_norm[(int64_t)b * Hq + h] = (float)norm;
+            free(kv); free(o); free(m); free(Z);
+        }
+    }
+    if (fail) { if (!prob) free(pbuf); return -2; }
+
+    /* Section 3.4, Table 3 (H2O): u_i <- decay*u_i + a_i, a_i = sum over the query
+     * heads that read entry i of its attention probability.  Only shards that some
+     * head visited this step (and that hold entries) are touched.                      */
+    if (utility) {
+#pragma omp parallel for collapse(2) schedule(dynamic)
+        for (int b = 0; b < B; ++b) {
+            for (int e = 0; e < E; ++e) {
+                const int n = n_valid[(int64_t)b * E + e];
+                if (n <= 0) continue;
+                int visited = 0;
+                for (int h = 0; h < Hq && !visited; ++h) {
+                    const int row = b * route_rows_per_seq + (route_rows_per_seq == 1 ? 0 : h);
+                    for (int j = 0; j < k; ++j)
+                        if (topk_idx[(int64_t)row * k + j] == e) visited = 1;
+                }
+                if (!visited) continue;
+                float *u = utility + ((int64_t)b * E + e) * S;
+                for (int i = 0; i < n; ++i) {
+                    double a = 0.0;
+                    for (int h = 0; h < Hq; ++h) {
+                        const int row = b * route_rows_per_seq + (route_rows_per_seq == 1 ? 0 : h);
+                        for (int j = 0; j < k; ++j)
+                            if (topk_idx[(int64_t)row * k + j] == e)
+                                a += pbuf[(((int64_t)b * Hq + h) * k + j) * S + i];
+                    }
+                    u[i] = (float)(decay * (double)u[i] + a);
+                }
+            }
+        }
+    }
+    if (!prob) free(pbuf);
+    return 0;
+}
+
+/* ------------------------------------------------------------------ evict */
+/* Algorithm 1 scheduling step, Section 3.4: a shard holding n > capacity entries keeps
+ * the `capacity` entries that come first when ordered by (utility descending, slot
+ * ascending) - a full sort - and evicts the rest, reported in ascending slot order.
+ * compact != 0 moves the kept rows (K, V, utility) down to slots 0..capacity-1 in
+ * ascending original-slot order.  n becomes capacity.                                 */
+typedef struct { float u; int slot; } evict_key;
+
+static int evict_cmp(const void *a, const void *b) {
+    const evict_key *x = a, *y = b;
+    if (x->u > y->u) return -1;
+    if (x->u < y->u) return 1;
+    return (x->slot > y->slot) - (x->slot < y->slot);
+}
+
+static int int_cmp(const void *a, const void *b) {
+    int x = *(const int *)a, y = *(const int *)b;
+    return (x > y) - (x < y);
+}
+
+int pikv_oracle_evict(int B, int E, int S, int Hkv, int width, int dtype, int64_t stride_h,
+                      int64_t stride_s, float *utility, int32_t *n_valid, int capacity,
+                      const int32_t *shard_mask, int32_t *evicted_idx, int32_t *evicted_cnt,
+                      int max_evict, int compact, void *const *K_shards,
+                      void *const *V_shards) {
+    if (capacity < 0 || max_evict < 0) return -1;
+    evict_key *key = malloc(sizeof(evict_key) * (size_t)S);
+    int *gone = malloc(sizeof(int) * (size_t)S);
+    char *is_gone = malloc((size_t)S);
+    if (!key || !gone || !is_gone) { free(key); free(gone); free(is_gone); return -2; }
+    const size_t es = elem_size(dtype);
+    int rc = 0;
+    for (int b = 0; b < B && !rc; ++b) {
+        for (int e = 0; e < E; ++e) {
+            const int64_t be = (int64_t)b * E + e;
+            evicted_cnt[be] = 0;
+            if (shard_mask && !shard_mask[be]) continue;
+            const int n = n_valid[be];
+            if (n <= capacity) continue;
+            const int ngone = n - capacity;
+            if (ngone > max_evict) { rc = -3; break; }
+            float *u = utility + be * S;
+            for (int i = 0; i < n; ++i) { key[i].u = u[i]; key[i].slot = i; }
+            qsort(key, (size_t)n, sizeof(evict_key), evict_cmp);
+            for (int i = 0; i < ngone; ++i) gone[i] = key[capacity + i].slot;
+            qsort(gone, (size_t)ngone, sizeof(int), int_cmp);
+            for (int i = 0; i < ngone; ++i) evicted_idx[be * max_evict + i] = gone[i];
+            evicted_cnt[be] = ngone;
+            if (compact) {
+                memset(is_gone, 0, (size_t)n);
+                for (int i = 0; i < ngone; ++i) is_gone[gone[i]] = 1;
+                int dst = 0;
+                for (int src = 0; src < n; ++src) {
+                    if (is_gone[src]) continue;
+                    if (dst != src) {
+                        u[dst] = u[src];
+                        for (int hk = 0; hk < Hkv; ++hk) {
+                            const int64_t so = ((int64_t)hk * stride_h + (int64_t)src * stride_s);
+                            const int64_t dk = ((int64_t)hk * stride_h + (int64_t)dst * stride_s);
+                            if (K_shards)
+                                memmove((char *)K_shards[be] + dk * es,
+                                        (char *)K_shards[be] + so * es, (size_t)width * es);
+                            if (V_shards)
+                                memmove((char *)V_shards[be] + dk * es,
+                                        (char *)V_shards[be] + so * es, (size_t)width * es);
+                        }
+                    }
+                    ++dst;
+                }
+            }
+            n_valid[be] = capacity;
+        }
+    }
+    free(key); free(gone); free(is_gone);
+    return rc;
+}
+
+/* ----------------------------------------------------------------- append */
+/* Algorithm 1 Insert / Section 3.1 storage invariants: each selected shard of sequence
+ * b receives the new entry (one row per kv head) in O(1): into the slot an eviction
+ * just freed (reuse_cnt > 0: first listed slot), otherwise at slot n.  The entry's
+ * utility starts at 0 and the shard's entry count grows by one.                       */
+int pikv_oracle_append(int B, int E, int S, int Hkv, int width, int dtype, int64_t stride_h,
+                       int64_t stride_s, const void *K_new, const void *V_new,
+                       const int32_t *topk_idx, int k, const int32_t *reuse_idx,
+                       const int32_t *reuse_cnt, int max_evict, void *const *K_shards,
+                       void *const *V_shards, float *utility, int32_t *n_valid) {
+    const size_t es = elem_size(dtype);
+    for (int b = 0; b < B; ++b) {
+        for (int j = 0; j < k; ++j) {
+            const int e = topk_idx[(int64_t)b * k + j];
+            const int64_t be = (int64_t)b * E + e;
+            int slot = n_valid[be];
+            if (reuse_cnt && reuse_cnt[be] > 0) slot = reuse_idx[be * max_evict];
+            if (slot < 0 || slot >= S || n_valid[be] >= S) return -3;
+            for (int hk = 0; hk < Hkv; ++hk) {
+                const int64_t dst = (int64_t)hk * stride_h + (int64_t)slot * stride_s;
+                const int64_t src = ((int64_t)b * Hkv + hk) * width;
+                memcpy((char *)K_shards[be] + dst * es, (const char *)K_new + src * es,
+                       (size_t)width * es);
+                memcpy((char *)V_shards[be] + dst * es, (const char *)V_new + src * es,
+                       (size_t)width * es);
+            }
+            utility[be * S + slot] = 0.0f;
+            n_valid[be] += 1;
+        }
+    }
+    return 0;
+}

@@ -1,0 +1,198 @@
+"""ctypes front-end of the CPU oracle (``pikv_oracle.c``).
+
+Test infrastructure only: the test-suite, the smoke check and the benchmark's
+``cpu_baseline`` leg call it; the product package never does.  Arrays are numpy, on the
+host; bfloat16 data travels as ``uint16`` bit patterns (``dtype='bf16'``).
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "pikv_oracle.c")
+_LIB = os.path.join(_HERE, "libpikv_oracle.so")
+
+F32, BF16 = 0, 1
+COMBINE_LSE, COMBINE_LOCAL = 0, 1
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (plain C, -O2, OpenMP over independent units)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        tmp = _LIB + ".tmp%d" % os.getpid()
+        subprocess.check_call(
+            ["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
+             "-o", tmp, _SRC, "-lm"])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        # PIKV_ORACLE_LIB lets the mutation test load a deliberately broken build
+        _lib = C.CDLL(os.environ.get("PIKV_ORACLE_LIB") or build())
+        for name in ("pikv_oracle_route", "pikv_oracle_attend", "pikv_oracle_evict",
+                     "pikv_oracle_append"):
+            getattr(_lib, name).restype = C.c_int
+    return _lib
+
+
+def _dt(dtype) -> int:
+    return {"f32": F32, "bf16": BF16, F32: F32, BF16: BF16}[dtype]
+
+
+def _np_dtype(dtype):
+    return np.float32 if _dt(dtype) == F32 else np.uint16
+
+
+def _ptr(a):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+def _chk(a, dtype, name):
+    if a is None:
+        return None
+    if not isinstance(a, np.ndarray) or a.dtype != dtype or not a.flags["C_CONTIGUOUS"]:
+        raise TypeError("%s must be a C-contiguous numpy array of %s" % (name, dtype))
+    return a
+
+
+def _ptr_table(shards):
+    """list of numpy arrays -> (ctypes void* array, keep-alive)."""
+    arr = (C.c_void_p * len(shards))()
+    for i, s in enumerate(shards):
+        arr[i] = s.ctypes.data
+    return arr
+
+
+def route(x, W_r, k, bias=None, dtype="f32", want_logits=False):
+    """x [rows,d_r], W_r [d_r,E] -> idx int32 [rows,k], gates f32 [rows,k], probs f32 [rows,E]."""
+    nd = _np_dtype(dtype)
+    x = _chk(x, nd, "x")
+    W_r = _chk(W_r, nd, "W_r")
+    rows, d_r = x.shape
+    E = W_r.shape[1]
+    assert W_r.shape[0] == d_r
+    bias = _chk(bias, np.float32, "bias")
+    idx = np.zeros((rows, k), np.int32)
+    gates = np.zeros((rows, k), np.float32)
+    probs = np.zeros((rows, E), np.float32)
+    logits = np.zeros((rows, E), np.float64)
+    rc = lib().pikv_oracle_route(_ptr(x), _ptr(W_r), _ptr(bias), rows, d_r, E, k, _dt(dtype),
+                                 _ptr(idx), _ptr(gates), _ptr(probs), _ptr(logits))
+    if rc:
+        raise ValueError("pikv_oracle_route failed: %d" % rc)
+    if want_logits:
+        return idx, gates, probs, logits
+    return idx, gates, probs
+
+
+def attend(q, K_shards, V_shards, n_valid, topk_idx, gates, *, Hkv, E, S, dtype="f32",
+           rank=0, U_K=None, U_V=None, combine=COMBINE_LSE, scale=0.0, stride_h=None,
+           stride_s=None, utility=None, decay=1.0, want_prob=False):
+    """One decode step of routed attention (+ optional in-place utility update).
+
+    q [B,Hq,D]; K_shards/V_shards: list of B*E arrays, each [Hkv,S,w] (w = D or rank);
+    n_valid int32 [B,E]; topk_idx int32 [R,k] with R = B (per-token) or B*Hq (per-head);
+    gates f32 [R,k] or None.  Returns dict(y, row_max, row_norm[, prob]).
+    """
+    nd = _np_dtype(dtype)
+    q = _chk(q, nd, "q")
+    B, Hq, D = q.shape
+    w = rank if rank else D
+    if stride_s is None:
+        stride_s = w
+    if stride_h is None:
+        stride_h = S * stride_s
+    assert len(K_shards) == B * E and len(V_shards) == B * E
+    for s in list(K_shards) + list(V_shards):
+        _chk(s, nd, "shard")
+    n_valid = _chk(n_valid, np.int32, "n_valid")
+    topk_idx = _chk(topk_idx, np.int32, "topk_idx")
+    gates = _chk(gates, np.float32, "gates")
+    R, k = topk_idx.shape
+    assert R in (B, B * Hq)
+    rr = 1 if R == B else Hq
+    U_K = _chk(U_K, nd, "U_K")
+    U_V = _chk(U_V, nd, "U_V")
+    utility = _chk(utility, np.float32, "utility")
+    y = np.zeros((B, Hq, D), np.float32)
+    row_max = np.zeros((B, Hq), np.float32)
+    row_norm = np.zeros((B, Hq), np.float32)
+    prob = np.zeros((B, Hq, k, S), np.float64) if want_prob else None
+    kt, vt = _ptr_table(K_shards), _ptr_table(V_shards)
+    rc = lib().pikv_oracle_attend(
+        B, Hq, Hkv, D, E, S, rank, _dt(dtype), C.c_int64(stride_h), C.c_int64(stride_s), rr,
+        _ptr(q), kt, vt, _ptr(U_K), _ptr(U_V), _ptr(n_valid), _ptr(topk_idx), _ptr(gates), k,
+        combine, C.c_double(scale), _ptr(y), _ptr(row_max), _ptr(row_norm), _ptr(prob),
+        C.c_double(decay), _ptr(utility))
+    if rc:
+        raise ValueError("pikv_oracle_attend failed: %d" % rc)
+    out = {"y": y, "row_max": row_max, "row_norm": row_norm}
+    if want_prob:
+        out["prob"] = prob
+    return out
+
+
+def evict(utility, n_valid, capacity, *, shard_mask=None, max_evict=None, compact=False,
+          K_shards=None, V_shards=None, Hkv=0, width=0, dtype="f32", stride_h=None,
+          stride_s=None):
+    """In place on utility / n_valid (/ shards when compact).  Returns (evicted_idx, evicted_cnt)."""
+    utility = _chk(utility, np.float32, "utility")
+    n_valid = _chk(n_valid, np.int32, "n_valid")
+    B, E, S = utility.shape
+    shard_mask = _chk(shard_mask, np.int32, "shard_mask")
+    if max_evict is None:
+        max_evict = max(0, S - capacity)
+    if stride_s is None:
+        stride_s = width
+    if stride_h is None:
+        stride_h = S * stride_s
+    idx = np.full((B, E, max_evict), -1, np.int32)
+    cnt = np.zeros((B, E), np.int32)
+    kt = _ptr_table(K_shards) if K_shards is not None else None
+    vt = _ptr_table(V_shards) if V_shards is not None else None
+    rc = lib().pikv_oracle_evict(B, E, S, Hkv, width, _dt(dtype), C.c_int64(stride_h),
+                                 C.c_int64(stride_s), _ptr(utility), _ptr(n_valid), capacity,
+                                 _ptr(shard_mask), _ptr(idx), _ptr(cnt), max_evict,
+                                 1 if compact else 0, kt, vt)
+    if rc:
+        raise ValueError("pikv_oracle_evict failed: %d" % rc)
+    return idx, cnt
+
+
+def append(K_new, V_new, topk_idx, K_shards, V_shards, utility, n_valid, *, dtype="f32",
+           reuse_idx=None, reuse_cnt=None, stride_h=None, stride_s=None):
+    """In place on the shards, utility and n_valid.  K_new/V_new [B,Hkv,w]; topk_idx [B,k]."""
+    nd = _np_dtype(dtype)
+    K_new = _chk(K_new, nd, "K_new")
+    V_new = _chk(V_new, nd, "V_new")
+    B, Hkv, width = K_new.shape
+    _, E, S = utility.shape
+    topk_idx = _chk(topk_idx, np.int32, "topk_idx")
+    k = topk_idx.shape[1]
+    if stride_s is None:
+        stride_s = width
+    if stride_h is None:
+        stride_h = S * stride_s
+    max_evict = 0
+    if reuse_idx is not None:
+        reuse_idx = _chk(reuse_idx, np.int32, "reuse_idx")
+        reuse_cnt = _chk(reuse_cnt, np.int32, "reuse_cnt")
+        max_evict = reuse_idx.shape[2]
+    kt, vt = _ptr_table(K_shards), _ptr_table(V_shards)
+    rc = lib().pikv_oracle_append(B, E, S, Hkv, width, _dt(dtype), C.c_int64(stride_h),
+                                  C.c_int64(stride_s), _ptr(K_new), _ptr(V_new), _ptr(topk_idx),
+                                  k, _ptr(reuse_idx), _ptr(reuse_cnt), max_evict, kt, vt,
+                                  _ptr(_chk(utility, np.float32, "utility")),
+                                  _ptr(_chk(n_valid, np.int32, "n_valid")))
+    if rc:
+        raise ValueError("pikv_oracle_append failed: %d" % rc)
