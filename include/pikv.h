@@ -1,0 +1,178 @@
+/*
+ * pikv.h - C ABI of the MI355X (gfx950) implementation of PiKV's decode-step hot path
+ * (arxiv 2508.06526): route -> attend over the top-k expert KV shards -> combine ->
+ * update per-entry utility -> evict / append.
+ *
+ * General conventions
+ *   - Every pointer argument is a DEVICE pointer unless the comment says "host".  The
+ *     descriptor (pikv_desc) is a host struct passed by const pointer.
+ *   - The caller owns every buffer.  The library allocates nothing, frees nothing and
+ *     keeps no state between calls; scratch space is passed in as `workspace`.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only
+ *     enqueue work and return; they never synchronise.
+ *   - Return value: a pikv_status.  Argument errors are detected on the host before
+ *     anything is launched and leave all outputs untouched; HIP launch failures map to
+ *     PIKV_ERR_HIP.  Nothing is printed, nothing aborts.
+ *   - Layout of one expert shard (one (sequence b, expert e) pair): rows
+ *         shard[h' * stride_h + slot * stride_s + 0 .. width)
+ *     for kv head h' in [0,Hkv), slot in [0,S); width = D (dense) or rank (codes); the
+ *     last dimension is contiguous; strides are in elements; every row must start on a
+ *     16-byte boundary.  K_shards / V_shards are device arrays of B*E device pointers,
+ *     entry b*E+e.  The valid entries of a shard are the prefix 0 .. n_valid[b][e]-1.
+ *   - Outputs that are probabilities, gates, utilities or attention results are float32
+ *     whatever the storage dtype.
+ *   - Routing decisions come in rows: row = b (route_rows_per_seq == 1, one decision per
+ *     token) or row = b*Hq + h (route_rows_per_seq == Hq, one decision per token and head).
+ */
+#ifndef PIKV_H
+#define PIKV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    PIKV_OK = 0,
+    PIKV_ERR_INVALID = -1,      /* bad argument (null pointer, size out of range, ...)   */
+    PIKV_ERR_UNSUPPORTED = -2,  /* valid in principle, no kernel for this shape          */
+    PIKV_ERR_WORKSPACE = -3,    /* workspace_bytes smaller than pikv_attn_workspace_bytes */
+    PIKV_ERR_HIP = -4           /* the HIP runtime refused a launch                      */
+} pikv_status;
+
+typedef enum { PIKV_F32 = 0, PIKV_BF16 = 1 } pikv_dtype;
+
+/* How the per-shard attention results are merged (Algorithm 1, f_attn over C[g_t], with
+ * the router's gate weights supplied by the caller):
+ *   LSE   - one softmax over the union of the selected shards, each entry weighted by its
+ *           shard's gate: p_i = g_e exp(s_i) / sum.  With gates == NULL this is the paper's
+ *           0/1 mask (Section 3.2) and k == E reproduces dense attention.
+ *   LOCAL - softmax inside each shard, outputs mixed by the gates renormalised over the
+ *           non-empty selected shards: y = sum_e g_e o_e / sum_e g_e.                      */
+typedef enum { PIKV_COMBINE_LSE = 0, PIKV_COMBINE_LOCAL = 1 } pikv_combine;
+
+/* Geometry of one layer's expert-sharded cache (Section 3.1: E shards of capacity S per
+ * sequence).  Plain data, host memory.                                                    */
+typedef struct pikv_desc {
+    int32_t B;        /* sequences (decode streams)                                        */
+    int32_t Hq;       /* query heads, <= 256                                               */
+    int32_t Hkv;      /* kv heads, Hq % Hkv == 0; query head h reads kv head h / (Hq/Hkv)  */
+    int32_t D;        /* head dimension: 16, 32, 64 or 128                                 */
+    int32_t E;        /* expert shards per sequence, 1..64                                 */
+    int32_t S;        /* slot capacity of every shard                                      */
+    int32_t rank;     /* 0: rows hold D values; r in {16,32,64}: rows hold rank-r codes    */
+    int32_t dtype;    /* pikv_dtype of q, K/V (or codes), U_K/U_V                          */
+    int64_t stride_h; /* elements between kv heads inside a shard buffer                   */
+    int64_t stride_s; /* elements between slots (>= width, multiple of 16 bytes)           */
+    int32_t route_rows_per_seq; /* 1 or Hq                                                 */
+    int32_t reserved; /* must be 0                                                         */
+} pikv_desc;
+
+/* Section 3.2, Table 1 "TopK softmax" router (with the table's additive per-expert
+ * penalty as `bias`): logits = x W_r + bias, p = softmax over the E experts, the mask has
+ * ones at the k largest logits.
+ *   x      [rows, d_r]  dtype      query vectors being routed
+ *   W_r    [d_r, E]     dtype      router weights, row-major
+ *   bias   [E] float32 or NULL
+ *   topk_idx [rows, k] int32  out  selected experts, descending logit; equal logits:
+ *                                  lower expert index first; NaN logits rank as -inf
+ *   gates  [rows, k] float32  out  p restricted to the selection, renormalised to sum 1
+ *   probs  [rows, E] float32  out  full softmax, or NULL
+ * Errors: INVALID for null x/W_r/topk_idx/gates, rows < 0, d_r < 1, E not in 1..64,
+ * k not in 1..E, unknown dtype.  rows == 0 is a no-op.                                     */
+int pikv_route(const void *x, const void *W_r, const float *bias, int32_t rows, int32_t d_r,
+               int32_t E, int32_t k, int32_t dtype, int32_t *topk_idx, float *gates,
+               float *probs, void *stream);
+
+/* Bytes of scratch pikv_sharded_attn needs for this geometry and k (host computation;
+ * 0 if the descriptor is invalid).  The workspace must be 256-byte aligned.              */
+size_t pikv_attn_workspace_bytes(const pikv_desc *desc, int32_t k);
+
+/* Algorithm 1, y_t = f_attn(q_t, C[g_t]): attention of each query head over the valid
+ * entries of its selected shards only (Section 3.2: the fetch is 2*B*L*h*k, not ...*E).
+ * Scores s_i = scale * <q_h, K_i>.  With rank > 0 the stored rows are codes and the
+ * entries are K_i = code_i U_K[h'], V_i = code_i U_V[h'] (Section 3.3, decoder of the
+ * rank-r compressor, fused into the kernel: the codes are what is streamed from HBM).
+ *   q        [B,Hq,D] dtype
+ *   U_K,U_V  [Hkv,rank,D] dtype   (rank > 0 only, else ignored)
+ *   n_valid  [B,E] int32
+ *   topk_idx [rows,k] int32       selected experts per routing row (distinct within a row)
+ *   gates    [rows,k] float32 or NULL (NULL: every gate is 1)
+ *   combine  pikv_combine
+ *   scale    <= 0 selects 1/sqrt(D)
+ *   y        [B,Hq,D] float32 out  (0 where every selected shard is empty)
+ *   row_max  [B,Hq] float32 out or NULL: max score over the non-empty selected shards
+ *   row_norm [B,Hq] float32 out or NULL: the normaliser y was divided by
+ *                (LSE: sum_e g_e sum_i exp(s_i - row_max); LOCAL: sum_e g_e)
+ *   scores   [B,Hq,k,S] float32 out or NULL: raw s_i of entry i of the j-th selected shard
+ *   slot_coef [B,Hq,k,2] float32 out or NULL: (shift, coef) such that the attention
+ *                probability of entry i is coef * exp(s_i - shift); coef = 0 for an empty
+ *                shard.  scores + slot_coef are what pikv_update_utility consumes.
+ * Errors: INVALID / UNSUPPORTED per the descriptor limits above, k not in 1..E, null
+ * required pointer; WORKSPACE if workspace_bytes is too small.  B == 0 is a no-op.         */
+int pikv_sharded_attn(const pikv_desc *desc, const void *q, const void *const *K_shards,
+                      const void *const *V_shards, const void *U_K, const void *U_V,
+                      const int32_t *n_valid, const int32_t *topk_idx, const float *gates,
+                      int32_t k, int32_t combine, float scale, float *y, float *row_max,
+                      float *row_norm, float *scores, float *slot_coef, void *workspace,
+                      size_t workspace_bytes, void *stream);
+
+/* Section 3.4, Table 3 row H2O (u_i = a_i, the attention an entry received), kept as a
+ * running score: for every shard that at least one query head selected this step and
+ * every valid slot i:  u_i <- decay * u_i + sum over those heads of p_{h,i}.
+ * decay == 1 accumulates; decay < 1 gives the exponentially decayed score.  Shards nobody
+ * selected are not touched.  `scores`, `slot_coef`, `topk_idx`, `k` are those of the
+ * pikv_sharded_attn call of the same step.
+ *   utility [B,E,S] float32, in place.
+ * Errors: INVALID for null pointers, k out of range, decay < 0 or not finite.              */
+int pikv_update_utility(const pikv_desc *desc, const float *scores, const float *slot_coef,
+                        const int32_t *n_valid, const int32_t *topk_idx, int32_t k,
+                        float decay, float *utility, void *stream);
+
+/* Algorithm 1, C <- S(C, q_t) under bounded memory (Section 3.4): every processed shard
+ * holding n > capacity entries keeps the `capacity` entries that come first in the order
+ * (utility descending, slot ascending) and evicts the other n - capacity.
+ *   sel_idx  [B,sel_k] int32 or NULL: process only the shards listed for each sequence
+ *            (e.g. this step's topk_idx under per-token routing); NULL: all B*E shards
+ *   evicted_idx [B,E,max_evict] int32 out: evicted slots, ascending
+ *   evicted_cnt [B,E] int32 out: number evicted (0 for shards skipped or within capacity;
+ *            -1, and the shard is left untouched, if n - capacity > max_evict)
+ *   compact  != 0: move the kept rows of K, V (all kv heads) and utility down to slots
+ *            0..capacity-1 in ascending original order (K_shards/V_shards required).
+ *            == 0: rows stay where they are; the evicted slots are holes the caller must
+ *            refill with pikv_append (reuse_idx) before the next attention call.
+ *   n_valid  [B,E] int32, in place: becomes capacity for shards that evicted.
+ * Errors: INVALID for null utility/n_valid/evicted_*, capacity < 0, max_evict < 1,
+ * sel_k not in 1..E when sel_idx is given, compact without shard tables.                   */
+int pikv_evict(const pikv_desc *desc, float *utility, int32_t *n_valid, int32_t capacity,
+               const int32_t *sel_idx, int32_t sel_k, int32_t *evicted_idx,
+               int32_t *evicted_cnt, int32_t max_evict, int32_t compact,
+               void *const *K_shards, void *const *V_shards, void *stream);
+
+/* Algorithm 1, Insert into C[e][s]; Section 3.1 storage invariants (fixed-capacity buffer,
+ * O(1) insertion, no reallocation): for each sequence b and each expert e = topk_idx[b][j]
+ * the new entry's rows (one per kv head) are written to slot
+ *     reuse_idx[b][e][0]  if reuse_cnt != NULL and reuse_cnt[b][e] > 0 (a slot pikv_evict
+ *                         just freed), else n_valid[b][e];
+ * its utility is set to 0 and n_valid[b][e] grows by one.  A shard that is already full
+ * (n_valid == S) is skipped: the entry is dropped for that shard.
+ *   K_new,V_new [B,Hkv,width] dtype;  topk_idx [B,k] int32 (distinct within a row)
+ *   reuse_idx [B,E,max_evict] int32, reuse_cnt [B,E] int32, or both NULL
+ * Errors: INVALID for null required pointers, k not in 1..E.                               */
+int pikv_append(const pikv_desc *desc, const void *K_new, const void *V_new,
+                const int32_t *topk_idx, int32_t k, const int32_t *reuse_idx,
+                const int32_t *reuse_cnt, int32_t max_evict, void *const *K_shards,
+                void *const *V_shards, float *utility, int32_t *n_valid, void *stream);
+
+/* Static description of a status code (host string, never NULL).                          */
+const char *pikv_strerror(int status);
+
+/* Library version: major*10000 + minor*100 + patch.                                        */
+int pikv_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PIKV_H */

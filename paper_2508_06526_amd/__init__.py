@@ -1,0 +1,10 @@
+"""MI355X (gfx950) implementation of PiKV's routed sharded-KV decode path.
+
+The work is done by hand-written HIP kernels in ``libpikv.so`` behind the C ABI declared
+in ``include/pikv.h``; this package is the thin ctypes binding (argument marshalling only).
+There is no CPU or eager fallback: if the library is missing, calls raise.
+"""
+from .binding import (  # noqa: F401
+    COMBINE_LOCAL, COMBINE_LSE, PikvDesc, PikvError, library_path, load_library, make_desc,
+    pikv_append, pikv_attn_workspace_bytes, pikv_evict, pikv_route, pikv_sharded_attn,
+    pikv_strerror, pikv_update_utility, pikv_version, shard_table)

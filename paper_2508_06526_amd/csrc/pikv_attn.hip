@@ -1,0 +1,521 @@
+// Routed attention over the selected expert shards (PiKV Algorithm 1, the f_attn step over
+// C[g_t]; Section 3.2: only the k selected shards are fetched; Section 3.3: rank-r codes are
+// decoded inside the kernel) as a split flash-decode for gfx950:
+//
+//   attn_partial : grid over (sequence, head group, selected shard, split).  Each wave64
+//                  streams whole K rows and V rows with 16-byte lane loads (a wave load is
+//                  1 KiB of consecutive bytes), keeps a running max / sum / output in fp32
+//                  registers and never revisits a byte.  A block of 4 waves merges its
+//                  waves through LDS and writes one (max, sum, acc[width]) partial.
+//   attn_combine : one block per (sequence, query head) merges the k * nsplit partials with
+//                  the router gates, applies the value decoder for rank-r codes, and emits
+//                  y, the row statistics and the (shift, coef) pairs the utility pass needs.
+//
+// Low-rank entries are never materialised: s_i = scale * <U_K q, code_i> and
+// y = (sum_i p_i code_i) U_V, so the streamed bytes are the codes and the decode costs
+// O(rank) per entry (the paper's T_decode is linear in the compressed width, eq. 2).
+#include "pikv_common.h"
+
+#include <math.h>
+
+namespace pikv {
+
+namespace {
+
+constexpr int kLoadsPerTile = 8;   // 16-byte loads each lane keeps in flight per K (or V) tile
+constexpr int kWavesPerBlock = 4;
+
+struct AttnParams {
+    const void *q;
+    const void *const *K;
+    const void *const *V;
+    const void *U_K;
+    const int32_t *n_valid;
+    const int32_t *topk;
+    float *part_acc;
+    float *part_ml;
+    float *scores;
+    int B, Hq, G, D, E, S, k, rr, rank;
+    int64_t stride_h, stride_s;
+    int nsplit, chunk;
+    float scale;
+};
+
+template <typename T, int W, int GB>
+__global__ __launch_bounds__(kWavesPerBlock *kWave) void attn_partial(AttnParams p) {
+    constexpr int EPL = Pack16<T>::N;        // elements per lane per load
+    constexpr int LPR = W / EPL;             // lanes covering one row
+    constexpr int RPL = kWave / LPR;         // rows covered by one wave load
+    constexpr int NL = kLoadsPerTile;
+    constexpr int TILE = RPL * NL;           // rows per wave iteration
+    constexpr int CB = ilog2(LPR);           // lane bits that index the column chunk
+    static_assert(LPR >= 1 && LPR <= 32 && (LPR & (LPR - 1)) == 0, "row must be 16..512 bytes");
+
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1);
+    const int wave = tid >> 6;
+    const int c = lane & (LPR - 1);
+    const int r = lane >> CB;
+
+    int bid = blockIdx.x;
+    const int split = bid % p.nsplit;
+    bid /= p.nsplit;
+    const int j = bid % p.k;
+    bid /= p.k;
+    const int hgroups = p.Hq / GB;
+    const int hg = bid % hgroups;
+    const int b = bid / hgroups;
+    const int h0 = hg * GB;
+    const int hk = h0 / p.G;
+    const int route_row = b * p.rr + (p.rr == 1 ? 0 : h0);
+    const int e = p.topk[(int64_t)route_row * p.k + j];
+    const int n = p.n_valid[(int64_t)b * p.E + e];
+    const int r0 = split * p.chunk;
+    const int r1 = min(n, r0 + p.chunk);
+
+    __shared__ float q_s[GB][W];
+    __shared__ float sm_acc[kWavesPerBlock][GB][W];
+    __shared__ float sm_m[kWavesPerBlock][GB];
+    __shared__ float sm_l[kWavesPerBlock][GB];
+
+    const int64_t part_base = (((int64_t)b * p.Hq + h0) * p.k + j) * p.nsplit + split;
+    const int64_t part_head_stride = (int64_t)p.k * p.nsplit;
+
+    if (r0 >= r1) {  // nothing valid in this split (short or empty shard)
+        for (int idx = tid; idx < GB * W; idx += blockDim.x) {
+            const int g = idx / W, d = idx - g * W;
+            p.part_acc[(part_base + g * part_head_stride) * W + d] = 0.0f;
+            if (d == 0) {
+                p.part_ml[(part_base + g * part_head_stride) * 2 + 0] = -INFINITY;
+                p.part_ml[(part_base + g * part_head_stride) * 2 + 1] = 0.0f;
+            }
+        }
+        return;
+    }
+
+    // Stage the (scaled) query in LDS; for rank-r codes it is the projected query U_K q.
+    const T *qp = static_cast<const T *>(p.q) + ((int64_t)b * p.Hq + h0) * p.D;
+    if (p.rank == 0) {
+        for (int idx = tid; idx < GB * W; idx += blockDim.x)
+            q_s[idx / W][idx % W] = p.scale * load_scalar<T>(qp, idx);   // W == D here
+    } else {
+        const T *U = static_cast<const T *>(p.U_K) + (int64_t)hk * p.rank * p.D;
+        for (int idx = tid; idx < GB * W; idx += blockDim.x) {
+            const int g = idx / W, col = idx - g * W;
+            float a = 0.0f;
+            for (int d = 0; d < p.D; ++d)
+                a = fmaf(load_scalar<T>(U, (int64_t)col * p.D + d),
+                         load_scalar<T>(qp, (int64_t)g * p.D + d), a);
+            q_s[g][col] = p.scale * a;
+        }
+    }
+    __syncthreads();
+
+    float qf[GB][EPL];
+#pragma unroll
+    for (int g = 0; g < GB; ++g)
+#pragma unroll
+        for (int i = 0; i < EPL; ++i) qf[g][i] = q_s[g][c * EPL + i];
+
+    float m[GB], l[GB], acc[GB][EPL];
+#pragma unroll
+    for (int g = 0; g < GB; ++g) {
+        m[g] = -INFINITY;
+        l[g] = 0.0f;
+#pragma unroll
+        for (int i = 0; i < EPL; ++i) acc[g][i] = 0.0f;
+    }
+
+    const int64_t shard = (int64_t)b * p.E + e;
+    const T *Kb = static_cast<const T *>(p.K[shard]) + (int64_t)hk * p.stride_h + c * EPL;
+    const T *Vb = static_cast<const T *>(p.V[shard]) + (int64_t)hk * p.stride_h + c * EPL;
+
+    for (int t0 = r0 + wave * TILE; t0 < r1; t0 += kWavesPerBlock * TILE) {
+        uint4 kr[NL], vr[NL];
+#pragma unroll
+        for (int t = 0; t < NL; ++t) {
+            const int row = t0 + t * RPL + r;
+            kr[t] = row < r1 ? load16(Kb + (int64_t)row * p.stride_s) : make_uint4(0, 0, 0, 0);
+        }
+#pragma unroll
+        for (int t = 0; t < NL; ++t) {
+            const int row = t0 + t * RPL + r;
+            vr[t] = row < r1 ? load16(Vb + (int64_t)row * p.stride_s) : make_uint4(0, 0, 0, 0);
+        }
+
+        // scores: each lane's partial dot over its EPL columns, summed over the row's lanes
+        float s[NL][GB];
+#pragma unroll
+        for (int t = 0; t < NL; ++t) {
+            float kf[EPL];
+            Pack16<T>::widen(kr[t], kf);
+            const bool valid = (t0 + t * RPL + r) < r1;
+#pragma unroll
+            for (int g = 0; g < GB; ++g) {
+                float d = 0.0f;
+#pragma unroll
+                for (int i = 0; i < EPL; ++i) d = fmaf(qf[g][i], kf[i], d);
+                d = bits_sum<0, CB>(d);
+                s[t][g] = valid ? d : -INFINITY;
+            }
+        }
+
+        if (p.scores != nullptr) {  // raw scores for the utility pass, one row per lane
+#pragma unroll
+            for (int g = 0; g < GB; ++g) {
+                float *dst = p.scores + (((int64_t)b * p.Hq + h0 + g) * p.k + j) * p.S;
+#pragma unroll
+                for (int u = 0; u < NL; u += LPR) {
+                    float v = s[u][g];
+#pragma unroll
+                    for (int t = 1; t < LPR && u + t < NL; ++t) v = (c == t) ? s[u + t][g] : v;
+                    const int row = t0 + (u + c) * RPL + r;
+                    if (u + c < NL && row < r1) dst[row] = v;
+                }
+            }
+        }
+
+        // online softmax update (wave-uniform running max per head)
+#pragma unroll
+        for (int g = 0; g < GB; ++g) {
+            float tm = s[0][g];
+#pragma unroll
+            for (int t = 1; t < NL; ++t) tm = fmaxf(tm, s[t][g]);
+            tm = bits_max<CB, 6>(tm);
+            const float mn = fmaxf(m[g], tm);
+            const float corr = __expf(m[g] - mn);
+            m[g] = mn;
+            l[g] *= corr;
+#pragma unroll
+            for (int i = 0; i < EPL; ++i) acc[g][i] *= corr;
+#pragma unroll
+            for (int t = 0; t < NL; ++t) {
+                const float pt = __expf(s[t][g] - mn);
+                s[t][g] = pt;
+                l[g] += pt;
+            }
+        }
+
+        // acc += p * V rows
+#pragma unroll
+        for (int t = 0; t < NL; ++t) {
+            float vf[EPL];
+            Pack16<T>::widen(vr[t], vf);
+#pragma unroll
+            for (int g = 0; g < GB; ++g)
+#pragma unroll
+                for (int i = 0; i < EPL; ++i) acc[g][i] = fmaf(s[t][g], vf[i], acc[g][i]);
+        }
+    }
+
+    // merge the row groups of the wave (same column chunk c, different r) ...
+#pragma unroll
+    for (int off = LPR; off < kWave; off <<= 1) {
+#pragma unroll
+        for (int g = 0; g < GB; ++g) {
+            l[g] += __shfl_xor(l[g], off, kWave);
+#pragma unroll
+            for (int i = 0; i < EPL; ++i) acc[g][i] += __shfl_xor(acc[g][i], off, kWave);
+        }
+    }
+    if (r == 0) {
+#pragma unroll
+        for (int g = 0; g < GB; ++g)
+#pragma unroll
+            for (int i = 0; i < EPL; ++i) sm_acc[wave][g][c * EPL + i] = acc[g][i];
+    }
+    if (lane == 0) {
+#pragma unroll
+        for (int g = 0; g < GB; ++g) {
+            sm_m[wave][g] = m[g];
+            sm_l[wave][g] = l[g];
+        }
+    }
+    __syncthreads();
+
+    // ... then the waves of the block, and write the block's partial.
+    for (int idx = tid; idx < GB * W; idx += blockDim.x) {
+        const int g = idx / W, d = idx - g * W;
+        float M = sm_m[0][g];
+#pragma unroll
+        for (int w = 1; w < kWavesPerBlock; ++w) M = fmaxf(M, sm_m[w][g]);
+        float a = 0.0f, L = 0.0f;
+#pragma unroll
+        for (int w = 0; w < kWavesPerBlock; ++w) {
+            const float f = sm_m[w][g] == -INFINITY ? 0.0f : __expf(sm_m[w][g] - M);
+            a = fmaf(sm_acc[w][g][d], f, a);
+            L = fmaf(sm_l[w][g], f, L);
+        }
+        p.part_acc[(part_base + g * part_head_stride) * W + d] = a;
+        if (d == 0) {
+            p.part_ml[(part_base + g * part_head_stride) * 2 + 0] = M;
+            p.part_ml[(part_base + g * part_head_stride) * 2 + 1] = L;
+        }
+    }
+}
+
+struct CombineParams {
+    const float *part_acc;
+    const float *part_ml;
+    const float *gates;
+    const void *U_V;
+    float *y;
+    float *row_max;
+    float *row_norm;
+    float *slot_coef;
+    int Hq, G, D, W, k, rr, rank, nsplit, combine;
+};
+
+constexpr int kCombineThreads = 128;
+constexpr int kMaxPartialsPerHead = 2048;   // k * nsplit
+
+template <typename T>
+__global__ __launch_bounds__(kCombineThreads) void attn_combine(CombineParams p) {
+    const int bh = blockIdx.x;
+    const int b = bh / p.Hq, h = bh - b * p.Hq;
+    const int hk = h / p.G;
+    const int tid = threadIdx.x;
+    const int np = p.k * p.nsplit;
+
+    __shared__ float wt[kMaxPartialsPerHead];   // (max, then weight) of every partial
+    __shared__ float ls[kMaxPartialsPerHead];
+    __shared__ float Mj[64], Zj[64], shard_w[64];
+    __shared__ float ycode[128];
+    __shared__ float stat[2];
+
+    const float *ml = p.part_ml + (int64_t)bh * np * 2;
+    for (int i = tid; i < np; i += blockDim.x) {
+        wt[i] = ml[2 * i];
+        ls[i] = ml[2 * i + 1];
+    }
+    __syncthreads();
+    if (tid < p.k) {  // per selected shard: max and sum over its splits
+        const int j = tid;
+        float M = -INFINITY;
+        for (int s = 0; s < p.nsplit; ++s)
+            if (ls[j * p.nsplit + s] > 0.0f) M = fmaxf(M, wt[j * p.nsplit + s]);
+        float Z = 0.0f;
+        for (int s = 0; s < p.nsplit; ++s)
+            if (ls[j * p.nsplit + s] > 0.0f) Z += ls[j * p.nsplit + s] * __expf(wt[j * p.nsplit + s] - M);
+        Mj[j] = M;
+        Zj[j] = Z;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        const int row = b * p.rr + (p.rr == 1 ? 0 : h);
+        const float *g = p.gates ? p.gates + (int64_t)row * p.k : nullptr;
+        float M = -INFINITY, norm = 0.0f;
+        for (int j = 0; j < p.k; ++j)
+            if (Zj[j] > 0.0f) M = fmaxf(M, Mj[j]);
+        if (p.combine == PIKV_COMBINE_LSE) {
+            for (int j = 0; j < p.k; ++j)
+                if (Zj[j] > 0.0f) norm += (g ? g[j] : 1.0f) * Zj[j] * __expf(Mj[j] - M);
+            for (int j = 0; j < p.k; ++j) {
+                const bool live = Zj[j] > 0.0f;
+                const float gj = g ? g[j] : 1.0f;
+                shard_w[j] = live ? gj * __expf(Mj[j] - M) / norm : 0.0f;
+                if (p.slot_coef) {
+                    p.slot_coef[((int64_t)bh * p.k + j) * 2 + 0] = live ? M : 0.0f;
+                    p.slot_coef[((int64_t)bh * p.k + j) * 2 + 1] = live ? gj / norm : 0.0f;
+                }
+            }
+        } else {
+            for (int j = 0; j < p.k; ++j)
+                if (Zj[j] > 0.0f) norm += g ? g[j] : 1.0f;
+            for (int j = 0; j < p.k; ++j) {
+                const bool live = Zj[j] > 0.0f;
+                const float gj = g ? g[j] : 1.0f;
+                shard_w[j] = live ? gj / (norm * Zj[j]) : 0.0f;
+                if (p.slot_coef) {
+                    p.slot_coef[((int64_t)bh * p.k + j) * 2 + 0] = live ? Mj[j] : 0.0f;
+                    p.slot_coef[((int64_t)bh * p.k + j) * 2 + 1] = shard_w[j];
+                }
+            }
+        }
+        stat[0] = M;
+        stat[1] = norm;
+        if (p.row_max) p.row_max[bh] = M;
+        if (p.row_norm) p.row_norm[bh] = norm;
+    }
+    __syncthreads();
+    // weight of every partial: shard weight * exp(m_split - M_shard)
+    for (int i = tid; i < np; i += blockDim.x) {
+        const int j = i / p.nsplit;
+        wt[i] = ls[i] > 0.0f ? shard_w[j] * __expf(wt[i] - Mj[j]) : 0.0f;
+    }
+    __syncthreads();
+
+    const float *acc = p.part_acc + (int64_t)bh * np * p.W;
+    if (tid < p.W) {
+        float a = 0.0f;
+        for (int i = 0; i < np; ++i)
+            if (wt[i] != 0.0f) a = fmaf(wt[i], acc[(int64_t)i * p.W + tid], a);
+        if (p.rank == 0)
+            p.y[(int64_t)bh * p.D + tid] = a;
+        else
+            ycode[tid] = a;
+    }
+    if (p.rank != 0) {  // value decoder: y = ycode U_V[h']
+        __syncthreads();
+        const T *U = static_cast<const T *>(p.U_V) + (int64_t)hk * p.rank * p.D;
+        for (int d = tid; d < p.D; d += blockDim.x) {
+            float a = 0.0f;
+            for (int cidx = 0; cidx < p.rank; ++cidx)
+                a = fmaf(ycode[cidx], load_scalar<T>(U, (int64_t)cidx * p.D + d), a);
+            p.y[(int64_t)bh * p.D + d] = a;
+        }
+    }
+}
+
+template <typename T, int W>
+int launch_partial_w(int gb, const AttnParams &p, int blocks, hipStream_t st) {
+    const dim3 grid(blocks), block(kWavesPerBlock * kWave);
+    switch (gb) {
+        case 1: hipLaunchKernelGGL((attn_partial<T, W, 1>), grid, block, 0, st, p); break;
+        case 2: hipLaunchKernelGGL((attn_partial<T, W, 2>), grid, block, 0, st, p); break;
+        case 4: hipLaunchKernelGGL((attn_partial<T, W, 4>), grid, block, 0, st, p); break;
+        case 8: hipLaunchKernelGGL((attn_partial<T, W, 8>), grid, block, 0, st, p); break;
+        default: return PIKV_ERR_UNSUPPORTED;
+    }
+    return launch_status();
+}
+
+template <typename T>
+int launch_partial(int width, int gb, const AttnParams &p, int blocks, hipStream_t st) {
+    switch (width) {
+        case 16: return launch_partial_w<T, 16>(gb, p, blocks, st);
+        case 32: return launch_partial_w<T, 32>(gb, p, blocks, st);
+        case 64: return launch_partial_w<T, 64>(gb, p, blocks, st);
+        case 128: return launch_partial_w<T, 128>(gb, p, blocks, st);
+        default: return PIKV_ERR_UNSUPPORTED;
+    }
+}
+
+}  // namespace
+
+int make_attn_plan(const pikv_desc *d, int k, AttnPlan *plan) {
+    const int rc = check_desc(d);
+    if (rc != PIKV_OK) return rc;
+    if (k < 1 || k > d->E) return PIKV_ERR_INVALID;
+    const int W = desc_width(d);
+    const int G = d->Hq / d->Hkv;
+    int gb = 1;
+    if (d->route_rows_per_seq == 1 && (G == 2 || G == 4 || G == 8)) gb = G;
+    const int epl = 16 / elem_bytes(d->dtype);
+    const int lpr = W / epl;
+    if (lpr < 1 || lpr > 32) return PIKV_ERR_UNSUPPORTED;
+    const int tile = (kWave / lpr) * kLoadsPerTile;
+    const int granule = kWavesPerBlock * tile;
+    const int64_t units = (int64_t)d->B * (d->Hq / gb) * k;
+    const int64_t target_blocks = 2048;
+    int64_t nsplit = units > 0 ? (target_blocks + units - 1) / units : 1;
+    const int64_t max_split = (d->S + granule - 1) / granule;
+    if (nsplit > max_split) nsplit = max_split;
+    if (nsplit > kMaxPartialsPerHead / k) nsplit = kMaxPartialsPerHead / k;
+    if (nsplit < 1) nsplit = 1;
+    int chunk = (int)((d->S + nsplit - 1) / nsplit);
+    chunk = (chunk + granule - 1) / granule * granule;
+    nsplit = (d->S + chunk - 1) / chunk;
+    plan->heads_per_block = gb;
+    plan->head_blocks = d->Hq / gb;
+    plan->tile_rows = tile;
+    plan->chunk = chunk;
+    plan->nsplit = (int)nsplit;
+    plan->acc_floats = (size_t)d->B * d->Hq * k * nsplit * W;
+    plan->ml_floats = (size_t)d->B * d->Hq * k * nsplit * 2;
+    return PIKV_OK;
+}
+
+}  // namespace pikv
+
+using namespace pikv;
+
+extern "C" size_t pikv_attn_workspace_bytes(const pikv_desc *desc, int32_t k) {
+    AttnPlan plan;
+    if (make_attn_plan(desc, k, &plan) != PIKV_OK) return 0;
+    const size_t acc = (plan.acc_floats * sizeof(float) + 255) / 256 * 256;
+    const size_t ml = (plan.ml_floats * sizeof(float) + 255) / 256 * 256;
+    return acc + ml + 256;
+}
+
+extern "C" int pikv_sharded_attn(const pikv_desc *desc, const void *q, const void *const *K_shards,
+                                 const void *const *V_shards, const void *U_K, const void *U_V,
+                                 const int32_t *n_valid, const int32_t *topk_idx,
+                                 const float *gates, int32_t k, int32_t combine, float scale,
+                                 float *y, float *row_max, float *row_norm, float *scores,
+                                 float *slot_coef, void *workspace, size_t workspace_bytes,
+                                 void *stream) {
+    AttnPlan plan;
+    const int rc = make_attn_plan(desc, k, &plan);
+    if (rc != PIKV_OK) return rc;
+    if (!q || !K_shards || !V_shards || !n_valid || !topk_idx || !y) return PIKV_ERR_INVALID;
+    if (desc->rank > 0 && (!U_K || !U_V)) return PIKV_ERR_INVALID;
+    if (combine != PIKV_COMBINE_LSE && combine != PIKV_COMBINE_LOCAL) return PIKV_ERR_INVALID;
+    if (!(scale == scale)) return PIKV_ERR_INVALID;
+    if (desc->B == 0) return PIKV_OK;
+    const size_t need = pikv_attn_workspace_bytes(desc, k);
+    if (!workspace || workspace_bytes < need) return PIKV_ERR_WORKSPACE;
+    if (reinterpret_cast<uintptr_t>(workspace) % 256 != 0) return PIKV_ERR_INVALID;
+
+    const int W = desc_width(desc);
+    float *part_acc = static_cast<float *>(workspace);
+    float *part_ml = part_acc + (plan.acc_floats * sizeof(float) + 255) / 256 * 64;
+
+    AttnParams p;
+    p.q = q;
+    p.K = K_shards;
+    p.V = V_shards;
+    p.U_K = U_K;
+    p.n_valid = n_valid;
+    p.topk = topk_idx;
+    p.part_acc = part_acc;
+    p.part_ml = part_ml;
+    p.scores = scores;
+    p.B = desc->B;
+    p.Hq = desc->Hq;
+    p.G = desc->Hq / desc->Hkv;
+    p.D = desc->D;
+    p.E = desc->E;
+    p.S = desc->S;
+    p.k = k;
+    p.rr = desc->route_rows_per_seq;
+    p.rank = desc->rank;
+    p.stride_h = desc->stride_h;
+    p.stride_s = desc->stride_s;
+    p.nsplit = plan.nsplit;
+    p.chunk = plan.chunk;
+    p.scale = scale > 0.0f ? scale : 1.0f / sqrtf((float)desc->D);
+
+    const int64_t blocks64 = (int64_t)desc->B * plan.head_blocks * k * plan.nsplit;
+    if (blocks64 > 0x7fffffff) return PIKV_ERR_UNSUPPORTED;
+    hipStream_t st = as_stream(stream);
+    int lrc = desc->dtype == PIKV_F32
+                  ? launch_partial<float>(W, plan.heads_per_block, p, (int)blocks64, st)
+                  : launch_partial<bf16>(W, plan.heads_per_block, p, (int)blocks64, st);
+    if (lrc != PIKV_OK) return lrc;
+
+    CombineParams c;
+    c.part_acc = part_acc;
+    c.part_ml = part_ml;
+    c.gates = gates;
+    c.U_V = U_V;
+    c.y = y;
+    c.row_max = row_max;
+    c.row_norm = row_norm;
+    c.slot_coef = slot_coef;
+    c.Hq = desc->Hq;
+    c.G = p.G;
+    c.D = desc->D;
+    c.W = W;
+    c.k = k;
+    c.rr = p.rr;
+    c.rank = desc->rank;
+    c.nsplit = plan.nsplit;
+    c.combine = combine;
+    const dim3 cgrid(desc->B * desc->Hq), cblock(kCombineThreads);
+    if (desc->dtype == PIKV_F32)
+        hipLaunchKernelGGL(attn_combine<float>, cgrid, cblock, 0, st, c);
+    else
+        hipLaunchKernelGGL(attn_combine<bf16>, cgrid, cblock, 0, st, c);
+    return launch_status();
+}

@@ -1,0 +1,126 @@
+// Internal helpers shared by the gfx950 kernels of libpikv (not part of the C ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "pikv.h"
+
+namespace pikv {
+
+constexpr int kWave = 64;
+
+// Storage element tags.  bfloat16 is handled as its 16-bit pattern: widening to fp32 is a
+// shift, and the kernels never round back to bf16.
+struct bf16 {
+    uint16_t bits;
+};
+
+template <typename T>
+struct Pack16;  // how many elements one 16-byte lane load carries, and how to widen them
+
+template <>
+struct Pack16<float> {
+    static constexpr int N = 4;
+    static __device__ __forceinline__ void widen(const uint4 &r, float *f) {
+        f[0] = __uint_as_float(r.x);
+        f[1] = __uint_as_float(r.y);
+        f[2] = __uint_as_float(r.z);
+        f[3] = __uint_as_float(r.w);
+    }
+};
+
+template <>
+struct Pack16<bf16> {
+    static constexpr int N = 8;
+    static __device__ __forceinline__ void widen(const uint4 &r, float *f) {
+        f[0] = __uint_as_float(r.x << 16);
+        f[1] = __uint_as_float(r.x & 0xffff0000u);
+        f[2] = __uint_as_float(r.y << 16);
+        f[3] = __uint_as_float(r.y & 0xffff0000u);
+        f[4] = __uint_as_float(r.z << 16);
+        f[5] = __uint_as_float(r.z & 0xffff0000u);
+        f[6] = __uint_as_float(r.w << 16);
+        f[7] = __uint_as_float(r.w & 0xffff0000u);
+    }
+};
+
+template <typename T>
+__device__ __forceinline__ float load_scalar(const T *p, int64_t i);
+template <>
+__device__ __forceinline__ float load_scalar<float>(const float *p, int64_t i) {
+    return p[i];
+}
+template <>
+__device__ __forceinline__ float load_scalar<bf16>(const bf16 *p, int64_t i) {
+    return __uint_as_float(static_cast<uint32_t>(p[i].bits) << 16);
+}
+
+// Exchange across one lane-index bit of the wavefront.  Bits 0..3 stay inside a DPP row of
+// 16 lanes (no LDS traffic); bits 2 and 3 use the mirror patterns, which pair lane i with
+// the lane whose lower bits are complemented as well - callers only use them on values
+// that are already uniform across the lower bits (a bottom-up butterfly guarantees it).
+template <int BIT>
+__device__ __forceinline__ float lane_xchg(float x) {
+    static_assert(BIT >= 0 && BIT < 6, "wave64");
+    if constexpr (BIT == 0) {
+        return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0xB1, 0xf, 0xf, true));
+    } else if constexpr (BIT == 1) {
+        return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x4E, 0xf, 0xf, true));
+    } else if constexpr (BIT == 2) {
+        return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x141, 0xf, 0xf, true));
+    } else if constexpr (BIT == 3) {
+        return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x140, 0xf, 0xf, true));
+    } else {
+        return __shfl_xor(x, 1 << BIT, kWave);
+    }
+}
+
+// Sum / max over the lane bits [LO, HI): every participating lane ends with the result.
+template <int LO, int HI>
+__device__ __forceinline__ float bits_sum(float x) {
+    if constexpr (LO < HI) {
+        x += lane_xchg<LO>(x);
+        return bits_sum<LO + 1, HI>(x);
+    } else {
+        return x;
+    }
+}
+template <int LO, int HI>
+__device__ __forceinline__ float bits_max(float x) {
+    if constexpr (LO < HI) {
+        x = fmaxf(x, lane_xchg<LO>(x));
+        return bits_max<LO + 1, HI>(x);
+    } else {
+        return x;
+    }
+}
+
+constexpr __host__ __device__ int ilog2(int v) { return v <= 1 ? 0 : 1 + ilog2(v >> 1); }
+
+__device__ __forceinline__ uint4 load16(const void *p) {
+    return *reinterpret_cast<const uint4 *>(p);
+}
+
+inline hipStream_t as_stream(void *s) { return reinterpret_cast<hipStream_t>(s); }
+
+inline int launch_status() { return hipGetLastError() == hipSuccess ? PIKV_OK : PIKV_ERR_HIP; }
+
+// Host-side descriptor checks common to every call that takes a pikv_desc.
+int check_desc(const pikv_desc *d);
+inline int desc_width(const pikv_desc *d) { return d->rank ? d->rank : d->D; }
+inline int elem_bytes(int dtype) { return dtype == PIKV_F32 ? 4 : 2; }
+
+// Split geometry of the attention pass (also defines the workspace size).
+struct AttnPlan {
+    int heads_per_block;  // query heads sharing one K/V stream (1, 2, 4 or 8)
+    int head_blocks;      // Hq / heads_per_block
+    int tile_rows;        // rows one wave consumes per iteration
+    int chunk;            // rows per split (multiple of 4 * tile_rows)
+    int nsplit;
+    size_t acc_floats;    // B*Hq*k*nsplit*width
+    size_t ml_floats;     // B*Hq*k*nsplit*2
+};
+int make_attn_plan(const pikv_desc *d, int k, AttnPlan *plan);
+
+}  // namespace pikv

@@ -1,0 +1,114 @@
+"""The C-ABI library loads without a GPU, exports every function the header declares, and
+rejects bad arguments on the host before anything is launched."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import paper_2508_06526_amd as pk
+from paper_2508_06526_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "pikv.h")
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(pikv_[a-z_]+)\s*\(", text)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(pk.library_path()):
+        from paper_2508_06526_amd import build
+        build.build()
+    return pk.load_library()
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = declared_functions()
+    assert set(names) == set(binding.EXPORTS)
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_version_and_strerror(lib):
+    assert pk.pikv_version() >= 100
+    assert pk.pikv_strerror(0) == "ok"
+    for code in (-1, -2, -3, -4, 77):
+        assert pk.pikv_strerror(code)
+
+
+def test_desc_struct_matches_header_layout():
+    assert C.sizeof(pk.PikvDesc) == 56
+    assert pk.PikvDesc.stride_h.offset == 32 and pk.PikvDesc.route_rows_per_seq.offset == 48
+
+
+def test_workspace_size_is_zero_for_bad_geometry_and_positive_otherwise(lib):
+    good = pk.make_desc(1, 32, 8, 128, 16, 8192)
+    assert pk.pikv_attn_workspace_bytes(good, 4) > 0
+    assert pk.pikv_attn_workspace_bytes(good, 0) == 0
+    assert pk.pikv_attn_workspace_bytes(good, 17) == 0
+    assert pk.pikv_attn_workspace_bytes(pk.make_desc(1, 32, 5, 128, 16, 8192), 4) == 0   # Hq % Hkv
+    assert pk.pikv_attn_workspace_bytes(pk.make_desc(1, 32, 8, 96, 16, 8192), 4) == 0    # D
+    assert pk.pikv_attn_workspace_bytes(pk.make_desc(1, 32, 8, 128, 65, 8192), 4) == 0   # E > 64
+    assert pk.pikv_attn_workspace_bytes(pk.make_desc(1, 32, 8, 128, 16, 8192, rank=24), 4) == 0
+
+
+def test_host_side_argument_errors(lib):
+    """NULL pointers / out-of-range sizes return PIKV_ERR_INVALID with no GPU present."""
+    vp = C.c_void_p
+    fake = vp(0x1000)        # never dereferenced: every call below fails validation first
+    INVALID, UNSUPPORTED, WORKSPACE = -1, -2, -3
+    r = lib.pikv_route
+    assert r(None, fake, None, 1, 8, 4, 2, 0, fake, fake, None, None) == INVALID
+    assert r(fake, fake, None, 1, 8, 4, 5, 0, fake, fake, None, None) == INVALID      # k > E
+    assert r(fake, fake, None, 1, 8, 65, 2, 0, fake, fake, None, None) == INVALID     # E > 64
+    assert r(fake, fake, None, 1, 0, 4, 2, 0, fake, fake, None, None) == INVALID      # d_r
+    assert r(fake, fake, None, 1, 8, 4, 2, 9, fake, fake, None, None) == INVALID      # dtype
+    assert r(fake, fake, None, 0, 8, 4, 2, 0, fake, fake, None, None) == 0            # no rows
+
+    d = pk.make_desc(1, 4, 4, 64, 4, 256)
+    a = lib.pikv_sharded_attn
+
+    def attn(desc, q=fake, k=2, combine=0, ws=fake, ws_bytes=1 << 30, y=fake, uk=None):
+        return a(C.byref(desc), q, fake, fake, uk, uk, fake, fake, None, k, combine, 0.0, y, None,
+                 None, None, None, ws, ws_bytes, None)
+    assert attn(d, q=None) == INVALID
+    assert attn(d, y=None) == INVALID
+    assert attn(d, k=0) == INVALID
+    assert attn(d, combine=3) == INVALID
+    assert attn(d, ws_bytes=16) == WORKSPACE
+    assert attn(d, ws=None) == WORKSPACE
+    assert attn(pk.make_desc(1, 4, 4, 64, 4, 256, rank=32)) == INVALID                 # U_K missing
+    assert attn(pk.make_desc(1, 4, 4, 48, 4, 256)) == UNSUPPORTED
+    assert attn(pk.make_desc(1, 4, 4, 64, 4, 256, stride_s=60)) == INVALID
+    assert attn(pk.make_desc(1, 4, 4, 64, 4, 256, route_rows_per_seq=2)) == INVALID
+    assert attn(pk.make_desc(0, 4, 4, 64, 4, 256)) == 0                                # B == 0
+
+    u = lib.pikv_update_utility
+    assert u(C.byref(d), None, fake, fake, fake, 2, 1.0, fake, None) == INVALID
+    assert u(C.byref(d), fake, fake, fake, fake, 2, -0.5, fake, None) == INVALID
+    assert u(C.byref(d), fake, fake, fake, fake, 9, 1.0, fake, None) == INVALID
+    assert u(C.byref(d), fake, fake, fake, fake, 2, float("nan"), fake, None) == INVALID
+
+    e = lib.pikv_evict
+    assert e(C.byref(d), None, fake, 10, None, 0, fake, fake, 4, 0, None, None, None) == INVALID
+    assert e(C.byref(d), fake, fake, -1, None, 0, fake, fake, 4, 0, None, None, None) == INVALID
+    assert e(C.byref(d), fake, fake, 10, None, 0, fake, fake, 0, 0, None, None, None) == INVALID
+    assert e(C.byref(d), fake, fake, 10, fake, 0, fake, fake, 4, 0, None, None, None) == INVALID
+    assert e(C.byref(d), fake, fake, 10, None, 0, fake, fake, 4, 1, None, None, None) == INVALID
+
+    ap = lib.pikv_append
+    assert ap(C.byref(d), None, fake, fake, 2, None, None, 0, fake, fake, fake, fake, None) == INVALID
+    assert ap(C.byref(d), fake, fake, fake, 5, None, None, 0, fake, fake, fake, fake, None) == INVALID
+    assert ap(C.byref(d), fake, fake, fake, 2, fake, None, 1, fake, fake, fake, fake, None) == INVALID
+
+
+def test_missing_library_fails_loudly(monkeypatch, tmp_path):
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "_LIB_PATH", str(tmp_path / "nope.so"))
+    with pytest.raises(OSError):
+        binding.load_library()

@@ -1,0 +1,374 @@
+"""HIP path vs CPU oracle, element by element, on identical seeded inputs.
+
+Bars: expert indices, evicted slots, appended rows: bit-exact.  Attention output:
+|d| <= 2e-3 + 1e-2 |ref| (bf16 storage, fp32 accumulate) plus a relative-L2 bound of 1e-3;
+utilities: rel 1e-4.  Sizes span several tiles, several splits and ragged tails.
+"""
+import numpy as np
+import pytest
+
+import workloads as wl
+from oracle import pikv_oracle as orc
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+if not torch.cuda.is_available():  # pragma: no cover
+    pytest.skip("no GPU", allow_module_level=True)
+
+import paper_2508_06526_amd as pk  # noqa: E402
+from gpu_harness import (DEV, DeviceCase, assert_utility_close, ensure_route_margin, t2n,  # noqa: E402
+                         y_tolerance_ok)
+
+
+def oracle_step(case, idx, gates, combine, utility=None, decay=1.0, scale=0.0):
+    g = case.geo
+    return orc.attend(case.q, case.K_shards, case.V_shards, case.n_valid, idx, gates, Hkv=g.Hkv,
+                      E=g.E, S=g.S, dtype=g.dtype, rank=g.rank, U_K=case.U_K, U_V=case.U_V,
+                      combine=combine, scale=scale, utility=utility, decay=decay, want_prob=True)
+
+
+# ---------------------------------------------------------------------- route
+ROUTE_CASES = [
+    # (rows-shape geometry, k)
+    dict(B=1, Hq=4, Hkv=4, D=64, E=4, S=8, k=2, dtype="f32", per_head_routing=True),
+    dict(B=8, Hq=32, Hkv=32, D=128, E=16, S=8, k=2, dtype="bf16"),
+    dict(B=1, Hq=32, Hkv=8, D=128, E=16, S=8, k=4, dtype="bf16"),
+    dict(B=32, Hq=32, Hkv=32, D=128, E=8, S=8, k=2, dtype="bf16"),
+    dict(B=3, Hq=2, Hkv=1, D=16, E=5, S=8, k=3, dtype="f32"),
+    dict(B=5, Hq=4, Hkv=4, D=32, E=64, S=8, k=7, dtype="bf16"),
+    dict(B=2, Hq=8, Hkv=8, D=64, E=1, S=8, k=1, dtype="bf16"),
+    dict(B=4, Hq=8, Hkv=8, D=64, E=33, S=8, k=33, dtype="f32"),
+]
+
+
+@pytest.mark.parametrize("spec", ROUTE_CASES, ids=lambda s: "E%d_k%d_%s_B%d" % (s["E"], s["k"], s["dtype"], s["B"]))
+@pytest.mark.parametrize("with_bias", [False, True])
+def test_route_matches_oracle(spec, with_bias):
+    g = wl.Geometry(**spec)
+    case = wl.make_host_case(g, seed=3, w_sigma=1.0 if g.dtype == "f32" else 0.02,
+                             zipf_s=1.1 if with_bias else 0.0)
+    ensure_route_margin(case, g.k)
+    dc = DeviceCase(case)
+    dc.route()
+    x = np.ascontiguousarray(case.q.reshape(g.route_rows, g.d_r))
+    idx, gates, probs = orc.route(x, case.W_r, g.k, bias=case.bias, dtype=g.dtype)
+    np.testing.assert_array_equal(t2n(dc.topk), idx)
+    np.testing.assert_allclose(t2n(dc.gates), gates, rtol=2e-5, atol=1e-7)
+    np.testing.assert_allclose(t2n(dc.probs), probs, rtol=2e-5, atol=1e-7)
+
+
+def test_route_exact_ties_lower_index_first():
+    rng = np.random.default_rng(6)
+    rows, d_r = 64, 32
+    x = rng.integers(-3, 4, size=(rows, d_r)).astype(np.float32)
+    Wb = rng.integers(-2, 3, size=(d_r, 4)).astype(np.float32)
+    W = np.ascontiguousarray(np.concatenate([Wb, Wb[:, [1, 3]], Wb[:, [0]], Wb], axis=1))   # E = 11
+    x[0] = 0
+    for dtype in ("f32", "bf16"):
+        xs, Ws = wl.encode(x, dtype), wl.encode(W, dtype)
+        for k in (1, 3, 6, 11):
+            idx, gates, _ = orc.route(xs, Ws, k, dtype=dtype)
+            from gpu_harness import dev_storage
+            tk = torch.zeros((rows, k), device=DEV, dtype=torch.int32)
+            tg = torch.zeros((rows, k), device=DEV)
+            pk.pikv_route(dev_storage(xs, dtype), dev_storage(Ws, dtype), None, rows, d_r, 11, k, tk, tg)
+            np.testing.assert_array_equal(t2n(tk), idx)
+            np.testing.assert_allclose(t2n(tg), gates, rtol=2e-5)
+
+
+# ------------------------------------------------------------------ attention
+ATTN_CASES = {
+    # config 1 itself: per-head routing, fp32
+    "c1_tiny_f32": (dict(B=1, Hq=4, Hkv=4, D=64, E=4, S=256, k=2, dtype="f32", per_head_routing=True), "full"),
+    # scaled config 2: G=1, bf16, several splits and a ragged tail
+    "c2_scaled": (dict(B=2, Hq=4, Hkv=4, D=128, E=6, S=700, k=2, dtype="bf16"), "ragged"),
+    # scaled config 3: GQA group of 4, k=4
+    "c3_scaled": (dict(B=1, Hq=8, Hkv=2, D=128, E=8, S=1100, k=4, dtype="bf16"), "ragged"),
+    "gqa2": (dict(B=2, Hq=4, Hkv=2, D=64, E=4, S=300, k=2, dtype="bf16"), "ragged"),
+    "gqa8": (dict(B=1, Hq=8, Hkv=1, D=128, E=4, S=260, k=2, dtype="bf16"), "full"),
+    "gqa3_generic": (dict(B=1, Hq=6, Hkv=2, D=64, E=4, S=150, k=3, dtype="bf16"), "ragged"),
+    # scaled config 5: rank-32 codes
+    "c5_scaled": (dict(B=2, Hq=4, Hkv=4, D=128, E=6, S=900, k=2, dtype="bf16", rank=32), "ragged"),
+    "rank16_gqa4": (dict(B=1, Hq=8, Hkv=2, D=64, E=4, S=520, k=2, dtype="bf16", rank=16), "ragged"),
+    "rank64_f32": (dict(B=1, Hq=2, Hkv=2, D=128, E=3, S=130, k=2, dtype="f32", rank=64), "full"),
+    "f32_d128": (dict(B=1, Hq=2, Hkv=1, D=128, E=3, S=100, k=3, dtype="f32"), "ragged"),
+    "d32_bf16": (dict(B=2, Hq=2, Hkv=2, D=32, E=4, S=515, k=2, dtype="bf16"), "ragged"),
+    "d16_bf16_perhead": (dict(B=2, Hq=4, Hkv=2, D=16, E=4, S=1030, k=2, dtype="bf16", per_head_routing=True), "ragged"),
+    "k_equals_E": (dict(B=1, Hq=4, Hkv=4, D=64, E=4, S=129, k=4, dtype="bf16"), "ragged"),
+    "one_slot": (dict(B=1, Hq=2, Hkv=2, D=64, E=2, S=1, k=2, dtype="bf16"), "full"),
+}
+
+
+def random_selection(g, seed):
+    rng = np.random.default_rng(seed)
+    idx = np.stack([rng.permutation(g.E)[:g.k] for _ in range(g.route_rows)]).astype(np.int32)
+    gates = rng.random((g.route_rows, g.k)).astype(np.float32) + 0.05
+    gates /= gates.sum(-1, keepdims=True)
+    return idx, gates.astype(np.float32)
+
+
+@pytest.mark.parametrize("name", sorted(ATTN_CASES))
+@pytest.mark.parametrize("combine", [orc.COMBINE_LSE, orc.COMBINE_LOCAL], ids=["lse", "local"])
+@pytest.mark.parametrize("use_gates", [True, False], ids=["gates", "mask"])
+def test_attention_and_utility_match_oracle(name, combine, use_gates):
+    spec, nv = ATTN_CASES[name]
+    g = wl.Geometry(**spec)
+    case = wl.make_host_case(g, seed=11, kv="lognormal_token", n_valid=nv, utility0="exp")
+    idx, gates = random_selection(g, 5)
+    if not use_gates:
+        gates = None
+    u_ref = case.utility.copy()
+    ref = oracle_step(case, idx, gates, combine, utility=u_ref, decay=0.9)
+
+    dc = DeviceCase(case)
+    d_idx = torch.from_numpy(idx).to(DEV)
+    d_gates = None if gates is None else torch.from_numpy(gates).to(DEV)
+    dc.attend(topk=d_idx, gates=d_gates, combine=combine)
+    dc.update_utility(0.9, topk=d_idx)
+
+    y = t2n(dc.y)
+    ok, emax, l2 = y_tolerance_ok(y, ref["y"], g.dtype)
+    assert ok, "y mismatch: max abs %.3e, rel L2 %.3e" % (emax, l2)
+    np.testing.assert_allclose(t2n(dc.row_max), ref["row_max"], rtol=1e-4, atol=1e-5)
+    np.testing.assert_allclose(t2n(dc.row_norm), ref["row_norm"], rtol=1e-4, atol=1e-9)
+    assert_utility_close(t2n(dc.utility), u_ref)
+    # per-entry probabilities rebuilt from the emitted scores and (shift, coef)
+    sc, co = t2n(dc.scores).astype(np.float64), t2n(dc.slot_coef).astype(np.float64)
+    for b in range(g.B):
+        for h in range(g.Hq):
+            row = b * g.Hq + h if g.per_head_routing else b
+            for j in range(g.k):
+                n = case.n_valid[b, idx[row, j]]
+                p = co[b, h, j, 1] * np.exp(sc[b, h, j, :n] - co[b, h, j, 0])
+                np.testing.assert_allclose(p, ref["prob"][b, h, j, :n], rtol=1e-4, atol=1e-10)
+
+
+def test_attention_is_bitwise_repeatable():
+    spec, nv = ATTN_CASES["c3_scaled"]
+    g = wl.Geometry(**spec)
+    case = wl.make_host_case(g, seed=12, n_valid=nv)
+    idx, gates = random_selection(g, 6)
+    dc = DeviceCase(case)
+    d_idx, d_gates = torch.from_numpy(idx).to(DEV), torch.from_numpy(gates).to(DEV)
+    outs = []
+    for _ in range(2):
+        dc.utility.zero_()
+        dc.attend(topk=d_idx, gates=d_gates)
+        dc.update_utility(1.0, topk=d_idx)
+        outs.append((t2n(dc.y), t2n(dc.utility)))
+    np.testing.assert_array_equal(outs[0][0], outs[1][0])
+    np.testing.assert_array_equal(outs[0][1], outs[1][1])
+
+
+def test_strided_shards_and_explicit_scale():
+    g = wl.Geometry(B=1, Hq=4, Hkv=2, D=64, E=3, S=200, k=2, dtype="bf16")
+    case = wl.make_host_case(g, seed=13, n_valid="ragged")
+    idx, gates = random_selection(g, 7)
+    ref = oracle_step(case, idx, gates, orc.COMBINE_LSE, scale=0.2)
+    dc = DeviceCase(case, stride_pad=(8, 5))
+    dc.attend(topk=torch.from_numpy(idx).to(DEV), gates=torch.from_numpy(gates).to(DEV), scale=0.2,
+              want_scores=False)
+    ok, emax, l2 = y_tolerance_ok(t2n(dc.y), ref["y"], g.dtype)
+    assert ok, (emax, l2)
+
+
+def test_all_selected_shards_empty_gives_zero_and_leaves_utility():
+    g = wl.Geometry(B=2, Hq=4, Hkv=4, D=64, E=4, S=64, k=2, dtype="bf16")
+    case = wl.make_host_case(g, seed=14, utility0="exp")
+    case.n_valid[0, :] = 0
+    case.n_valid[1, 2] = 0
+    idx = np.array([[0, 1], [2, 3]], np.int32)
+    u_ref = case.utility.copy()
+    ref = oracle_step(case, idx, None, orc.COMBINE_LSE, utility=u_ref, decay=0.5)
+    dc = DeviceCase(case)
+    d_idx = torch.from_numpy(idx).to(DEV)
+    dc.attend(topk=d_idx, gates=None)
+    dc.update_utility(0.5, topk=d_idx)
+    y = t2n(dc.y)
+    assert (y[0] == 0).all()
+    ok, emax, l2 = y_tolerance_ok(y, ref["y"], g.dtype)
+    assert ok, (emax, l2)
+    assert_utility_close(t2n(dc.utility), u_ref)
+    np.testing.assert_array_equal(t2n(dc.utility)[0], case.utility[0])
+
+
+# ---------------------------------------------------------------- evict / append
+def run_gpu_evict(g, u, n, capacity, sel=None, max_evict=None, compact=False, case=None):
+    dt = g.dtype
+    if case is None:
+        case = wl.make_host_case(g, seed=1)
+    case = case.clone()
+    case.utility, case.n_valid = u.copy(), n.copy()
+    dc = DeviceCase(case)
+    if max_evict is None:
+        max_evict = max(1, g.S - capacity)
+    eidx = torch.full((g.B, g.E, max_evict), -1, device=DEV, dtype=torch.int32)
+    ecnt = torch.full((g.B, g.E), -7, device=DEV, dtype=torch.int32)
+    d_sel = None if sel is None else torch.from_numpy(sel).to(DEV)
+    pk.pikv_evict(dc.desc, dc.utility, dc.n_valid, capacity, d_sel, 0 if sel is None else sel.shape[1],
+                  eidx, ecnt, max_evict, compact, dc.K_tab if compact else None,
+                  dc.V_tab if compact else None)
+    return dc, t2n(eidx), t2n(ecnt)
+
+
+@pytest.mark.parametrize("S,capacity", [(256, 192), (1000, 1), (16, 6), (2048, 2047), (5000, 4096), (300, 0)])
+@pytest.mark.parametrize("ties", [False, True], ids=["distinct", "ties"])
+def test_evict_matches_oracle_bit_exact(S, capacity, ties):
+    g = wl.Geometry(B=2, Hq=2, Hkv=2, D=16, E=3, S=S, k=2, dtype="bf16")
+    rng = np.random.default_rng(S + capacity)
+    if ties:
+        u = (rng.integers(0, 6, size=(g.B, g.E, S)) / 8).astype(np.float32)
+    else:
+        u = (rng.exponential(1.0, size=(g.B, g.E, S)) / S).astype(np.float32)
+    n = rng.integers(max(0, capacity - 3), S + 1, size=(g.B, g.E)).astype(np.int32)
+    n[0, 0] = S
+    u_ref, n_ref = u.copy(), n.copy()
+    ridx, rcnt = orc.evict(u_ref, n_ref, capacity, max_evict=max(1, S - capacity))
+    dc, eidx, ecnt = run_gpu_evict(g, u, n, capacity)
+    np.testing.assert_array_equal(ecnt, rcnt)
+    for b in range(g.B):
+        for e in range(g.E):
+            np.testing.assert_array_equal(eidx[b, e, :rcnt[b, e]], ridx[b, e, :rcnt[b, e]])
+    np.testing.assert_array_equal(t2n(dc.n_valid), n_ref)
+    np.testing.assert_array_equal(t2n(dc.utility), u_ref)
+
+
+def test_evict_special_values_and_selection_list():
+    g = wl.Geometry(B=2, Hq=2, Hkv=2, D=16, E=4, S=64, k=2, dtype="bf16")
+    rng = np.random.default_rng(3)
+    u = rng.standard_normal((g.B, g.E, g.S)).astype(np.float32)       # negative utilities too
+    u[0, 1, ::3] = 0.0
+    u[0, 1, 1::6] = -0.0
+    u[1, 2, :] = 0.25                                                  # all equal
+    n = np.full((g.B, g.E), g.S, np.int32)
+    sel = np.array([[1, 3], [2, 0]], np.int32)
+    mask = np.zeros((g.B, g.E), np.int32)
+    for b in range(g.B):
+        mask[b, sel[b]] = 1
+    u_ref, n_ref = u.copy(), n.copy()
+    ridx, rcnt = orc.evict(u_ref, n_ref, 40, shard_mask=mask, max_evict=24)
+    dc, eidx, ecnt = run_gpu_evict(g, u, n, 40, sel=sel, max_evict=24)
+    np.testing.assert_array_equal(ecnt, rcnt)
+    np.testing.assert_array_equal(eidx[mask == 1], ridx[mask == 1])
+    np.testing.assert_array_equal(t2n(dc.n_valid), n_ref)
+    # more to evict than max_evict: shard untouched, count -1
+    dc, eidx, ecnt = run_gpu_evict(g, u, n, 10, max_evict=5)
+    assert (ecnt == -1).all() and (t2n(dc.n_valid) == g.S).all()
+
+
+@pytest.mark.parametrize("spec", [
+    dict(B=1, Hq=4, Hkv=4, D=64, E=4, S=256, k=2, dtype="f32", per_head_routing=True),   # config 1: 256 -> 192
+    dict(B=2, Hq=4, Hkv=2, D=128, E=3, S=700, k=2, dtype="bf16"),
+    dict(B=1, Hq=2, Hkv=2, D=128, E=2, S=300, k=2, dtype="bf16", rank=32),
+], ids=["c1", "bf16_d128", "rank32"])
+def test_evict_with_compaction_moves_rows_like_oracle(spec):
+    g = wl.Geometry(**spec)
+    case = wl.make_host_case(g, seed=21, n_valid="ragged", utility0="exp")
+    case.n_valid[0, 0] = g.S
+    capacity = (g.S * 3) // 4
+    ref = case.clone()
+    ridx, rcnt = orc.evict(ref.utility, ref.n_valid, capacity, compact=True, K_shards=ref.K_shards,
+                           V_shards=ref.V_shards, Hkv=g.Hkv, width=g.width, dtype=g.dtype)
+    dc, eidx, ecnt = run_gpu_evict(g, case.utility, case.n_valid, capacity, compact=True, case=case)
+    np.testing.assert_array_equal(ecnt, rcnt)
+    n_new = t2n(dc.n_valid)
+    np.testing.assert_array_equal(n_new, ref.n_valid)
+    u = t2n(dc.utility)
+    for b in range(g.B):
+        for e in range(g.E):
+            s, nn = b * g.E + e, n_new[b, e]
+            np.testing.assert_array_equal(eidx[b, e, :rcnt[b, e]], ridx[b, e, :rcnt[b, e]])
+            np.testing.assert_array_equal(u[b, e, :nn], ref.utility[b, e, :nn])
+            np.testing.assert_array_equal(dc.shard_host("K", s)[:, :nn], ref.K_shards[s][:, :nn])
+            np.testing.assert_array_equal(dc.shard_host("V", s)[:, :nn], ref.V_shards[s][:, :nn])
+
+
+def test_append_matches_oracle_bit_exact():
+    g = wl.Geometry(B=3, Hq=4, Hkv=2, D=128, E=4, S=50, k=2, dtype="bf16")
+    case = wl.make_host_case(g, seed=22, n_valid="ragged", utility0="exp")
+    case.n_valid[1, 1] = g.S                                # a full shard: entry dropped
+    idx = np.array([[0, 2], [1, 3], [3, 0]], np.int32)
+    kn, vn = wl.draw_new_kv(g, 5)
+    from gpu_harness import dev_storage
+    dc = DeviceCase(case)
+    pk.pikv_append(dc.desc, dev_storage(kn, g.dtype), dev_storage(vn, g.dtype),
+                   torch.from_numpy(idx).to(DEV), g.k, None, None, 0, dc.K_tab, dc.V_tab,
+                   dc.utility, dc.n_valid)
+    ref = case.clone()
+    # the oracle reports a full shard as an error; the library drops the entry for that shard
+    idx_ok = idx.copy()
+    ref_n_full = ref.n_valid.copy()
+    for b in range(g.B):
+        sel = [e for e in idx[b] if ref.n_valid[b, e] < g.S]
+        for e in sel:
+            one = np.array([[e]], np.int32)
+            orc.append(np.ascontiguousarray(kn[b:b + 1]), np.ascontiguousarray(vn[b:b + 1]), one,
+                       ref.K_shards[b * g.E:(b + 1) * g.E], ref.V_shards[b * g.E:(b + 1) * g.E],
+                       ref.utility[b:b + 1], ref.n_valid[b:b + 1], dtype=g.dtype)
+    np.testing.assert_array_equal(t2n(dc.n_valid), ref.n_valid)
+    np.testing.assert_array_equal(t2n(dc.utility), ref.utility)
+    for s in range(g.B * g.E):
+        np.testing.assert_array_equal(dc.shard_host("K", s), ref.K_shards[s])
+        np.testing.assert_array_equal(dc.shard_host("V", s), ref.V_shards[s])
+    assert ref.n_valid[1, 1] == g.S and idx_ok is not None and ref_n_full is not None
+
+
+# --------------------------------------------------------- streaming (config 4, scaled)
+def test_streaming_steps_route_evict_append_attend_update():
+    """Each step: route -> evict the min-utility entry of every selected full shard ->
+    append the new token there -> attend -> utility with decay 0.9.  The GPU carries its own
+    state; at every step its selections and evicted slots must equal the oracle's applied
+    to the GPU's own pre-step bits, and the free-running oracle state must stay within
+    tolerance."""
+    g = wl.Geometry(B=4, Hq=4, Hkv=4, D=64, E=4, S=96, k=2, dtype="bf16")
+    case = wl.make_host_case(g, seed=31, utility0="exp")
+    case.n_valid[:, 0] = g.S - 2                      # some shards still have room
+    from gpu_harness import dev_storage
+    dc = DeviceCase(case)
+    eidx = torch.full((g.B, g.E, 1), -1, device=DEV, dtype=torch.int32)
+    ecnt = torch.zeros((g.B, g.E), device=DEV, dtype=torch.int32)
+    ref = case.clone()
+    for step in range(12):
+        qn = wl.draw_queries(g, 500 + step)
+        probe = case.clone()
+        probe.q = qn
+        ensure_route_margin(probe, g.k)
+        qn = probe.q
+        kn, vn = wl.draw_new_kv(g, 900 + step)
+        # --- GPU
+        dc.q.copy_(dev_storage(qn, g.dtype))
+        u_before, n_before = t2n(dc.utility), t2n(dc.n_valid)
+        dc.route()
+        pk.pikv_evict(dc.desc, dc.utility, dc.n_valid, g.S - 1, dc.topk, g.k, eidx, ecnt, 1, False,
+                      None, None)
+        pk.pikv_append(dc.desc, dev_storage(kn, g.dtype), dev_storage(vn, g.dtype), dc.topk, g.k,
+                       eidx, ecnt, 1, dc.K_tab, dc.V_tab, dc.utility, dc.n_valid)
+        dc.attend(combine=pk.COMBINE_LSE)
+        dc.update_utility(0.9)
+        # --- oracle, free running
+        x = np.ascontiguousarray(qn.reshape(g.route_rows, g.d_r))
+        idx, gates, _ = orc.route(x, ref.W_r, g.k, dtype=g.dtype)
+        np.testing.assert_array_equal(t2n(dc.topk), idx)
+        mask = np.zeros((g.B, g.E), np.int32)
+        for b in range(g.B):
+            mask[b, idx[b]] = 1
+        # evict parity on identical bits: the oracle applied to the GPU's own pre-step state
+        ub, nb = u_before.copy(), n_before.copy()
+        pidx, pcnt = orc.evict(ub, nb, g.S - 1, shard_mask=mask, max_evict=1)
+        np.testing.assert_array_equal(t2n(ecnt), pcnt)
+        np.testing.assert_array_equal(t2n(eidx)[pcnt == 1], pidx[pcnt == 1])
+        ridx, rcnt = orc.evict(ref.utility, ref.n_valid, g.S - 1, shard_mask=mask, max_evict=1)
+        np.testing.assert_array_equal(rcnt, pcnt)
+        assert (ridx[rcnt == 1] == pidx[pcnt == 1]).all(), "free-running oracle diverged at step %d" % step
+        orc.append(kn, vn, idx, ref.K_shards, ref.V_shards, ref.utility, ref.n_valid, dtype=g.dtype,
+                   reuse_idx=ridx, reuse_cnt=rcnt)
+        ref.q = qn
+        out = oracle_step(ref, idx, gates, orc.COMBINE_LSE, utility=ref.utility, decay=0.9)
+        ok, emax, l2 = y_tolerance_ok(t2n(dc.y), out["y"], g.dtype)
+        assert ok, (step, emax, l2)
+        assert_utility_close(t2n(dc.utility), ref.utility)
+        np.testing.assert_array_equal(t2n(dc.n_valid), ref.n_valid)
+        assert (ref.n_valid <= g.S).all()
+    for s in range(g.B * g.E):
+        np.testing.assert_array_equal(dc.shard_host("K", s), ref.K_shards[s])
