@@ -122,14 +122,15 @@ def ensure_route_margin(case: wl.HostCase, k: int, margin: float = 1e-3, max_red
     """Redraw query rows whose k-th and (k+1)-th logits (fp64, from the oracle) are closer
     than `margin`, so that any fp32 summation order selects the same experts."""
     g = case.geo
-    if k >= g.E:
+    if g.E == 1:
         return
     for attempt in range(max_redraw):
         x = case.q.reshape(g.route_rows, g.d_r)
         _, _, _, logits = orc.route(np.ascontiguousarray(x), case.W_r, k, bias=case.bias,
                                     dtype=g.dtype, want_logits=True)
         srt = -np.sort(-logits, axis=1)
-        gaps = np.abs(np.diff(srt, axis=1)).min(axis=1)      # every adjacent pair: order is output too
+        # adjacent pairs among the first k+1: the selection AND its output order are decided there
+        gaps = np.abs(np.diff(srt[:, :k + 1], axis=1)).min(axis=1)
         bad = np.nonzero(gaps < margin)[0]
         if bad.size == 0:
             return
