@@ -1,0 +1,254 @@
+#!/usr/bin/env python3
+"""Benchmark of the PiKV routed sharded-KV decode path on one MI355X.
+
+A "step" is one pass of the whole hot path over one batch of queries against one layer's
+expert-sharded cache:  route -> evict (min-utility entry of every selected full shard) ->
+append the new token's K/V -> attention over the selected shards -> utility update.
+Every step runs in the HIP kernels of libpikv.so through the C ABI; inputs are seeded,
+synthetic, and resident in HBM before the timed region starts.
+
+Default workload: the 128K-context / 16-expert long-context configuration (B=1, 32 query
+heads over 8 KV heads, D=128, E=16 shards x 8192 tokens, top-k=4, bf16).  One step reads
+128 MiB of K/V, which would fit the 256 MB Infinity Cache, so the steps cycle round-robin
+over 32 independent layer instances (16 GiB), as a 32-layer model does for every token.
+
+Prints ONE JSON line (see README for the fields).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=4096)
+    ap.add_argument("--warmup", type=int, default=256)
+    ap.add_argument("--config", default="c3_long_context")
+    ap.add_argument("--layers", type=int, default=0, help="layer instances cycled (0: per config)")
+    ap.add_argument("--mode", choices=["graph", "eager"], default="graph")
+    ap.add_argument("--cpu-steps", type=int, default=-1, help="oracle steps timed (0: skip, -1: auto)")
+    ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--seed", type=int, default=0)
+    return ap.parse_args()
+
+
+# layer instances so that consecutive steps cannot be served from the 256 MB Infinity Cache
+DEFAULT_LAYERS = {"c1_tiny_f32": 1, "c2_bf16_decode": 2, "c3_long_context": 32, "c4_streaming": 2,
+                  "c5_compressed": 16}
+RECIPE = {  # how each configuration's inputs are drawn (workloads.make_device_layers arguments)
+    "c1_tiny_f32": dict(w_sigma=1.0),
+    "c2_bf16_decode": dict(kv="lognormal_token"),
+    "c3_long_context": dict(zipf_s=1.1),
+    "c4_streaming": dict(utility0="exp"),
+    "c5_compressed": dict(zipf_s=1.1),
+}
+DECAY = {"c4_streaming": 0.9}
+
+
+class Layer:
+    """One layer instance's device state plus the binding calls of one step."""
+
+    def __init__(self, pk, torch, geo, tensors, shared):
+        self.pk, self.geo, self.t, self.sh = pk, geo, tensors, shared
+        g = geo
+        self.desc = pk.make_desc(g.B, g.Hq, g.Hkv, g.D, g.E, g.S, rank=g.rank,
+                                 dtype=0 if g.dtype == "f32" else 1,
+                                 route_rows_per_seq=g.Hq if g.per_head_routing else 1)
+        self.K_tab = pk.shard_table(tensors["K"])
+        self.V_tab = pk.shard_table(tensors["V"])
+        self.decay = DECAY.get(g.name, 1.0)
+
+    def step(self):
+        pk, g, t, s = self.pk, self.geo, self.t, self.sh
+        pk.pikv_route(t["q"], t["W_r"], t["bias"], g.route_rows, g.d_r, g.E, g.k, s["topk"],
+                      s["gates"], None)
+        if not g.per_head_routing:
+            pk.pikv_evict(self.desc, t["utility"], t["n_valid"], g.S - 1, s["topk"], g.k, s["eidx"],
+                          s["ecnt"], 1, False, None, None)
+            pk.pikv_append(self.desc, s["K_new"], s["V_new"], s["topk"], g.k, s["eidx"], s["ecnt"], 1,
+                           self.K_tab, self.V_tab, t["utility"], t["n_valid"])
+        self.attend()
+        pk.pikv_update_utility(self.desc, s["scores"], s["slot_coef"], t["n_valid"], s["topk"], g.k,
+                               self.decay, t["utility"])
+
+    def attend(self):
+        pk, g, t, s = self.pk, self.geo, self.t, self.sh
+        pk.pikv_sharded_attn(self.desc, t["q"], self.K_tab, self.V_tab, t["U_K"], t["U_V"],
+                             t["n_valid"], s["topk"], s["gates"], g.k, pk.COMBINE_LSE, 0.0, s["y"],
+                             s["row_max"], s["row_norm"], s["scores"], s["slot_coef"], s["workspace"])
+
+
+def make_shared(pk, torch, geo, dev):
+    g = geo
+    tdt = torch.float32 if g.dtype == "f32" else torch.bfloat16
+    R, k = g.route_rows, g.k
+    desc = pk.make_desc(g.B, g.Hq, g.Hkv, g.D, g.E, g.S, rank=g.rank, dtype=0 if g.dtype == "f32" else 1,
+                        route_rows_per_seq=g.Hq if g.per_head_routing else 1)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(12345)
+    return dict(
+        topk=torch.zeros((R, k), device=dev, dtype=torch.int32),
+        gates=torch.zeros((R, k), device=dev),
+        eidx=torch.zeros((g.B, g.E, 1), device=dev, dtype=torch.int32),
+        ecnt=torch.zeros((g.B, g.E), device=dev, dtype=torch.int32),
+        K_new=torch.randn((g.B, g.Hkv, g.width), device=dev, generator=gen).to(tdt),
+        V_new=torch.randn((g.B, g.Hkv, g.width), device=dev, generator=gen).to(tdt),
+        y=torch.zeros((g.B, g.Hq, g.D), device=dev),
+        row_max=torch.zeros((g.B, g.Hq), device=dev),
+        row_norm=torch.zeros((g.B, g.Hq), device=dev),
+        scores=torch.zeros((g.B, g.Hq, k, g.S), device=dev),
+        slot_coef=torch.zeros((g.B, g.Hq, k, 2), device=dev),
+        workspace=torch.empty(pk.pikv_attn_workspace_bytes(desc, k), device=dev, dtype=torch.uint8),
+    )
+
+
+def cpu_baseline(torch, wl, layers, n_steps):
+    """Time the oracle (as it stands) on the same inputs: route + attend + utility per step."""
+    from oracle import pikv_oracle as orc
+    import numpy as np
+    g = layers[0].geo
+    dummy = np.zeros((1,), np.float32 if g.dtype == "f32" else np.uint16)
+    prepared = []
+    for L in layers[:n_steps]:
+        t = L.t
+        q = wl.to_host(t["q"], g.dtype)
+        W = wl.to_host(t["W_r"], g.dtype)
+        bias = None if t["bias"] is None else t["bias"].cpu().numpy()
+        x = np.ascontiguousarray(q.reshape(g.route_rows, g.d_r))
+        idx, gates, _ = orc.route(x, W, g.k, bias=bias, dtype=g.dtype)
+        Ks, Vs = [dummy] * (g.B * g.E), [dummy] * (g.B * g.E)
+        for row in range(idx.shape[0]):
+            b = row // g.Hq if g.per_head_routing else row
+            for e in idx[row]:
+                i = b * g.E + int(e)
+                if Ks[i] is dummy:
+                    Ks[i] = wl.to_host(t["K"][b, e], g.dtype)
+                    Vs[i] = wl.to_host(t["V"][b, e], g.dtype)
+        prepared.append(dict(
+            q=q, W=W, bias=bias, x=x, Ks=Ks, Vs=Vs, n=t["n_valid"].cpu().numpy(),
+            u=t["utility"].cpu().numpy(),
+            UK=None if t["U_K"] is None else wl.to_host(t["U_K"], g.dtype),
+            UV=None if t["U_V"] is None else wl.to_host(t["U_V"], g.dtype)))
+    t0 = time.perf_counter()
+    for p in prepared:
+        idx, gates, _ = orc.route(p["x"], p["W"], g.k, bias=p["bias"], dtype=g.dtype)
+        orc.attend(p["q"], p["Ks"], p["Vs"], p["n"], idx, gates, Hkv=g.Hkv, E=g.E, S=g.S,
+                   dtype=g.dtype, rank=g.rank, U_K=p["UK"], U_V=p["UV"], utility=p["u"],
+                   decay=DECAY.get(g.name, 1.0))
+    dt = time.perf_counter() - t0
+    return dt / max(1, len(prepared)), len(prepared)
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build holds all expert shards on a single MI355X "
+              "and has no multi-GPU path; run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import paper_2508_06526_amd as pk
+    import workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU (no CPU fallback exists)", file=sys.stderr)
+        sys.exit(2)
+    pk.load_library()
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    geo = wl.CONFIGS[args.config]
+    n_layers = args.layers or DEFAULT_LAYERS[args.config]
+    raw = wl.make_device_layers(geo, n_layers, args.seed, dev, **RECIPE[args.config])
+    shared = make_shared(pk, torch, geo, dev)
+    layers = [Layer(pk, torch, geo, t, shared) for t in raw]
+    torch.cuda.synchronize()
+
+    stream = torch.cuda.Stream()          # default priority; all library calls go here
+    K, W = args.steps, args.warmup
+    with torch.cuda.stream(stream):
+        for i in range(W):
+            layers[i % n_layers].step()
+        stream.synchronize()
+        graph = None
+        if args.mode == "graph":
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=stream):
+                for L in layers:
+                    L.step()
+            graph.replay()                 # one untimed replay
+            stream.synchronize()
+
+        # ---- timed region: exactly K steps
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        done = 0
+        if graph is not None:
+            for _ in range(K // n_layers):
+                graph.replay()
+            done = (K // n_layers) * n_layers
+        for i in range(done, K):
+            layers[i % n_layers].step()
+        torch.cuda.synchronize()
+        elapsed = time.perf_counter() - t0
+
+        # ---- dominant kernel (the attention pass over the selected shards), HIP events on
+        # the stream it is launched on, same steps and launch configuration, eager launches
+        n_probe = min(K, 256)
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+              for _ in range(n_probe)]
+        for i in range(n_probe):
+            L = layers[i % n_layers]
+            g = geo
+            pk.pikv_route(L.t["q"], L.t["W_r"], L.t["bias"], g.route_rows, g.d_r, g.E, g.k,
+                          shared["topk"], shared["gates"], None)
+            ev[i][0].record(stream)
+            L.attend()
+            ev[i][1].record(stream)
+        stream.synchronize()
+        attn_ms = sorted(a.elapsed_time(b) for a, b in ev)
+        attn_avg_ms = sum(attn_ms) / len(attn_ms)
+
+    ms_per_step = elapsed * 1e3 / K
+    qps = geo.B * K / elapsed
+    n_mean = float(torch.stack([L.t["n_valid"].float().mean() for L in layers]).mean().item())
+    kv_bytes = geo.kv_bytes_per_step(n_mean)
+    achieved = kv_bytes / (attn_avg_ms * 1e-3) / 1e9
+    out = {
+        "metric": "routed sharded-KV decode queries/sec", "value": qps, "unit": "queries/s",
+        "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if geo.dtype == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": args.config, "B": geo.B, "Hq": geo.Hq, "Hkv": geo.Hkv, "D": geo.D,
+                   "E": geo.E, "S": geo.S, "k": geo.k, "rank": geo.rank, "layers_cycled": n_layers,
+                   "launch": args.mode,
+                   "step": "route+evict1+append+attend+utility"},
+        "step_effective_GBps": kv_bytes / (ms_per_step * 1e-3) / 1e9,
+        "step_frac_of_hbm_peak": kv_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "roofline": {"bound": "hbm", "kernel": "pikv_sharded_attn (attn_partial + attn_combine)",
+                     "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "bytes_per_launch": kv_bytes, "avg_ms": attn_avg_ms,
+                     "median_ms": attn_ms[len(attn_ms) // 2], "timed_with": "HIP events, eager launches"},
+    }
+    if not args.no_cpu and args.cpu_steps != 0:
+        n_cpu = args.cpu_steps if args.cpu_steps > 0 else min(n_layers, 8)
+        per_step, n_done = cpu_baseline(torch, wl, layers, n_cpu)
+        out["cpu_baseline"] = {"value": geo.B / per_step, "unit": "queries/s",
+                               "cores": int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1)),
+                               "kind": "oracle",
+                               "sample": "%d steps (layer instances) of %s: route+attend+utility, "
+                                         "selected shards copied to host" % (n_done, args.config)}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
