@@ -166,6 +166,12 @@ int pikv_append(const pikv_desc *desc, const void *K_new, const void *V_new,
                 const int32_t *reuse_cnt, int32_t max_evict, void *const *K_shards,
                 void *const *V_shards, float *utility, int32_t *n_valid, void *stream);
 
+/* Tuning hook: force the number of row-range splits per (head group, selected shard) used
+ * by pikv_sharded_attn and pikv_attn_workspace_bytes (process-wide; 0 restores the built-in
+ * choice of one round of resident blocks).  Change it only between calls, and size the
+ * workspace after changing it.                                                             */
+void pikv_set_attn_split(int32_t nsplit);
+
 /* Static description of a status code (host string, never NULL).                          */
 const char *pikv_strerror(int status);
 

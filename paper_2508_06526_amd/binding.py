@@ -16,7 +16,7 @@ F32, BF16 = 0, 1
 COMBINE_LSE, COMBINE_LOCAL = 0, 1
 
 EXPORTS = ("pikv_route", "pikv_attn_workspace_bytes", "pikv_sharded_attn", "pikv_update_utility",
-           "pikv_evict", "pikv_append", "pikv_strerror", "pikv_version")
+           "pikv_evict", "pikv_append", "pikv_strerror", "pikv_version", "pikv_set_attn_split")
 
 
 class PikvError(RuntimeError):
@@ -69,6 +69,8 @@ def load_library():
     lib.pikv_append.restype = C.c_int
     lib.pikv_strerror.argtypes = [C.c_int]
     lib.pikv_strerror.restype = C.c_char_p
+    lib.pikv_set_attn_split.argtypes = [i32]
+    lib.pikv_set_attn_split.restype = None
     lib.pikv_version.argtypes = []
     lib.pikv_version.restype = C.c_int
     _lib = lib
@@ -141,6 +143,10 @@ def pikv_strerror(status: int) -> str:
 
 def pikv_version() -> int:
     return load_library().pikv_version()
+
+
+def pikv_set_attn_split(nsplit: int) -> None:
+    load_library().pikv_set_attn_split(int(nsplit))
 
 
 def pikv_route(x, W_r, bias, rows, d_r, E, k, topk_idx, gates, probs=None, stream=None):

@@ -93,6 +93,30 @@ __global__ __launch_bounds__(kWavesPerBlock *kWave) void attn_partial(AttnParams
         return;
     }
 
+    const int64_t shard = (int64_t)b * p.E + e;
+    const T *Kb = static_cast<const T *>(p.K[shard]) + (int64_t)hk * p.stride_h + c * EPL;
+    const T *Vb = static_cast<const T *>(p.V[shard]) + (int64_t)hk * p.stride_h + c * EPL;
+
+    // A wave owns tiles t0, t0 + 4*TILE, ... of the block's row range.  The loads of a tile
+    // are issued one phase ahead of their use (K of the next tile while the softmax of this
+    // one runs, V of the next tile after this tile's PV), so every wave always has 8 KiB in
+    // flight; the first tile's loads go out before the query is staged.
+    uint4 kr[NL], vr[NL];
+    auto load_tile = [&](uint4(&dst)[NL], const T *base, int t0) {
+#pragma unroll
+        for (int t = 0; t < NL; ++t) {
+            // rows past the end are clamped onto the last valid row (always in bounds) and
+            // masked out of the softmax below, so the loads need no branches
+            const int row = min(t0 + t * RPL + r, r1 - 1);
+            dst[t] = load16_stream(base + (int64_t)row * p.stride_s);
+        }
+    };
+    int t0 = r0 + wave * TILE;
+    if (t0 < r1) {
+        load_tile(kr, Kb, t0);
+        load_tile(vr, Vb, t0);
+    }
+
     // Stage the (scaled) query in LDS; for rank-r codes it is the projected query U_K q.
     const T *qp = static_cast<const T *>(p.q) + ((int64_t)b * p.Hq + h0) * p.D;
     if (p.rank == 0) {
@@ -126,22 +150,8 @@ __global__ __launch_bounds__(kWavesPerBlock *kWave) void attn_partial(AttnParams
         for (int i = 0; i < EPL; ++i) acc[g][i] = 0.0f;
     }
 
-    const int64_t shard = (int64_t)b * p.E + e;
-    const T *Kb = static_cast<const T *>(p.K[shard]) + (int64_t)hk * p.stride_h + c * EPL;
-    const T *Vb = static_cast<const T *>(p.V[shard]) + (int64_t)hk * p.stride_h + c * EPL;
-
-    for (int t0 = r0 + wave * TILE; t0 < r1; t0 += kWavesPerBlock * TILE) {
-        uint4 kr[NL], vr[NL];
-#pragma unroll
-        for (int t = 0; t < NL; ++t) {
-            const int row = t0 + t * RPL + r;
-            kr[t] = row < r1 ? load16(Kb + (int64_t)row * p.stride_s) : make_uint4(0, 0, 0, 0);
-        }
-#pragma unroll
-        for (int t = 0; t < NL; ++t) {
-            const int row = t0 + t * RPL + r;
-            vr[t] = row < r1 ? load16(Vb + (int64_t)row * p.stride_s) : make_uint4(0, 0, 0, 0);
-        }
+    for (; t0 < r1; t0 += kWavesPerBlock * TILE) {
+        const int tnext = t0 + kWavesPerBlock * TILE;
 
         // scores: each lane's partial dot over its EPL columns, summed over the row's lanes
         float s[NL][GB];
@@ -159,6 +169,7 @@ __global__ __launch_bounds__(kWavesPerBlock *kWave) void attn_partial(AttnParams
                 s[t][g] = valid ? d : -INFINITY;
             }
         }
+        if (tnext < r1) load_tile(kr, Kb, tnext);
 
         if (p.scores != nullptr) {  // raw scores for the utility pass, one row per lane
 #pragma unroll
@@ -206,6 +217,7 @@ __global__ __launch_bounds__(kWavesPerBlock *kWave) void attn_partial(AttnParams
 #pragma unroll
                 for (int i = 0; i < EPL; ++i) acc[g][i] = fmaf(s[t][g], vf[i], acc[g][i]);
         }
+        if (tnext < r1) load_tile(vr, Vb, tnext);
     }
 
     // merge the row groups of the wave (same column chunk c, different r) ...
@@ -266,39 +278,51 @@ struct CombineParams {
     int Hq, G, D, W, k, rr, rank, nsplit, combine;
 };
 
-constexpr int kCombineThreads = 128;
+constexpr int kCombineThreads = 256;
 constexpr int kMaxPartialsPerHead = 2048;   // k * nsplit
 
+// One block per (sequence, query head).  Phase 1: every partial's (max, sum) into LDS and,
+// one wave per selected shard, the shard's max and normaliser.  Phase 2 (one thread): the
+// k gate-weighted shard weights in either combine mode.  Phase 3: the weighted sum of the
+// partial accumulators, threads laid out as (slice of partials) x (float4 column group) so
+// that every load is a contiguous run of a partial's row.
 template <typename T>
 __global__ __launch_bounds__(kCombineThreads) void attn_combine(CombineParams p) {
     const int bh = blockIdx.x;
     const int b = bh / p.Hq, h = bh - b * p.Hq;
     const int hk = h / p.G;
     const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1), wave = tid >> 6;
     const int np = p.k * p.nsplit;
 
-    __shared__ float wt[kMaxPartialsPerHead];   // (max, then weight) of every partial
+    __shared__ float wt[kMaxPartialsPerHead];   // max of every partial, later its weight
     __shared__ float ls[kMaxPartialsPerHead];
     __shared__ float Mj[64], Zj[64], shard_w[64];
+    __shared__ float4 red[kCombineThreads];
     __shared__ float ycode[128];
-    __shared__ float stat[2];
 
     const float *ml = p.part_ml + (int64_t)bh * np * 2;
-    for (int i = tid; i < np; i += blockDim.x) {
-        wt[i] = ml[2 * i];
-        ls[i] = ml[2 * i + 1];
+    for (int i = tid; i < np; i += kCombineThreads) {
+        const float2 v = *reinterpret_cast<const float2 *>(ml + 2 * i);
+        wt[i] = v.x;
+        ls[i] = v.y;
     }
     __syncthreads();
-    if (tid < p.k) {  // per selected shard: max and sum over its splits
-        const int j = tid;
+    for (int j = wave; j < p.k; j += kCombineThreads / kWave) {
         float M = -INFINITY;
-        for (int s = 0; s < p.nsplit; ++s)
+        for (int s = lane; s < p.nsplit; s += kWave)
             if (ls[j * p.nsplit + s] > 0.0f) M = fmaxf(M, wt[j * p.nsplit + s]);
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) M = fmaxf(M, __shfl_xor(M, off, kWave));
         float Z = 0.0f;
-        for (int s = 0; s < p.nsplit; ++s)
+        for (int s = lane; s < p.nsplit; s += kWave)
             if (ls[j * p.nsplit + s] > 0.0f) Z += ls[j * p.nsplit + s] * __expf(wt[j * p.nsplit + s] - M);
-        Mj[j] = M;
-        Zj[j] = Z;
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) Z += __shfl_xor(Z, off, kWave);
+        if (lane == 0) {
+            Mj[j] = M;
+            Zj[j] = Z;
+        }
     }
     __syncthreads();
     if (tid == 0) {
@@ -332,37 +356,58 @@ __global__ __launch_bounds__(kCombineThreads) void attn_combine(CombineParams p)
                 }
             }
         }
-        stat[0] = M;
-        stat[1] = norm;
         if (p.row_max) p.row_max[bh] = M;
         if (p.row_norm) p.row_norm[bh] = norm;
     }
     __syncthreads();
     // weight of every partial: shard weight * exp(m_split - M_shard)
-    for (int i = tid; i < np; i += blockDim.x) {
+    for (int i = tid; i < np; i += kCombineThreads) {
         const int j = i / p.nsplit;
         wt[i] = ls[i] > 0.0f ? shard_w[j] * __expf(wt[i] - Mj[j]) : 0.0f;
     }
     __syncthreads();
 
-    const float *acc = p.part_acc + (int64_t)bh * np * p.W;
-    if (tid < p.W) {
-        float a = 0.0f;
-        for (int i = 0; i < np; ++i)
-            if (wt[i] != 0.0f) a = fmaf(wt[i], acc[(int64_t)i * p.W + tid], a);
-        if (p.rank == 0)
-            p.y[(int64_t)bh * p.D + tid] = a;
-        else
-            ycode[tid] = a;
+    const int cgroups = p.W / 4;                       // float4 column groups: 4..32
+    const int slices = kCombineThreads / cgroups;      // partial slices: 64..8
+    const int cg = tid % cgroups, sl = tid / cgroups;
+    const float *acc = p.part_acc + (int64_t)bh * np * p.W + cg * 4;
+    float4 a = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int i = sl; i < np; i += slices) {
+        const float w = wt[i];
+        const float4 v = *reinterpret_cast<const float4 *>(acc + (int64_t)i * p.W);
+        a.x = fmaf(w, v.x, a.x);
+        a.y = fmaf(w, v.y, a.y);
+        a.z = fmaf(w, v.z, a.z);
+        a.w = fmaf(w, v.w, a.w);
+    }
+    red[tid] = a;
+    __syncthreads();
+    if (tid < cgroups) {
+        float4 t = red[tid];
+        for (int s2 = 1; s2 < slices; ++s2) {
+            const float4 v = red[s2 * cgroups + tid];
+            t.x += v.x;
+            t.y += v.y;
+            t.z += v.z;
+            t.w += v.w;
+        }
+        if (p.rank == 0) {
+            *reinterpret_cast<float4 *>(p.y + (int64_t)bh * p.D + tid * 4) = t;
+        } else {
+            ycode[tid * 4 + 0] = t.x;
+            ycode[tid * 4 + 1] = t.y;
+            ycode[tid * 4 + 2] = t.z;
+            ycode[tid * 4 + 3] = t.w;
+        }
     }
     if (p.rank != 0) {  // value decoder: y = ycode U_V[h']
         __syncthreads();
         const T *U = static_cast<const T *>(p.U_V) + (int64_t)hk * p.rank * p.D;
-        for (int d = tid; d < p.D; d += blockDim.x) {
-            float a = 0.0f;
+        for (int d = tid; d < p.D; d += kCombineThreads) {
+            float a2 = 0.0f;
             for (int cidx = 0; cidx < p.rank; ++cidx)
-                a = fmaf(ycode[cidx], load_scalar<T>(U, (int64_t)cidx * p.D + d), a);
-            p.y[(int64_t)bh * p.D + d] = a;
+                a2 = fmaf(ycode[cidx], load_scalar<T>(U, (int64_t)cidx * p.D + d), a2);
+            p.y[(int64_t)bh * p.D + d] = a2;
         }
     }
 }
@@ -393,6 +438,9 @@ int launch_partial(int width, int gb, const AttnParams &p, int blocks, hipStream
 
 }  // namespace
 
+static int g_split_override = 0;   // tuning hook, see pikv_set_attn_split
+void g_split_override_set(int v) { g_split_override = v > 0 ? v : 0; }
+
 int make_attn_plan(const pikv_desc *d, int k, AttnPlan *plan) {
     const int rc = check_desc(d);
     if (rc != PIKV_OK) return rc;
@@ -405,16 +453,20 @@ int make_attn_plan(const pikv_desc *d, int k, AttnPlan *plan) {
     const int lpr = W / epl;
     if (lpr < 1 || lpr > 32) return PIKV_ERR_UNSUPPORTED;
     const int tile = (kWave / lpr) * kLoadsPerTile;
-    const int granule = kWavesPerBlock * tile;
     const int64_t units = (int64_t)d->B * (d->Hq / gb) * k;
-    const int64_t target_blocks = 2048;
-    int64_t nsplit = units > 0 ? (target_blocks + units - 1) / units : 1;
-    const int64_t max_split = (d->S + granule - 1) / granule;
+    // One round of resident blocks: 256 CUs times the 4-wave blocks a CU holds at this
+    // kernel's register footprint.  Fewer, longer blocks keep the per-wave prefetch chain
+    // busy and shrink the partials that the combine pass has to merge.
+    const int resident = gb >= 8 ? 2 : (gb >= 4 ? 3 : 4);
+    const int64_t target_blocks = 256 * resident;
+    int64_t nsplit = units > 0 ? target_blocks / units : 1;
+    if (g_split_override > 0) nsplit = g_split_override;
+    const int64_t max_split = (d->S + tile - 1) / tile;
     if (nsplit > max_split) nsplit = max_split;
     if (nsplit > kMaxPartialsPerHead / k) nsplit = kMaxPartialsPerHead / k;
     if (nsplit < 1) nsplit = 1;
     int chunk = (int)((d->S + nsplit - 1) / nsplit);
-    chunk = (chunk + granule - 1) / granule * granule;
+    chunk = (chunk + tile - 1) / tile * tile;
     nsplit = (d->S + chunk - 1) / chunk;
     plan->heads_per_block = gb;
     plan->head_blocks = d->Hq / gb;
@@ -429,6 +481,8 @@ int make_attn_plan(const pikv_desc *d, int k, AttnPlan *plan) {
 }  // namespace pikv
 
 using namespace pikv;
+
+extern "C" void pikv_set_attn_split(int32_t nsplit) { pikv::g_split_override_set(nsplit); }
 
 extern "C" size_t pikv_attn_workspace_bytes(const pikv_desc *desc, int32_t k) {
     AttnPlan plan;

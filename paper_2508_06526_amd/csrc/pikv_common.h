@@ -102,6 +102,17 @@ __device__ __forceinline__ uint4 load16(const void *p) {
     return *reinterpret_cast<const uint4 *>(p);
 }
 
+// 16-byte load of data that is read exactly once (the K/V stream): the non-temporal hint
+// keeps it from displacing reusable lines in L2 / Infinity Cache.
+// The pointer is known to be device (global) memory, which lets the compiler emit
+// global_load instead of a flat load.
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+typedef const u32x4_t __attribute__((address_space(1))) *global_u32x4_ptr;
+__device__ __forceinline__ uint4 load16_stream(const void *p) {
+    const u32x4_t v = __builtin_nontemporal_load((global_u32x4_ptr)(uintptr_t)p);
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+
 inline hipStream_t as_stream(void *s) { return reinterpret_cast<hipStream_t>(s); }
 
 inline int launch_status() { return hipGetLastError() == hipSuccess ? PIKV_OK : PIKV_ERR_HIP; }
@@ -116,11 +127,12 @@ struct AttnPlan {
     int heads_per_block;  // query heads sharing one K/V stream (1, 2, 4 or 8)
     int head_blocks;      // Hq / heads_per_block
     int tile_rows;        // rows one wave consumes per iteration
-    int chunk;            // rows per split (multiple of 4 * tile_rows)
+    int chunk;            // rows per split (multiple of tile_rows)
     int nsplit;
     size_t acc_floats;    // B*Hq*k*nsplit*width
     size_t ml_floats;     // B*Hq*k*nsplit*2
 };
 int make_attn_plan(const pikv_desc *d, int k, AttnPlan *plan);
+void g_split_override_set(int v);
 
 }  // namespace pikv

@@ -81,6 +81,44 @@ __global__ __launch_bounds__(kEvictThreads) void evict_select(EvictParams p) {
     }
     float *u = p.utility + (int64_t)be * p.S;
 
+    if (ngone == 1 && !p.compact) {
+        // Streaming case: drop the single worst entry = minimum of (key, then largest slot).
+        // One composite 64-bit value per entry orders both at once.
+        uint64_t best = ~0ull;
+        const int n4 = (p.S % 4 == 0) ? (n / 4) * 4 : 0;   // float4 reads need aligned rows
+        for (int i = tid * 4; i < n4; i += kEvictThreads * 4) {
+            const float4 v = *reinterpret_cast<const float4 *>(u + i);
+            const uint64_t c0 = ((uint64_t)order_key(v.x) << 32) | (uint32_t)(0x7fffffff - i);
+            const uint64_t c1 = ((uint64_t)order_key(v.y) << 32) | (uint32_t)(0x7fffffff - (i + 1));
+            const uint64_t c2 = ((uint64_t)order_key(v.z) << 32) | (uint32_t)(0x7fffffff - (i + 2));
+            const uint64_t c3 = ((uint64_t)order_key(v.w) << 32) | (uint32_t)(0x7fffffff - (i + 3));
+            const uint64_t a = c0 < c1 ? c0 : c1, b2 = c2 < c3 ? c2 : c3;
+            const uint64_t c = a < b2 ? a : b2;
+            best = c < best ? c : best;
+        }
+        for (int i = n4 + tid; i < n; i += kEvictThreads) {
+            const uint64_t c = ((uint64_t)order_key(u[i]) << 32) | (uint32_t)(0x7fffffff - i);
+            best = c < best ? c : best;
+        }
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) {
+            const uint64_t o = __shfl_xor(best, off, kWave);
+            best = o < best ? o : best;
+        }
+        __shared__ uint64_t wave_best[kEvictThreads / kWave];
+        if ((tid & (kWave - 1)) == 0) wave_best[tid >> 6] = best;
+        __syncthreads();
+        if (tid == 0) {
+            uint64_t m = wave_best[0];
+#pragma unroll
+            for (int w = 1; w < kEvictThreads / kWave; ++w) m = wave_best[w] < m ? wave_best[w] : m;
+            p.evicted_idx[(int64_t)be * p.max_evict] = 0x7fffffff - (int)(uint32_t)(m & 0xffffffffu);
+            p.evicted_cnt[be] = 1;
+            p.n_valid[be] = p.capacity;
+        }
+        return;
+    }
+
     // radix select: value of the ngone-th smallest key
     uint32_t prefix = 0, mask = 0;
     int remaining = ngone;   // rank still to locate among the keys matching `prefix`

@@ -13,9 +13,8 @@
 namespace pikv {
 namespace {
 
-constexpr int kUtilThreads = 256;
-constexpr int kUtilSlotsPerThread = 4;
-constexpr int kUtilTile = kUtilThreads * kUtilSlotsPerThread;
+constexpr int kUtilThreads = 256;   // one slot per thread: a wave reads 256 contiguous bytes
+constexpr int kUtilTile = kUtilThreads;
 
 struct UtilParams {
     const float *scores;
@@ -37,54 +36,57 @@ __global__ __launch_bounds__(kUtilThreads) void utility_kernel(UtilParams p) {
     const int i0 = tile * kUtilTile;
     if (i0 >= n) return;
 
-    __shared__ int head_j[256];       // position of expert e in head h's selection, or -1
+    // heads that selected expert e, compacted in ascending head order (fixed summation order)
+    __shared__ int head_off[256];       // offset of the head's score row for this shard
     __shared__ float head_shift[256];
     __shared__ float head_coef[256];
-    __shared__ int any_head;
+    __shared__ int wave_cnt[kUtilThreads / kWave];
     const int tid = threadIdx.x;
-    if (tid == 0) any_head = 0;
-    __syncthreads();
-    for (int h = tid; h < p.Hq; h += blockDim.x) {
-        const int row = b * p.rr + (p.rr == 1 ? 0 : h);
-        int jj = -1;
+    const int lane = tid & (kWave - 1), wave = tid >> 6;
+
+    int jj = -1;
+    if (tid < p.Hq) {
+        const int row = b * p.rr + (p.rr == 1 ? 0 : tid);
         for (int j = 0; j < p.k; ++j)
             if (p.topk[(int64_t)row * p.k + j] == e) jj = j;
-        head_j[h] = jj;
-        if (jj >= 0) {
-            const float *sc = p.slot_coef + (((int64_t)b * p.Hq + h) * p.k + jj) * 2;
-            head_shift[h] = sc[0];
-            head_coef[h] = sc[1];
-            any_head = 1;
-        }
+    }
+    const uint64_t mask = __ballot(jj >= 0);
+    if (lane == 0) wave_cnt[wave] = __popcll(mask);
+    __syncthreads();
+    int before = 0, nact = 0;
+#pragma unroll
+    for (int w = 0; w < kUtilThreads / kWave; ++w) {
+        if (w < wave) before += wave_cnt[w];
+        nact += wave_cnt[w];
+    }
+    if (nact == 0) return;
+    if (jj >= 0) {
+        const int pos = before + __popcll(mask & ((1ull << lane) - 1ull));
+        const int hrow = (b * p.Hq + tid) * p.k + jj;
+        head_off[pos] = hrow;
+        head_shift[pos] = p.slot_coef[(int64_t)hrow * 2 + 0];
+        head_coef[pos] = p.slot_coef[(int64_t)hrow * 2 + 1];
     }
     __syncthreads();
-    if (!any_head) return;
 
-    const int i = i0 + tid * kUtilSlotsPerThread;
+    const int i = i0 + tid;
     if (i >= n) return;
-    float a[kUtilSlotsPerThread] = {0.0f, 0.0f, 0.0f, 0.0f};
-    const bool full = (i + kUtilSlotsPerThread <= n) && (p.S % kUtilSlotsPerThread == 0);
-    for (int h = 0; h < p.Hq; ++h) {
-        const int jj = head_j[h];
-        if (jj < 0) continue;
-        const float shift = head_shift[h], coef = head_coef[h];
-        const float *s = p.scores + (((int64_t)b * p.Hq + h) * p.k + jj) * p.S + i;
-        if (full) {
-            const float4 v = *reinterpret_cast<const float4 *>(s);
-            a[0] += coef * __expf(v.x - shift);
-            a[1] += coef * __expf(v.y - shift);
-            a[2] += coef * __expf(v.z - shift);
-            a[3] += coef * __expf(v.w - shift);
-        } else {
-#pragma unroll
-            for (int t = 0; t < kUtilSlotsPerThread; ++t)
-                if (i + t < n) a[t] += coef * __expf(s[t] - shift);
-        }
+    float a = 0.0f;
+    int t = 0;
+    for (; t + 4 <= nact; t += 4) {   // four independent loads in flight per thread
+        const float s0 = p.scores[(int64_t)head_off[t + 0] * p.S + i];
+        const float s1 = p.scores[(int64_t)head_off[t + 1] * p.S + i];
+        const float s2 = p.scores[(int64_t)head_off[t + 2] * p.S + i];
+        const float s3 = p.scores[(int64_t)head_off[t + 3] * p.S + i];
+        a += head_coef[t + 0] * __expf(s0 - head_shift[t + 0]);
+        a += head_coef[t + 1] * __expf(s1 - head_shift[t + 1]);
+        a += head_coef[t + 2] * __expf(s2 - head_shift[t + 2]);
+        a += head_coef[t + 3] * __expf(s3 - head_shift[t + 3]);
     }
+    for (; t < nact; ++t)
+        a += head_coef[t] * __expf(p.scores[(int64_t)head_off[t] * p.S + i] - head_shift[t]);
     float *u = p.utility + ((int64_t)b * p.E + e) * p.S + i;
-#pragma unroll
-    for (int t = 0; t < kUtilSlotsPerThread; ++t)
-        if (i + t < n) u[t] = fmaf(p.decay, u[t], a[t]);
+    *u = fmaf(p.decay, *u, a);
 }
 
 }  // namespace
