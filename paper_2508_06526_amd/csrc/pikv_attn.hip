@@ -266,6 +266,284 @@ __global__ __launch_bounds__(kWavesPerBlock *kWave) void attn_partial(AttnParams
     }
 }
 
+// ---------------------------------------------------------------------------------------
+// Grouped-query variant on the matrix cores (bf16 rows of 128 values, one routing decision
+// per token, 2..16 query heads per kv head).  With G query heads sharing every K/V byte the
+// plain-ALU kernel above spends ~G times more instructions per byte and stops being
+// memory-bound; here the G heads (padded to 16) form the second dimension of 16x16x32 bf16
+// MFMA tiles, so the instruction count per byte no longer depends on G.
+//
+// Per wave and per tile of 32 entries:
+//   * K and V rows arrive with the same coalesced 16-byte lane loads as above; lane
+//     (r = lane/16, c = lane%16) takes rows 8r..8r+7 and byte chunk c of each.
+//   * scores, transposed: S^T[entry][head] = K . Q^T.  The MFMA wants lane%16 to index the
+//     entry, so the K registers make one trip through a padded wave-private LDS tile
+//     (write row-major, read one entry per lane); Q sits in registers as the other operand.
+//     Result: lane (head c, group r) holds 8 entries of head c - the softmax is lane-local
+//     except for two cross-group steps.
+//   * probabilities go back through LDS (as a bf16 high part plus a bf16 residual, so the
+//     product is exact to ~2^-17) into the row-operand layout: lane (head c, group r) gets
+//     P[head c][entries 8r..8r+7].
+//   * output: O[head][d] += P . V.  V needs no transpose at all: for output column set i the
+//     column operand of lane (c, r) is V[entries 8r..8r+7][d = 8c + i], i.e. the i-th value
+//     of each of its own 8 loaded rows, packed by byte-permutes.
+constexpr int kGqaTile = 32;
+constexpr int kGqaKPitch = 272;   // bytes per staged K row: 256 + 16 keeps b128 reads conflict-free
+constexpr int kGqaPPitch = 80;    // bytes per staged P row (32 bf16 + 16 pad)
+
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ void wave_lds_order() {
+    // LDS operations of one wave execute in order; this only stops the compiler from moving
+    // them across the point where another lane's data is expected.
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+__global__ __launch_bounds__(kWavesPerBlock *kWave) void attn_partial_gqa128(AttnParams p) {
+    constexpr int W = 128;
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1);
+    const int wave = tid >> 6;
+    const int c = lane & 15;
+    const int r = lane >> 4;
+    const int gb = p.G;                       // heads per block = the whole query group
+
+    int bid = blockIdx.x;
+    const int split = bid % p.nsplit;
+    bid /= p.nsplit;
+    const int j = bid % p.k;
+    bid /= p.k;
+    const int hgroups = p.Hq / gb;
+    const int hk = bid % hgroups;
+    const int b = bid / hgroups;
+    const int h0 = hk * gb;
+    const int e = p.topk[(int64_t)b * p.k + j];
+    const int n = p.n_valid[(int64_t)b * p.E + e];
+    const int r0 = split * p.chunk;
+    const int r1 = min(n, r0 + p.chunk);
+
+    __shared__ __attribute__((aligned(16))) unsigned char lds_k[kWavesPerBlock][kGqaTile * kGqaKPitch];
+    __shared__ __attribute__((aligned(16))) unsigned char lds_p[kWavesPerBlock][2][16 * kGqaPPitch];
+    __shared__ __attribute__((aligned(16))) float lds_corr[kWavesPerBlock][16];
+    __shared__ float sm_m[kWavesPerBlock][16];
+    __shared__ float sm_l[kWavesPerBlock][16];
+
+    const int64_t part_base = (((int64_t)b * p.Hq + h0) * p.k + j) * p.nsplit + split;
+    const int64_t part_head_stride = (int64_t)p.k * p.nsplit;
+
+    if (r0 >= r1) {
+        for (int idx = tid; idx < gb * W; idx += blockDim.x) {
+            const int g = idx / W, d = idx - g * W;
+            p.part_acc[(part_base + g * part_head_stride) * W + d] = 0.0f;
+            if (d == 0) {
+                p.part_ml[(part_base + g * part_head_stride) * 2 + 0] = -INFINITY;
+                p.part_ml[(part_base + g * part_head_stride) * 2 + 1] = 0.0f;
+            }
+        }
+        return;
+    }
+
+    const int64_t shard = (int64_t)b * p.E + e;
+    const bf16 *Kb = static_cast<const bf16 *>(p.K[shard]) + (int64_t)hk * p.stride_h + c * 8;
+    const bf16 *Vb = static_cast<const bf16 *>(p.V[shard]) + (int64_t)hk * p.stride_h + c * 8;
+
+    uint4 kr[8], vr[8];
+    auto load_tile = [&](uint4(&dst)[8], const bf16 *base, int t0) {
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+            const int row = min(t0 + 8 * r + t, r1 - 1);   // clamped rows are masked below
+            dst[t] = load16_stream(base + (int64_t)row * p.stride_s);
+        }
+    };
+    int t0 = r0 + wave * kGqaTile;
+    if (t0 < r1) {
+        load_tile(kr, Kb, t0);
+        load_tile(vr, Vb, t0);
+    }
+
+    // query operand: lane (head c, group r) holds Q[h0 + c][32 s + 8 r .. +7], s = 0..3
+    bf16x8_t qop[4];
+    {
+        const bf16 *qrow = static_cast<const bf16 *>(p.q) + ((int64_t)b * p.Hq + h0 + min(c, gb - 1)) * W;
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            uint4 v = load16(qrow + 32 * s + 8 * r);
+            if (c >= gb) v = make_uint4(0, 0, 0, 0);
+            qop[s] = __builtin_bit_cast(bf16x8_t, v);
+        }
+    }
+
+    float m = -INFINITY, lsum = 0.0f;      // running max / partial sum of head c
+    f32x4_t oacc[8];                        // oacc[i][x] = O[head 4r + x][d = 8c + i]
+#pragma unroll
+    for (int i = 0; i < 8; ++i) oacc[i] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+
+    unsigned char *kst = lds_k[wave];
+    unsigned char *pst_hi = lds_p[wave][0];
+    unsigned char *pst_lo = lds_p[wave][1];
+
+    for (; t0 < r1; t0 += kWavesPerBlock * kGqaTile) {
+        const int tnext = t0 + kWavesPerBlock * kGqaTile;
+
+        // K rows -> LDS (row-major, padded), then the next tile's K loads reuse the registers
+#pragma unroll
+        for (int t = 0; t < 8; ++t)
+            *reinterpret_cast<uint4 *>(kst + (8 * r + t) * kGqaKPitch + 16 * c) = kr[t];
+        if (tnext < r1) load_tile(kr, Kb, tnext);
+        wave_lds_order();
+
+        // S^T = K Q^T for the two 16-entry halves of the tile
+        f32x4_t sc[2];
+#pragma unroll
+        for (int hb = 0; hb < 2; ++hb) {
+            sc[hb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                const uint4 a = *reinterpret_cast<const uint4 *>(kst + (16 * hb + c) * kGqaKPitch + 64 * s + 16 * r);
+                sc[hb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a), qop[s],
+                                                                sc[hb], 0, 0, 0);
+            }
+        }
+        // lane (head c, group r): sc[hb][x] is the score of entry t0 + 16 hb + 4 r + x
+        float sv[8];
+#pragma unroll
+        for (int hb = 0; hb < 2; ++hb)
+#pragma unroll
+            for (int x = 0; x < 4; ++x) {
+                const int row = t0 + 16 * hb + 4 * r + x;
+                sv[hb * 4 + x] = row < r1 ? sc[hb][x] * p.scale : -INFINITY;
+            }
+        if (p.scores != nullptr && c < gb) {
+            float *dst = p.scores + (((int64_t)b * p.Hq + h0 + c) * p.k + j) * p.S + t0 + 4 * r;
+#pragma unroll
+            for (int hb = 0; hb < 2; ++hb) {
+                const int row = t0 + 16 * hb + 4 * r;
+                if (row + 4 <= r1 && (p.S & 3) == 0) {
+                    *reinterpret_cast<float4 *>(dst + 16 * hb) =
+                        make_float4(sv[hb * 4], sv[hb * 4 + 1], sv[hb * 4 + 2], sv[hb * 4 + 3]);
+                } else {
+#pragma unroll
+                    for (int x = 0; x < 4; ++x)
+                        if (row + x < r1) dst[16 * hb + x] = sv[hb * 4 + x];
+                }
+            }
+        }
+
+        // online softmax for head c (entries are spread over the 4 lane groups)
+        float tm = sv[0];
+#pragma unroll
+        for (int x = 1; x < 8; ++x) tm = fmaxf(tm, sv[x]);
+        tm = fmaxf(tm, __shfl_xor(tm, 16, kWave));
+        tm = fmaxf(tm, __shfl_xor(tm, 32, kWave));
+        const float mn = fmaxf(m, tm);
+        const float corr = __expf(m - mn);
+        m = mn;
+        lsum *= corr;
+        float pv[8];
+#pragma unroll
+        for (int x = 0; x < 8; ++x) {
+            pv[x] = __expf(sv[x] - mn);
+            lsum += pv[x];
+        }
+        // probabilities as bf16 high part + bf16 residual, 4 consecutive entries per store
+#pragma unroll
+        for (int hb = 0; hb < 2; ++hb) {
+            uint32_t hi2[2], lo2[2];
+#pragma unroll
+            for (int q2 = 0; q2 < 2; ++q2) {
+                const f32x2_t v = {pv[hb * 4 + 2 * q2], pv[hb * 4 + 2 * q2 + 1]};
+                const bf16x2_t hi = __builtin_convertvector(v, bf16x2_t);
+                const f32x2_t back = {(float)hi[0], (float)hi[1]};
+                const bf16x2_t lo = __builtin_convertvector(v - back, bf16x2_t);
+                hi2[q2] = __builtin_bit_cast(uint32_t, hi);
+                lo2[q2] = __builtin_bit_cast(uint32_t, lo);
+            }
+            const int off = c * kGqaPPitch + (16 * hb + 4 * r) * 2;
+            *reinterpret_cast<uint2 *>(pst_hi + off) = make_uint2(hi2[0], hi2[1]);
+            *reinterpret_cast<uint2 *>(pst_lo + off) = make_uint2(lo2[0], lo2[1]);
+        }
+        if (r == 0) lds_corr[wave][c] = corr;
+        wave_lds_order();
+
+        // row operands P[head c][entries 8r..8r+7] and the rescale factors of heads 4r..4r+3
+        const bf16x8_t p_hi = __builtin_bit_cast(
+            bf16x8_t, *reinterpret_cast<const uint4 *>(pst_hi + c * kGqaPPitch + 16 * r));
+        const bf16x8_t p_lo = __builtin_bit_cast(
+            bf16x8_t, *reinterpret_cast<const uint4 *>(pst_lo + c * kGqaPPitch + 16 * r));
+        const float4 cr = *reinterpret_cast<const float4 *>(&lds_corr[wave][4 * r]);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            oacc[i][0] *= cr.x;
+            oacc[i][1] *= cr.y;
+            oacc[i][2] *= cr.z;
+            oacc[i][3] *= cr.w;
+        }
+        // O += P V, output column set i takes the i-th value of each of the lane's 8 V rows
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const uint32_t sel = (i & 1) ? 0x07060302u : 0x05040100u;
+            uint32_t w[8];
+#pragma unroll
+            for (int t = 0; t < 8; ++t) {
+                const uint4 &v = vr[t];
+                w[t] = (i >> 1) == 0 ? v.x : (i >> 1) == 1 ? v.y : (i >> 1) == 2 ? v.z : v.w;
+            }
+            const uint4 packed = make_uint4(__builtin_amdgcn_perm(w[1], w[0], sel),
+                                            __builtin_amdgcn_perm(w[3], w[2], sel),
+                                            __builtin_amdgcn_perm(w[5], w[4], sel),
+                                            __builtin_amdgcn_perm(w[7], w[6], sel));
+            const bf16x8_t vop = __builtin_bit_cast(bf16x8_t, packed);
+            oacc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(p_hi, vop, oacc[i], 0, 0, 0);
+            oacc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(p_lo, vop, oacc[i], 0, 0, 0);
+        }
+        if (tnext < r1) load_tile(vr, Vb, tnext);
+        wave_lds_order();
+    }
+
+    // wave result -> LDS (the wave's own K staging area is free now), then merge the waves
+    lsum += __shfl_xor(lsum, 16, kWave);
+    lsum += __shfl_xor(lsum, 32, kWave);
+    float *wacc = reinterpret_cast<float *>(kst);          // [gb][128] floats <= 8 KiB
+#pragma unroll
+    for (int x = 0; x < 4; ++x) {
+        const int head = 4 * r + x;
+        if (head < gb) {
+            *reinterpret_cast<float4 *>(wacc + head * W + 8 * c) =
+                make_float4(oacc[0][x], oacc[1][x], oacc[2][x], oacc[3][x]);
+            *reinterpret_cast<float4 *>(wacc + head * W + 8 * c + 4) =
+                make_float4(oacc[4][x], oacc[5][x], oacc[6][x], oacc[7][x]);
+        }
+    }
+    if (r == 0) {
+        sm_m[wave][c] = m;
+        sm_l[wave][c] = lsum;
+    }
+    __syncthreads();
+    for (int idx = tid; idx < gb * W; idx += blockDim.x) {
+        const int g = idx / W, d = idx - g * W;
+        float M = sm_m[0][g];
+#pragma unroll
+        for (int w2 = 1; w2 < kWavesPerBlock; ++w2) M = fmaxf(M, sm_m[w2][g]);
+        float a = 0.0f, L = 0.0f;
+#pragma unroll
+        for (int w2 = 0; w2 < kWavesPerBlock; ++w2) {
+            const float f = sm_m[w2][g] == -INFINITY ? 0.0f : __expf(sm_m[w2][g] - M);
+            a = fmaf(reinterpret_cast<const float *>(lds_k[w2])[g * W + d], f, a);
+            L = fmaf(sm_l[w2][g], f, L);
+        }
+        p.part_acc[(part_base + g * part_head_stride) * W + d] = a;
+        if (d == 0) {
+            p.part_ml[(part_base + g * part_head_stride) * 2 + 0] = M;
+            p.part_ml[(part_base + g * part_head_stride) * 2 + 1] = L;
+        }
+    }
+}
+
 struct CombineParams {
     const float *part_acc;
     const float *part_ml;
@@ -449,15 +727,18 @@ int make_attn_plan(const pikv_desc *d, int k, AttnPlan *plan) {
     const int G = d->Hq / d->Hkv;
     int gb = 1;
     if (d->route_rows_per_seq == 1 && (G == 2 || G == 4 || G == 8)) gb = G;
+    const bool gqa_mfma = d->route_rows_per_seq == 1 && d->dtype == PIKV_BF16 && d->rank == 0 &&
+                          d->D == 128 && G >= 2 && G <= 16;
+    if (gqa_mfma) gb = G;
     const int epl = 16 / elem_bytes(d->dtype);
     const int lpr = W / epl;
     if (lpr < 1 || lpr > 32) return PIKV_ERR_UNSUPPORTED;
-    const int tile = (kWave / lpr) * kLoadsPerTile;
+    const int tile = gqa_mfma ? kGqaTile : (kWave / lpr) * kLoadsPerTile;
     const int64_t units = (int64_t)d->B * (d->Hq / gb) * k;
     // One round of resident blocks: 256 CUs times the 4-wave blocks a CU holds at this
     // kernel's register footprint.  Fewer, longer blocks keep the per-wave prefetch chain
     // busy and shrink the partials that the combine pass has to merge.
-    const int resident = gb >= 8 ? 2 : (gb >= 4 ? 3 : 4);
+    const int resident = gqa_mfma ? 3 : (gb >= 8 ? 2 : (gb >= 4 ? 3 : 4));
     const int64_t target_blocks = 256 * resident;
     int64_t nsplit = units > 0 ? target_blocks / units : 1;
     if (g_split_override > 0) nsplit = g_split_override;
@@ -468,6 +749,7 @@ int make_attn_plan(const pikv_desc *d, int k, AttnPlan *plan) {
     int chunk = (int)((d->S + nsplit - 1) / nsplit);
     chunk = (chunk + tile - 1) / tile * tile;
     nsplit = (d->S + chunk - 1) / chunk;
+    plan->gqa_mfma = gqa_mfma;
     plan->heads_per_block = gb;
     plan->head_blocks = d->Hq / gb;
     plan->tile_rows = tile;
@@ -543,7 +825,13 @@ extern "C" int pikv_sharded_attn(const pikv_desc *desc, const void *q, const voi
     const int64_t blocks64 = (int64_t)desc->B * plan.head_blocks * k * plan.nsplit;
     if (blocks64 > 0x7fffffff) return PIKV_ERR_UNSUPPORTED;
     hipStream_t st = as_stream(stream);
-    int lrc = desc->dtype == PIKV_F32
+    int lrc;
+    if (plan.gqa_mfma) {
+        hipLaunchKernelGGL(attn_partial_gqa128, dim3((unsigned)blocks64), dim3(kWavesPerBlock * kWave),
+                           0, st, p);
+        lrc = launch_status();
+    } else
+        lrc = desc->dtype == PIKV_F32
                   ? launch_partial<float>(W, plan.heads_per_block, p, (int)blocks64, st)
                   : launch_partial<bf16>(W, plan.heads_per_block, p, (int)blocks64, st);
     if (lrc != PIKV_OK) return lrc;

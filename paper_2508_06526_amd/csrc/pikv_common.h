@@ -124,7 +124,8 @@ inline int elem_bytes(int dtype) { return dtype == PIKV_F32 ? 4 : 2; }
 
 // Split geometry of the attention pass (also defines the workspace size).
 struct AttnPlan {
-    int heads_per_block;  // query heads sharing one K/V stream (1, 2, 4 or 8)
+    bool gqa_mfma;        // matrix-core grouped-query kernel (bf16, D = 128, 2..16 heads per kv head)
+    int heads_per_block;  // query heads sharing one K/V stream
     int head_blocks;      // Hq / heads_per_block
     int tile_rows;        // rows one wave consumes per iteration
     int chunk;            // rows per split (multiple of tile_rows)

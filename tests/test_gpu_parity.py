@@ -88,6 +88,11 @@ ATTN_CASES = {
     "gqa2": (dict(B=2, Hq=4, Hkv=2, D=64, E=4, S=300, k=2, dtype="bf16"), "ragged"),
     "gqa8": (dict(B=1, Hq=8, Hkv=1, D=128, E=4, S=260, k=2, dtype="bf16"), "full"),
     "gqa3_generic": (dict(B=1, Hq=6, Hkv=2, D=64, E=4, S=150, k=3, dtype="bf16"), "ragged"),
+    # matrix-core grouped-query kernel (bf16, D=128): odd group sizes, the 16-head limit, short tails
+    "gqa3_d128": (dict(B=2, Hq=6, Hkv=2, D=128, E=4, S=333, k=2, dtype="bf16"), "ragged"),
+    "gqa16_d128": (dict(B=1, Hq=16, Hkv=1, D=128, E=3, S=1500, k=2, dtype="bf16"), "ragged"),
+    "gqa5_d128_tiny": (dict(B=1, Hq=5, Hkv=1, D=128, E=2, S=7, k=2, dtype="bf16"), "full"),
+    "gqa32_falls_back": (dict(B=1, Hq=32, Hkv=1, D=128, E=2, S=70, k=1, dtype="bf16"), "full"),
     # scaled config 5: rank-32 codes
     "c5_scaled": (dict(B=2, Hq=4, Hkv=4, D=128, E=6, S=900, k=2, dtype="bf16", rank=32), "ragged"),
     "rank16_gqa4": (dict(B=1, Hq=8, Hkv=2, D=64, E=4, S=520, k=2, dtype="bf16", rank=16), "ragged"),
