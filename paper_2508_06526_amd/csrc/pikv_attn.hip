@@ -41,6 +41,33 @@ struct AttnParams {
     float scale;
 };
 
+// Resolve the j-th selected shard of a routing row with ONE round trip to memory: the
+// expert id is fetched while lanes 0..E-1 fetch the entry count and the K/V base address of
+// every expert of the sequence; the selected lane's values are then broadcast.
+struct ShardRef {
+    int e, n;
+    const char *K, *V;
+};
+__device__ __forceinline__ ShardRef resolve_shard(const AttnParams &p, int b, int route_row, int j,
+                                                  int lane) {
+    const int l = min(lane, p.E - 1);
+    const int64_t s = (int64_t)b * p.E + l;
+    const int nv = p.n_valid[s];
+    const uint64_t kp = reinterpret_cast<uint64_t>(p.K[s]);
+    const uint64_t vp = reinterpret_cast<uint64_t>(p.V[s]);
+    const int e = __builtin_amdgcn_readfirstlane(p.topk[(int64_t)route_row * p.k + j]);
+    ShardRef out;
+    out.e = e;
+    out.n = __builtin_amdgcn_readlane(nv, e);
+    const uint32_t klo = __builtin_amdgcn_readlane((int)(uint32_t)kp, e);
+    const uint32_t khi = __builtin_amdgcn_readlane((int)(uint32_t)(kp >> 32), e);
+    const uint32_t vlo = __builtin_amdgcn_readlane((int)(uint32_t)vp, e);
+    const uint32_t vhi = __builtin_amdgcn_readlane((int)(uint32_t)(vp >> 32), e);
+    out.K = reinterpret_cast<const char *>(((uint64_t)khi << 32) | klo);
+    out.V = reinterpret_cast<const char *>(((uint64_t)vhi << 32) | vlo);
+    return out;
+}
+
 template <typename T, int W, int GB>
 __global__ __launch_bounds__(kWavesPerBlock *kWave) void attn_partial(AttnParams p) {
     constexpr int EPL = Pack16<T>::N;        // elements per lane per load
@@ -68,8 +95,8 @@ __global__ __launch_bounds__(kWavesPerBlock *kWave) void attn_partial(AttnParams
     const int h0 = hg * GB;
     const int hk = h0 / p.G;
     const int route_row = b * p.rr + (p.rr == 1 ? 0 : h0);
-    const int e = p.topk[(int64_t)route_row * p.k + j];
-    const int n = p.n_valid[(int64_t)b * p.E + e];
+    const ShardRef sh = resolve_shard(p, b, route_row, j, lane);
+    const int n = sh.n;
     const int r0 = split * p.chunk;
     const int r1 = min(n, r0 + p.chunk);
 
@@ -93,9 +120,8 @@ __global__ __launch_bounds__(kWavesPerBlock *kWave) void attn_partial(AttnParams
         return;
     }
 
-    const int64_t shard = (int64_t)b * p.E + e;
-    const T *Kb = static_cast<const T *>(p.K[shard]) + (int64_t)hk * p.stride_h + c * EPL;
-    const T *Vb = static_cast<const T *>(p.V[shard]) + (int64_t)hk * p.stride_h + c * EPL;
+    const T *Kb = reinterpret_cast<const T *>(sh.K) + (int64_t)hk * p.stride_h + c * EPL;
+    const T *Vb = reinterpret_cast<const T *>(sh.V) + (int64_t)hk * p.stride_h + c * EPL;
 
     // A wave owns tiles t0, t0 + 4*TILE, ... of the block's row range.  The loads of a tile
     // are issued one phase ahead of their use (K of the next tile while the softmax of this
@@ -304,7 +330,7 @@ __device__ __forceinline__ void wave_lds_order() {
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-__global__ __launch_bounds__(kWavesPerBlock *kWave) void attn_partial_gqa128(AttnParams p) {
+__global__ __launch_bounds__(kWavesPerBlock *kWave, 3) void attn_partial_gqa128(AttnParams p) {
     constexpr int W = 128;
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
@@ -322,8 +348,8 @@ __global__ __launch_bounds__(kWavesPerBlock *kWave) void attn_partial_gqa128(Att
     const int hk = bid % hgroups;
     const int b = bid / hgroups;
     const int h0 = hk * gb;
-    const int e = p.topk[(int64_t)b * p.k + j];
-    const int n = p.n_valid[(int64_t)b * p.E + e];
+    const ShardRef sh = resolve_shard(p, b, b, j, lane);
+    const int n = sh.n;
     const int r0 = split * p.chunk;
     const int r1 = min(n, r0 + p.chunk);
 
@@ -348,19 +374,27 @@ __global__ __launch_bounds__(kWavesPerBlock *kWave) void attn_partial_gqa128(Att
         return;
     }
 
-    const int64_t shard = (int64_t)b * p.E + e;
-    const bf16 *Kb = static_cast<const bf16 *>(p.K[shard]) + (int64_t)hk * p.stride_h + c * 8;
-    const bf16 *Vb = static_cast<const bf16 *>(p.V[shard]) + (int64_t)hk * p.stride_h + c * 8;
+    const int64_t row_bytes = p.stride_s * 2;
+    const char *Kb = sh.K + (int64_t)hk * p.stride_h * 2;
+    const char *Vb = sh.V + (int64_t)hk * p.stride_h * 2;
+    // lane part of every address: rows 8r.. of the tile, byte chunk c (fits 32 bits)
+    const uint32_t lane_off = (uint32_t)(8 * r) * (uint32_t)row_bytes + 16u * c;
 
     uint4 kr[8], vr[8];
-    auto load_tile = [&](uint4(&dst)[8], const bf16 *base, int t0) {
+    auto load_tile = [&](uint4(&dst)[8], const char *base, int t0) {
+        if (t0 + kGqaTile <= r1) {     // full tile: wave-uniform base + constant lane offset
+            const char *bp = base + (int64_t)t0 * row_bytes;
 #pragma unroll
-        for (int t = 0; t < 8; ++t) {
-            const int row = min(t0 + 8 * r + t, r1 - 1);   // clamped rows are masked below
-            dst[t] = load16_stream(base + (int64_t)row * p.stride_s);
+            for (int t = 0; t < 8; ++t) dst[t] = load16_stream(bp + t * row_bytes + lane_off);
+        } else {                        // ragged tail: clamp onto the last valid row, mask later
+#pragma unroll
+            for (int t = 0; t < 8; ++t) {
+                const int row = min(t0 + 8 * r + t, r1 - 1);
+                dst[t] = load16_stream(base + (int64_t)row * row_bytes + 16 * c);
+            }
         }
     };
-    int t0 = r0 + wave * kGqaTile;
+    int t0 = r0 + __builtin_amdgcn_readfirstlane(wave) * kGqaTile;
     if (t0 < r1) {
         load_tile(kr, Kb, t0);
         load_tile(vr, Vb, t0);
@@ -556,14 +590,17 @@ struct CombineParams {
     int Hq, G, D, W, k, rr, rank, nsplit, combine;
 };
 
-constexpr int kCombineThreads = 256;
+constexpr int kCombineThreads = 1024;
+constexpr int kCombinePrefetch = 4;         // partial rows each thread loads before the weights exist
 constexpr int kMaxPartialsPerHead = 2048;   // k * nsplit
 
-// One block per (sequence, query head).  Phase 1: every partial's (max, sum) into LDS and,
-// one wave per selected shard, the shard's max and normaliser.  Phase 2 (one thread): the
-// k gate-weighted shard weights in either combine mode.  Phase 3: the weighted sum of the
-// partial accumulators, threads laid out as (slice of partials) x (float4 column group) so
-// that every load is a contiguous run of a partial's row.
+// One block per (sequence, query head).  The partial accumulators do not depend on the
+// weights, so their loads are issued first and overlap the whole weight computation:
+//   phase 0: every thread = (slice of partials, float4 column group) issues its first
+//            accumulator loads; (max, sum) of every partial goes to LDS.
+//   phase 1: one wave per selected shard reduces its splits to (max, normaliser).
+//   phase 2: one thread forms the k gate-weighted shard weights in either combine mode.
+//   phase 3: weighted sum of the accumulators, slices reduced through LDS in fixed order.
 template <typename T>
 __global__ __launch_bounds__(kCombineThreads) void attn_combine(CombineParams p) {
     const int bh = blockIdx.x;
@@ -578,6 +615,18 @@ __global__ __launch_bounds__(kCombineThreads) void attn_combine(CombineParams p)
     __shared__ float Mj[64], Zj[64], shard_w[64];
     __shared__ float4 red[kCombineThreads];
     __shared__ float ycode[128];
+
+    const int cgroups = p.W / 4;                       // float4 column groups: 4..32
+    const int slices = kCombineThreads / cgroups;      // partial slices: 256..32
+    const int cg = tid % cgroups, sl = tid / cgroups;
+    const float *acc = p.part_acc + (int64_t)bh * np * p.W + cg * 4;
+    float4 pre[kCombinePrefetch];
+#pragma unroll
+    for (int u = 0; u < kCombinePrefetch; ++u) {
+        const int i = sl + u * slices;
+        pre[u] = i < np ? *reinterpret_cast<const float4 *>(acc + (int64_t)i * p.W)
+                        : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
 
     const float *ml = p.part_ml + (int64_t)bh * np * 2;
     for (int i = tid; i < np; i += kCombineThreads) {
@@ -645,12 +694,17 @@ __global__ __launch_bounds__(kCombineThreads) void attn_combine(CombineParams p)
     }
     __syncthreads();
 
-    const int cgroups = p.W / 4;                       // float4 column groups: 4..32
-    const int slices = kCombineThreads / cgroups;      // partial slices: 64..8
-    const int cg = tid % cgroups, sl = tid / cgroups;
-    const float *acc = p.part_acc + (int64_t)bh * np * p.W + cg * 4;
     float4 a = make_float4(0.f, 0.f, 0.f, 0.f);
-    for (int i = sl; i < np; i += slices) {
+#pragma unroll
+    for (int u = 0; u < kCombinePrefetch; ++u) {
+        const int i = sl + u * slices;
+        const float w = i < np ? wt[i] : 0.0f;
+        a.x = fmaf(w, pre[u].x, a.x);
+        a.y = fmaf(w, pre[u].y, a.y);
+        a.z = fmaf(w, pre[u].z, a.z);
+        a.w = fmaf(w, pre[u].w, a.w);
+    }
+    for (int i = sl + kCombinePrefetch * slices; i < np; i += slices) {
         const float w = wt[i];
         const float4 v = *reinterpret_cast<const float4 *>(acc + (int64_t)i * p.W);
         a.x = fmaf(w, v.x, a.x);
@@ -660,15 +714,21 @@ __global__ __launch_bounds__(kCombineThreads) void attn_combine(CombineParams p)
     }
     red[tid] = a;
     __syncthreads();
-    if (tid < cgroups) {
-        float4 t = red[tid];
-        for (int s2 = 1; s2 < slices; ++s2) {
-            const float4 v = red[s2 * cgroups + tid];
+    // fixed-order tree over the slices (slices is a power of two)
+    for (int half = slices >> 1; half >= 1; half >>= 1) {
+        if (sl < half) {
+            const float4 v = red[tid + half * cgroups];
+            float4 t = red[tid];
             t.x += v.x;
             t.y += v.y;
             t.z += v.z;
             t.w += v.w;
+            red[tid] = t;
         }
+        __syncthreads();
+    }
+    if (tid < cgroups) {
+        const float4 t = red[tid];
         if (p.rank == 0) {
             *reinterpret_cast<float4 *>(p.y + (int64_t)bh * p.D + tid * 4) = t;
         } else {
