@@ -36,6 +36,8 @@ def parse_args():
     ap.add_argument("--config", default="c3_long_context")
     ap.add_argument("--layers", type=int, default=0, help="layer instances cycled (0: per config)")
     ap.add_argument("--mode", choices=["graph", "eager"], default="graph")
+    ap.add_argument("--api", choices=["fused", "separate"], default="fused",
+                    help="fused: pikv_decode_step (3 launches); separate: the five calls (6 launches)")
     ap.add_argument("--cpu-steps", type=int, default=-1, help="oracle steps timed (0: skip, -1: auto)")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--seed", type=int, default=0)
@@ -67,9 +69,17 @@ class Layer:
         self.K_tab = pk.shard_table(tensors["K"])
         self.V_tab = pk.shard_table(tensors["V"])
         self.decay = DECAY.get(g.name, 1.0)
+        self.fused = shared.get("fused", False) and not g.per_head_routing
 
     def step(self):
         pk, g, t, s = self.pk, self.geo, self.t, self.sh
+        if self.fused:
+            pk.pikv_decode_step(self.desc, t["q"], t["W_r"], t["bias"], s["K_new"], s["V_new"],
+                                self.K_tab, self.V_tab, t["U_K"], t["U_V"], t["n_valid"], t["utility"],
+                                g.k, pk.COMBINE_LSE, 0.0, self.decay, s["topk"], s["gates"], s["eidx"],
+                                s["ecnt"], s["y"], s["row_max"], s["row_norm"], s["scores"],
+                                s["slot_coef"], s["workspace"])
+            return
         pk.pikv_route(t["q"], t["W_r"], t["bias"], g.route_rows, g.d_r, g.E, g.k, s["topk"],
                       s["gates"], None)
         if not g.per_head_routing:
@@ -169,6 +179,7 @@ def main():
     n_layers = args.layers or DEFAULT_LAYERS[args.config]
     raw = wl.make_device_layers(geo, n_layers, args.seed, dev, **RECIPE[args.config])
     shared = make_shared(pk, torch, geo, dev)
+    shared["fused"] = args.api == "fused"
     layers = [Layer(pk, torch, geo, t, shared) for t in raw]
     torch.cuda.synchronize()
 
@@ -229,7 +240,7 @@ def main():
         "dtype": "bf16" if geo.dtype == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": args.config, "B": geo.B, "Hq": geo.Hq, "Hkv": geo.Hkv, "D": geo.D,
                    "E": geo.E, "S": geo.S, "k": geo.k, "rank": geo.rank, "layers_cycled": n_layers,
-                   "launch": args.mode,
+                   "launch": args.mode, "api": args.api,
                    "step": "route+evict1+append+attend+utility"},
         "step_effective_GBps": kv_bytes / (ms_per_step * 1e-3) / 1e9,
         "step_frac_of_hbm_peak": kv_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,

@@ -166,6 +166,28 @@ int pikv_append(const pikv_desc *desc, const void *K_new, const void *V_new,
                 const int32_t *reuse_cnt, int32_t max_evict, void *const *K_shards,
                 void *const *V_shards, float *utility, int32_t *n_valid, void *stream);
 
+/* One iteration of Algorithm 1's loop in three launches instead of six (per-token routing
+ * only): route q -> for every selected shard that is full evict its minimum-utility entry
+ * (order: utility ascending, then higher slot first) -> insert the new token's rows there
+ * (or at slot n_valid if the shard has room) -> attention over the selected shards (new
+ * entry included) -> utility update.  Results are exactly those of the call sequence
+ *   pikv_route(q as [B, Hq*D], W_r, bias, ...);
+ *   pikv_evict(capacity = S-1, sel_idx = topk_idx, max_evict = 1, compact = 0);
+ *   pikv_append(K_new, V_new, topk_idx, reuse = the evict outputs);
+ *   pikv_sharded_attn(...); pikv_update_utility(...);
+ * with the same argument meanings.  K_new == V_new == NULL skips the evict/insert stage
+ * (evicted_* may then be NULL).  evicted_idx is [B,E,1], evicted_cnt [B,E]; scores and
+ * slot_coef are required.  Errors: as for the separate calls; UNSUPPORTED when
+ * route_rows_per_seq != 1 or a row of W_r is not a power-of-two number of aligned 16-byte
+ * chunks (E * sizeof(element) in {16,32,64,128,256}).                                      */
+int pikv_decode_step(const pikv_desc *desc, const void *q, const void *W_r, const float *bias,
+                     const void *K_new, const void *V_new, void *const *K_shards,
+                     void *const *V_shards, const void *U_K, const void *U_V, int32_t *n_valid,
+                     float *utility, int32_t k, int32_t combine, float scale, float decay,
+                     int32_t *topk_idx, float *gates, int32_t *evicted_idx, int32_t *evicted_cnt,
+                     float *y, float *row_max, float *row_norm, float *scores, float *slot_coef,
+                     void *workspace, size_t workspace_bytes, void *stream);
+
 /* Tuning hook: force the number of row-range splits per (head group, selected shard) used
  * by pikv_sharded_attn and pikv_attn_workspace_bytes (process-wide; 0 restores the built-in
  * choice of one round of resident blocks).  Change it only between calls, and size the

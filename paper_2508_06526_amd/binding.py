@@ -16,7 +16,7 @@ F32, BF16 = 0, 1
 COMBINE_LSE, COMBINE_LOCAL = 0, 1
 
 EXPORTS = ("pikv_route", "pikv_attn_workspace_bytes", "pikv_sharded_attn", "pikv_update_utility",
-           "pikv_evict", "pikv_append", "pikv_strerror", "pikv_version", "pikv_set_attn_split")
+           "pikv_evict", "pikv_append", "pikv_strerror", "pikv_version", "pikv_set_attn_split", "pikv_decode_step")
 
 
 class PikvError(RuntimeError):
@@ -69,6 +69,9 @@ def load_library():
     lib.pikv_append.restype = C.c_int
     lib.pikv_strerror.argtypes = [C.c_int]
     lib.pikv_strerror.restype = C.c_char_p
+    lib.pikv_decode_step.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, f32, f32,
+                                     vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
+    lib.pikv_decode_step.restype = C.c_int
     lib.pikv_set_attn_split.argtypes = [i32]
     lib.pikv_set_attn_split.restype = None
     lib.pikv_version.argtypes = []
@@ -190,3 +193,15 @@ def pikv_append(desc, K_new, V_new, topk_idx, k, reuse_idx, reuse_cnt, max_evict
                                     _p(reuse_idx), _p(reuse_cnt), max_evict, _p(K_shards),
                                     _p(V_shards), _p(utility), _p(n_valid), _stream(stream))
     _check(st, "pikv_append")
+
+
+def pikv_decode_step(desc, q, W_r, bias, K_new, V_new, K_shards, V_shards, U_K, U_V, n_valid, utility,
+                     k, combine, scale, decay, topk_idx, gates, evicted_idx, evicted_cnt, y, row_max,
+                     row_norm, scores, slot_coef, workspace, stream=None):
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    st = load_library().pikv_decode_step(
+        C.byref(desc), _p(q), _p(W_r), _p(bias), _p(K_new), _p(V_new), _p(K_shards), _p(V_shards),
+        _p(U_K), _p(U_V), _p(n_valid), _p(utility), k, combine, float(scale), float(decay),
+        _p(topk_idx), _p(gates), _p(evicted_idx), _p(evicted_cnt), _p(y), _p(row_max), _p(row_norm),
+        _p(scores), _p(slot_coef), _p(workspace), ws_bytes, _stream(stream))
+    _check(st, "pikv_decode_step")

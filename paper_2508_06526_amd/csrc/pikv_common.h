@@ -113,6 +113,22 @@ __device__ __forceinline__ uint4 load16_stream(const void *p) {
     return make_uint4(v.x, v.y, v.z, v.w);
 }
 
+// fp32 -> uint32 whose unsigned order is the float order (-0 folded onto +0).
+__device__ __forceinline__ uint32_t order_key(float u) {
+    uint32_t bits = __float_as_uint(u);
+    if (bits == 0x80000000u) bits = 0u;
+    return (bits & 0x80000000u) ? ~bits : (bits | 0x80000000u);
+}
+
+// Eviction order in one integer: smaller composite = lower utility, then HIGHER slot (among
+// equal utilities the lower slot is the one that is kept).
+__device__ __forceinline__ uint64_t evict_composite(float u, int slot) {
+    return ((uint64_t)order_key(u) << 32) | (uint32_t)(0x7fffffff - slot);
+}
+__device__ __forceinline__ int evict_composite_slot(uint64_t c) {
+    return 0x7fffffff - (int)(uint32_t)(c & 0xffffffffu);
+}
+
 inline hipStream_t as_stream(void *s) { return reinterpret_cast<hipStream_t>(s); }
 
 inline int launch_status() { return hipGetLastError() == hipSuccess ? PIKV_OK : PIKV_ERR_HIP; }

@@ -21,13 +21,6 @@ namespace {
 
 constexpr int kEvictThreads = 256;
 
-// fp32 -> uint32 whose unsigned order is the float order (-0 folded onto +0).
-__device__ __forceinline__ uint32_t order_key(float u) {
-    uint32_t bits = __float_as_uint(u);
-    if (bits == 0x80000000u) bits = 0u;
-    return (bits & 0x80000000u) ? ~bits : (bits | 0x80000000u);
-}
-
 // Inclusive prefix sum over the 256 threads of the block; *total receives the block sum.
 __device__ __forceinline__ int block_scan_incl(int v, int *wave_sums, int *total) {
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;

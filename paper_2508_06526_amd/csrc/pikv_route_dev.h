@@ -1,0 +1,109 @@
+// Device-side pieces of the router shared by the stand-alone routing kernel and the fused
+// step kernel (PiKV Section 3.2, Table 1 "TopK softmax").
+#pragma once
+
+#include "pikv_common.h"
+
+#include <math.h>
+
+namespace pikv {
+
+constexpr int kRouteThreads = 1024;
+
+// Softmax over the E logits, rank-count selection and gate renormalisation, by the first
+// wavefront of the block (lane e owns expert e).  `logit` is in LDS.
+__device__ __forceinline__ void select_topk(const float *logit, int lane, int row, int E, int k,
+                                            int32_t *topk_idx, float *gates, float *probs,
+                                            int *sel_lds = nullptr) {
+    const float mine = logit[lane];
+    float mx = mine;
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, kWave));
+    const float pe = lane < E ? __expf(mine - mx) : 0.0f;
+    float den = pe;
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) den += __shfl_xor(den, off, kWave);
+    if (probs && lane < E) probs[(int64_t)row * E + lane] = pe / den;
+
+    int rank = 0;
+    for (int o = 0; o < E; ++o) {
+        const float other = logit[o];
+        rank += (other > mine) || (other == mine && o < lane);
+    }
+    const bool chosen = lane < E && rank < k;
+    float sel = chosen ? pe : 0.0f;
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) sel += __shfl_xor(sel, off, kWave);
+    if (chosen) {
+        if (topk_idx) {
+            topk_idx[(int64_t)row * k + rank] = lane;
+            gates[(int64_t)row * k + rank] = pe / sel;
+        }
+        if (sel_lds) sel_lds[rank] = lane;
+    }
+}
+
+// Logits of one routed row with the whole 1024-thread block, for a row-major W_r whose rows
+// are `cpr` (a power of two <= 16) 16-byte chunks.  Thread t streams chunks t, t+1024, ...
+// (a wave reads 1 KiB of consecutive bytes per load; all loads of a thread are independent);
+// its chunk-in-row index never changes, so it accumulates the same EPL experts throughout.
+// Lanes with equal chunk index are summed by xor-shuffles, the 16 waves through LDS in fixed
+// order, so the logits do not depend on scheduling.  Ends with logit[0..63] valid in LDS
+// (experts >= E hold -inf; a NaN logit is replaced by -inf) after a block barrier.
+template <typename T>
+__device__ __forceinline__ void route_logits_vec(const T *xr, const T *W_r, const float *bias,
+                                                 int d_r, int E, int cpr,
+                                                 float (*red)[64], float *logit) {
+    constexpr int EPL = Pack16<T>::N;
+    constexpr int kWaves = kRouteThreads / kWave;
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1), wave = tid >> 6;
+    const int cir = tid & (cpr - 1);
+    const int cshift = ilog2(cpr);
+    const int total = d_r * cpr;
+
+    float acc[EPL];
+#pragma unroll
+    for (int i = 0; i < EPL; ++i) acc[i] = 0.0f;
+#pragma unroll 4
+    for (int c = tid; c < total; c += kRouteThreads) {
+        const uint4 w = load16(W_r + (int64_t)c * EPL);
+        const float xj = load_scalar<T>(xr, c >> cshift);
+        float wf[EPL];
+        Pack16<T>::widen(w, wf);
+#pragma unroll
+        for (int i = 0; i < EPL; ++i) acc[i] = fmaf(xj, wf[i], acc[i]);
+    }
+    for (int off = cpr; off < kWave; off <<= 1) {
+#pragma unroll
+        for (int i = 0; i < EPL; ++i) acc[i] += __shfl_xor(acc[i], off, kWave);
+    }
+    if (lane < cpr) {
+#pragma unroll
+        for (int i = 0; i < EPL; ++i) red[wave][cir * EPL + i] = acc[i];
+    }
+    __syncthreads();
+    if (tid < 64) {
+        float v = -INFINITY;
+        if (tid < E) {
+            v = 0.0f;
+#pragma unroll
+            for (int w = 0; w < kWaves; ++w) v += red[w][tid];
+            v += bias ? bias[tid] : 0.0f;
+            if (v != v) v = -INFINITY;
+        }
+        logit[tid] = v;
+    }
+    __syncthreads();
+}
+
+// True when route_logits_vec applies: W_r rows are a power-of-two number of aligned 16-byte
+// chunks.
+inline bool route_vec_ok(const void *W_r, int E, int dtype, int *cpr) {
+    const int row_bytes = E * elem_bytes(dtype);
+    *cpr = row_bytes / 16;
+    return row_bytes % 16 == 0 && (*cpr & (*cpr - 1)) == 0 &&
+           reinterpret_cast<uintptr_t>(W_r) % 16 == 0;
+}
+
+}  // namespace pikv

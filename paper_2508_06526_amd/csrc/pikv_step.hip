@@ -1,0 +1,202 @@
+// One decode step of PiKV's hot path as three launches (Algorithm 1, one iteration of the
+// loop: route, insert the new entry under bounded memory, attend, score):
+//
+//   step_pre   : per (sequence, selected position), a 1024-thread block routes the query
+//                (Section 3.2), then for its selected shard evicts the minimum-utility entry
+//                if the shard is full (Section 3.4) and inserts the new token's K/V rows in
+//                O(1) (Section 3.1).
+//                Everything that depends only on the selected expert id (entry count, table
+//                pointers, the shard's utilities) is fetched in one round trip; the new rows
+//                are fetched before the router result exists.
+//   attention  : the split flash-decode over the selected shards (pikv_sharded_attn).
+//   utility    : u <- decay * u + attention mass (pikv_update_utility).
+//
+// Separate launches for the first stage cost ~2.4 us of dispatch each on MI355X, more than
+// the work itself; fusing them removes two launches and two dependent memory round trips.
+#include "pikv_common.h"
+#include "pikv_route_dev.h"
+
+namespace pikv {
+namespace {
+
+struct PreParams {
+    const void *x;
+    const void *W_r;
+    const float *bias;
+    int32_t *topk;
+    float *gates;
+    const void *K_new;
+    const void *V_new;
+    void *const *K;
+    void *const *V;
+    float *utility;
+    int32_t *n_valid;
+    int32_t *evicted_idx;
+    int32_t *evicted_cnt;
+    int64_t stride_h_bytes, stride_s_bytes;
+    int d_r, E, cpr, k, S, Hkv, row_chunks, do_insert;
+};
+
+// Grid: (sequence b, selected position j).  Every block of a sequence recomputes the routing
+// decision (W_r is L2-resident and tiny next to the cache) so that the k evict/insert jobs
+// run on k compute units at once instead of one after the other; block j == 0 publishes the
+// decision.
+template <typename T>
+__global__ __launch_bounds__(kRouteThreads) void step_pre(PreParams p) {
+    constexpr int kWaves = kRouteThreads / kWave;
+    const int b = blockIdx.x / p.k, j = blockIdx.x - b * p.k;
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1), wave = tid >> 6;
+
+    __shared__ float red[kWaves][64];
+    __shared__ float logit[64];
+    __shared__ int sel[64];
+    __shared__ uint64_t wave_best[kWaves];
+
+    // the new rows do not depend on the routing decision: fetch the first chunk now
+    const int new_chunks = p.Hkv * p.row_chunks;
+    uint4 knew = make_uint4(0, 0, 0, 0), vnew = knew;
+    if (p.do_insert && tid < new_chunks) {
+        knew = load16(static_cast<const char *>(p.K_new) + ((int64_t)b * new_chunks + tid) * 16);
+        vnew = load16(static_cast<const char *>(p.V_new) + ((int64_t)b * new_chunks + tid) * 16);
+    }
+
+    route_logits_vec<T>(static_cast<const T *>(p.x) + (int64_t)b * p.d_r,
+                        static_cast<const T *>(p.W_r), p.bias, p.d_r, p.E, p.cpr, red, logit);
+    if (tid < 64)
+        select_topk(logit, tid, b, p.E, p.k, j == 0 ? p.topk : nullptr, p.gates, nullptr, sel);
+    __syncthreads();
+    if (!p.do_insert) return;
+
+    // one round trip for everything that hangs off the expert id
+    const int e = sel[j];
+    const int64_t be = (int64_t)b * p.E + e;
+    const int n = p.n_valid[be];
+    char *Kd = static_cast<char *>(p.K[be]);
+    char *Vd = static_cast<char *>(p.V[be]);
+    const float *u = p.utility + be * p.S;
+    uint64_t best = ~0ull;
+    if ((p.S & 3) == 0) {
+        for (int i = tid * 4; i < p.S; i += kRouteThreads * 4) {
+            const float4 v = *reinterpret_cast<const float4 *>(u + i);
+            uint64_t c0 = evict_composite(v.x, i), c1 = evict_composite(v.y, i + 1);
+            uint64_t c2 = evict_composite(v.z, i + 2), c3 = evict_composite(v.w, i + 3);
+            c0 = c0 < c1 ? c0 : c1;
+            c2 = c2 < c3 ? c2 : c3;
+            c0 = c0 < c2 ? c0 : c2;
+            best = c0 < best ? c0 : best;
+        }
+    } else {
+        for (int i = tid; i < p.S; i += kRouteThreads) {
+            const uint64_t c0 = evict_composite(u[i], i);
+            best = c0 < best ? c0 : best;
+        }
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        const uint64_t o = __shfl_xor(best, off, kWave);
+        best = o < best ? o : best;
+    }
+    if (lane == 0) wave_best[wave] = best;
+    __syncthreads();
+    uint64_t m = wave_best[0];
+#pragma unroll
+    for (int w = 1; w < kWaves; ++w) m = wave_best[w] < m ? wave_best[w] : m;
+    const bool full = n >= p.S;
+    const int slot = full ? evict_composite_slot(m) : n;
+
+    // insert the new entry's rows (one 16-byte chunk per thread and pass)
+    Kd += slot * p.stride_s_bytes;
+    Vd += slot * p.stride_s_bytes;
+    for (int idx = tid; idx < new_chunks; idx += kRouteThreads) {
+        uint4 kv = knew, vv = vnew;
+        if (idx >= kRouteThreads) {
+            kv = load16(static_cast<const char *>(p.K_new) + ((int64_t)b * new_chunks + idx) * 16);
+            vv = load16(static_cast<const char *>(p.V_new) + ((int64_t)b * new_chunks + idx) * 16);
+        }
+        const int hk = idx / p.row_chunks, cc = idx - hk * p.row_chunks;
+        *reinterpret_cast<uint4 *>(Kd + hk * p.stride_h_bytes + cc * 16) = kv;
+        *reinterpret_cast<uint4 *>(Vd + hk * p.stride_h_bytes + cc * 16) = vv;
+    }
+    if (tid == 0) {
+        if (full) p.evicted_idx[be] = slot;
+        p.evicted_cnt[be] = full ? 1 : 0;
+        p.utility[be * p.S + slot] = 0.0f;
+        p.n_valid[be] = full ? p.S : n + 1;
+    }
+    // experts nobody selected report "nothing evicted" (block 0 of the sequence)
+    if (j == 0 && tid < p.E) {
+        bool chosen = false;
+        for (int jj = 0; jj < p.k; ++jj) chosen |= sel[jj] == tid;
+        if (!chosen) p.evicted_cnt[(int64_t)b * p.E + tid] = 0;
+    }
+}
+
+}  // namespace
+}  // namespace pikv
+
+using namespace pikv;
+
+extern "C" int pikv_decode_step(const pikv_desc *desc, const void *q, const void *W_r,
+                                const float *bias, const void *K_new, const void *V_new,
+                                void *const *K_shards, void *const *V_shards, const void *U_K,
+                                const void *U_V, int32_t *n_valid, float *utility, int32_t k,
+                                int32_t combine, float scale, float decay, int32_t *topk_idx,
+                                float *gates, int32_t *evicted_idx, int32_t *evicted_cnt, float *y,
+                                float *row_max, float *row_norm, float *scores, float *slot_coef,
+                                void *workspace, size_t workspace_bytes, void *stream) {
+    const int rc = check_desc(desc);
+    if (rc != PIKV_OK) return rc;
+    if (!q || !W_r || !K_shards || !V_shards || !n_valid || !utility || !topk_idx || !gates || !y ||
+        !scores || !slot_coef)
+        return PIKV_ERR_INVALID;
+    if ((K_new == nullptr) != (V_new == nullptr)) return PIKV_ERR_INVALID;
+    if (K_new && (!evicted_idx || !evicted_cnt)) return PIKV_ERR_INVALID;
+    if (k < 1 || k > desc->E) return PIKV_ERR_INVALID;
+    if (!(decay >= 0.0f) || decay > 3.0e38f) return PIKV_ERR_INVALID;
+    if (combine != PIKV_COMBINE_LSE && combine != PIKV_COMBINE_LOCAL) return PIKV_ERR_INVALID;
+    if (desc->route_rows_per_seq != 1) return PIKV_ERR_UNSUPPORTED;
+    int cpr = 0;
+    if (!route_vec_ok(W_r, desc->E, desc->dtype, &cpr)) return PIKV_ERR_UNSUPPORTED;
+    const size_t need = pikv_attn_workspace_bytes(desc, k);
+    if (!workspace || workspace_bytes < need) return PIKV_ERR_WORKSPACE;
+    if (desc->B == 0) return PIKV_OK;
+
+    PreParams p;
+    p.x = q;
+    p.W_r = W_r;
+    p.bias = bias;
+    p.topk = topk_idx;
+    p.gates = gates;
+    p.K_new = K_new;
+    p.V_new = V_new;
+    p.K = K_shards;
+    p.V = V_shards;
+    p.utility = utility;
+    p.n_valid = n_valid;
+    p.evicted_idx = evicted_idx;
+    p.evicted_cnt = evicted_cnt;
+    const int eb = elem_bytes(desc->dtype);
+    p.stride_h_bytes = desc->stride_h * eb;
+    p.stride_s_bytes = desc->stride_s * eb;
+    p.d_r = desc->Hq * desc->D;
+    p.E = desc->E;
+    p.cpr = cpr;
+    p.k = k;
+    p.S = desc->S;
+    p.Hkv = desc->Hkv;
+    p.row_chunks = desc_width(desc) * eb / 16;
+    p.do_insert = K_new != nullptr;
+    hipStream_t st = as_stream(stream);
+    if (desc->dtype == PIKV_F32)
+        hipLaunchKernelGGL(step_pre<float>, dim3(desc->B * k), dim3(kRouteThreads), 0, st, p);
+    else
+        hipLaunchKernelGGL(step_pre<bf16>, dim3(desc->B * k), dim3(kRouteThreads), 0, st, p);
+    int lrc = launch_status();
+    if (lrc != PIKV_OK) return lrc;
+    lrc = pikv_sharded_attn(desc, q, K_shards, V_shards, U_K, U_V, n_valid, topk_idx, gates, k,
+                            combine, scale, y, row_max, row_norm, scores, slot_coef, workspace,
+                            workspace_bytes, stream);
+    if (lrc != PIKV_OK) return lrc;
+    return pikv_update_utility(desc, scores, slot_coef, n_valid, topk_idx, k, decay, utility, stream);
+}

@@ -377,3 +377,89 @@ def test_streaming_steps_route_evict_append_attend_update():
         assert (ref.n_valid <= g.S).all()
     for s in range(g.B * g.E):
         np.testing.assert_array_equal(dc.shard_host("K", s), ref.K_shards[s])
+
+
+# ------------------------------------------------------------------- fused decode step
+@pytest.mark.parametrize("spec", [
+    dict(B=4, Hq=4, Hkv=4, D=64, E=8, S=96, k=2, dtype="bf16"),
+    dict(B=2, Hq=8, Hkv=2, D=128, E=16, S=200, k=4, dtype="bf16"),
+    dict(B=3, Hq=4, Hkv=4, D=128, E=8, S=64, k=5, dtype="bf16", rank=32),
+    dict(B=2, Hq=4, Hkv=2, D=64, E=4, S=50, k=2, dtype="f32"),
+], ids=["g1", "gqa4", "rank32_k5", "f32"])
+def test_fused_decode_step_equals_separate_calls_and_oracle(spec):
+    """pikv_decode_step (3 launches) vs the five separate calls (bit-identical state) vs oracle."""
+    from gpu_harness import dev_storage
+    g = wl.Geometry(**spec)
+    case = wl.make_host_case(g, seed=41, utility0="exp", zipf_s=1.1)
+    case.n_valid[:, 0] = g.S - 3                       # a shard with room
+    dA, dB = DeviceCase(case), DeviceCase(case)
+    eiA = torch.full((g.B, g.E, 1), -1, device=DEV, dtype=torch.int32)
+    ecA = torch.full((g.B, g.E), -5, device=DEV, dtype=torch.int32)
+    eiB, ecB = eiA.clone(), ecA.clone()
+    ref = case.clone()
+    for step in range(6):
+        probe = case.clone()
+        probe.q = wl.draw_queries(g, 700 + step)
+        ensure_route_margin(probe, g.k)
+        qn = probe.q
+        kn, vn = wl.draw_new_kv(g, 800 + step)
+        dkn, dvn = dev_storage(kn, g.dtype), dev_storage(vn, g.dtype)
+        for d in (dA, dB):
+            d.q.copy_(dev_storage(qn, g.dtype))
+        # A: fused
+        pk.pikv_decode_step(dA.desc, dA.q, dA.W_r, dA.bias, dkn, dvn, dA.K_tab, dA.V_tab, dA.U_K, dA.U_V,
+                            dA.n_valid, dA.utility, g.k, pk.COMBINE_LSE, 0.0, 0.9, dA.topk, dA.gates,
+                            eiA, ecA, dA.y, dA.row_max, dA.row_norm, dA.scores, dA.slot_coef, dA.workspace)
+        # B: separate calls
+        dB.route()
+        pk.pikv_evict(dB.desc, dB.utility, dB.n_valid, g.S - 1, dB.topk, g.k, eiB, ecB, 1, False, None, None)
+        pk.pikv_append(dB.desc, dkn, dvn, dB.topk, g.k, eiB, ecB, 1, dB.K_tab, dB.V_tab, dB.utility, dB.n_valid)
+        dB.attend(combine=pk.COMBINE_LSE)
+        dB.update_utility(0.9)
+        for name in ("topk", "gates", "n_valid", "utility", "y", "K", "V"):
+            a, b2 = getattr(dA, name), getattr(dB, name)
+            if a.dtype == torch.bfloat16:
+                a, b2 = a.view(torch.int16), b2.view(torch.int16)
+            np.testing.assert_array_equal(t2n(a), t2n(b2), err_msg="%s differs at step %d" % (name, step))
+        np.testing.assert_array_equal(t2n(ecA), t2n(ecB))
+        np.testing.assert_array_equal(t2n(eiA)[t2n(ecA) == 1], t2n(eiB)[t2n(ecB) == 1])
+        # oracle, free running
+        x = np.ascontiguousarray(qn.reshape(g.route_rows, g.d_r))
+        idx, gates, _ = orc.route(x, ref.W_r, g.k, bias=ref.bias, dtype=g.dtype)
+        np.testing.assert_array_equal(t2n(dA.topk), idx)
+        mask = np.zeros((g.B, g.E), np.int32)
+        for b in range(g.B):
+            mask[b, idx[b]] = 1
+        ridx, rcnt = orc.evict(ref.utility, ref.n_valid, g.S - 1, shard_mask=mask, max_evict=1)
+        np.testing.assert_array_equal(t2n(ecA), rcnt)
+        orc.append(kn, vn, idx, ref.K_shards, ref.V_shards, ref.utility, ref.n_valid, dtype=g.dtype,
+                   reuse_idx=ridx, reuse_cnt=rcnt)
+        ref.q = qn
+        out = oracle_step(ref, idx, gates, orc.COMBINE_LSE, utility=ref.utility, decay=0.9)
+        ok, emax, l2 = y_tolerance_ok(t2n(dA.y), out["y"], g.dtype)
+        assert ok, (step, emax, l2)
+        assert_utility_close(t2n(dA.utility), ref.utility)
+        np.testing.assert_array_equal(t2n(dA.n_valid), ref.n_valid)
+
+
+def test_fused_decode_step_without_insert_and_unsupported_shapes():
+    g = wl.Geometry(B=2, Hq=4, Hkv=4, D=64, E=8, S=80, k=2, dtype="bf16")
+    case = wl.make_host_case(g, seed=42, utility0="exp")
+    ensure_route_margin(case, g.k)
+    dA, dB = DeviceCase(case), DeviceCase(case)
+    pk.pikv_decode_step(dA.desc, dA.q, dA.W_r, dA.bias, None, None, dA.K_tab, dA.V_tab, None, None,
+                        dA.n_valid, dA.utility, g.k, pk.COMBINE_LOCAL, 0.0, 1.0, dA.topk, dA.gates,
+                        None, None, dA.y, dA.row_max, dA.row_norm, dA.scores, dA.slot_coef, dA.workspace)
+    dB.route()
+    dB.attend(combine=pk.COMBINE_LOCAL)
+    dB.update_utility(1.0)
+    for name in ("topk", "y", "utility", "n_valid"):
+        np.testing.assert_array_equal(t2n(getattr(dA, name)), t2n(getattr(dB, name)))
+    # per-head routing is not served by the fused step
+    g2 = wl.Geometry(B=1, Hq=4, Hkv=4, D=64, E=4, S=32, k=2, dtype="f32", per_head_routing=True)
+    d2 = DeviceCase(wl.make_host_case(g2, seed=1))
+    with pytest.raises(pk.PikvError) as ei:
+        pk.pikv_decode_step(d2.desc, d2.q, d2.W_r, None, None, None, d2.K_tab, d2.V_tab, None, None,
+                            d2.n_valid, d2.utility, g2.k, pk.COMBINE_LSE, 0.0, 1.0, d2.topk, d2.gates,
+                            None, None, d2.y, d2.row_max, d2.row_norm, d2.scores, d2.slot_coef, d2.workspace)
+    assert ei.value.status == -2
