@@ -41,6 +41,9 @@ def parse_args():
     ap.add_argument("--cpu-steps", type=int, default=-1, help="oracle steps timed (0: skip, -1: auto)")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="run a plain 1 GiB device copy 8 times and exit (reference for the "
+                         "rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")
     return ap.parse_args()
 
 
@@ -175,6 +178,16 @@ def main():
     pk.load_library()
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if args.calibrate_copy:
+        n = 1 << 30
+        src = torch.empty(n, device=dev, dtype=torch.uint8).random_(0, 255)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        for _ in range(8):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy_bytes_read": n, "calibrate_copy_bytes_written": n, "launches": 8}))
+        return
     geo = wl.CONFIGS[args.config]
     n_layers = args.layers or DEFAULT_LAYERS[args.config]
     raw = wl.make_device_layers(geo, n_layers, args.seed, dev, **RECIPE[args.config])
