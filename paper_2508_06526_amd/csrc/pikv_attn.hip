@@ -15,6 +15,7 @@
 // y = (sum_i p_i code_i) U_V, so the streamed bytes are the codes and the decode costs
 // O(rank) per entry (the paper's T_decode is linear in the compressed width, eq. 2).
 #include "pikv_common.h"
+#include "pikv_combine_dev.h"
 
 #include <math.h>
 
@@ -578,176 +579,11 @@ __global__ __launch_bounds__(kWavesPerBlock *kWave, 3) void attn_partial_gqa128(
     }
 }
 
-struct CombineParams {
-    const float *part_acc;
-    const float *part_ml;
-    const float *gates;
-    const void *U_V;
-    float *y;
-    float *row_max;
-    float *row_norm;
-    float *slot_coef;
-    int Hq, G, D, W, k, rr, rank, nsplit, combine;
-};
-
 constexpr int kCombineThreads = 1024;
-constexpr int kCombinePrefetch = 4;         // partial rows each thread loads before the weights exist
-constexpr int kMaxPartialsPerHead = 2048;   // k * nsplit
 
-// One block per (sequence, query head).  The partial accumulators do not depend on the
-// weights, so their loads are issued first and overlap the whole weight computation:
-//   phase 0: every thread = (slice of partials, float4 column group) issues its first
-//            accumulator loads; (max, sum) of every partial goes to LDS.
-//   phase 1: one wave per selected shard reduces its splits to (max, normaliser).
-//   phase 2: one thread forms the k gate-weighted shard weights in either combine mode.
-//   phase 3: weighted sum of the accumulators, slices reduced through LDS in fixed order.
 template <typename T>
 __global__ __launch_bounds__(kCombineThreads) void attn_combine(CombineParams p) {
-    const int bh = blockIdx.x;
-    const int b = bh / p.Hq, h = bh - b * p.Hq;
-    const int hk = h / p.G;
-    const int tid = threadIdx.x;
-    const int lane = tid & (kWave - 1), wave = tid >> 6;
-    const int np = p.k * p.nsplit;
-
-    __shared__ float wt[kMaxPartialsPerHead];   // max of every partial, later its weight
-    __shared__ float ls[kMaxPartialsPerHead];
-    __shared__ float Mj[64], Zj[64], shard_w[64];
-    __shared__ float4 red[kCombineThreads];
-    __shared__ float ycode[128];
-
-    const int cgroups = p.W / 4;                       // float4 column groups: 4..32
-    const int slices = kCombineThreads / cgroups;      // partial slices: 256..32
-    const int cg = tid % cgroups, sl = tid / cgroups;
-    const float *acc = p.part_acc + (int64_t)bh * np * p.W + cg * 4;
-    float4 pre[kCombinePrefetch];
-#pragma unroll
-    for (int u = 0; u < kCombinePrefetch; ++u) {
-        const int i = sl + u * slices;
-        pre[u] = i < np ? *reinterpret_cast<const float4 *>(acc + (int64_t)i * p.W)
-                        : make_float4(0.f, 0.f, 0.f, 0.f);
-    }
-
-    const float *ml = p.part_ml + (int64_t)bh * np * 2;
-    for (int i = tid; i < np; i += kCombineThreads) {
-        const float2 v = *reinterpret_cast<const float2 *>(ml + 2 * i);
-        wt[i] = v.x;
-        ls[i] = v.y;
-    }
-    __syncthreads();
-    for (int j = wave; j < p.k; j += kCombineThreads / kWave) {
-        float M = -INFINITY;
-        for (int s = lane; s < p.nsplit; s += kWave)
-            if (ls[j * p.nsplit + s] > 0.0f) M = fmaxf(M, wt[j * p.nsplit + s]);
-#pragma unroll
-        for (int off = 32; off >= 1; off >>= 1) M = fmaxf(M, __shfl_xor(M, off, kWave));
-        float Z = 0.0f;
-        for (int s = lane; s < p.nsplit; s += kWave)
-            if (ls[j * p.nsplit + s] > 0.0f) Z += ls[j * p.nsplit + s] * __expf(wt[j * p.nsplit + s] - M);
-#pragma unroll
-        for (int off = 32; off >= 1; off >>= 1) Z += __shfl_xor(Z, off, kWave);
-        if (lane == 0) {
-            Mj[j] = M;
-            Zj[j] = Z;
-        }
-    }
-    __syncthreads();
-    if (tid == 0) {
-        const int row = b * p.rr + (p.rr == 1 ? 0 : h);
-        const float *g = p.gates ? p.gates + (int64_t)row * p.k : nullptr;
-        float M = -INFINITY, norm = 0.0f;
-        for (int j = 0; j < p.k; ++j)
-            if (Zj[j] > 0.0f) M = fmaxf(M, Mj[j]);
-        if (p.combine == PIKV_COMBINE_LSE) {
-            for (int j = 0; j < p.k; ++j)
-                if (Zj[j] > 0.0f) norm += (g ? g[j] : 1.0f) * Zj[j] * __expf(Mj[j] - M);
-            for (int j = 0; j < p.k; ++j) {
-                const bool live = Zj[j] > 0.0f;
-                const float gj = g ? g[j] : 1.0f;
-                shard_w[j] = live ? gj * __expf(Mj[j] - M) / norm : 0.0f;
-                if (p.slot_coef) {
-                    p.slot_coef[((int64_t)bh * p.k + j) * 2 + 0] = live ? M : 0.0f;
-                    p.slot_coef[((int64_t)bh * p.k + j) * 2 + 1] = live ? gj / norm : 0.0f;
-                }
-            }
-        } else {
-            for (int j = 0; j < p.k; ++j)
-                if (Zj[j] > 0.0f) norm += g ? g[j] : 1.0f;
-            for (int j = 0; j < p.k; ++j) {
-                const bool live = Zj[j] > 0.0f;
-                const float gj = g ? g[j] : 1.0f;
-                shard_w[j] = live ? gj / (norm * Zj[j]) : 0.0f;
-                if (p.slot_coef) {
-                    p.slot_coef[((int64_t)bh * p.k + j) * 2 + 0] = live ? Mj[j] : 0.0f;
-                    p.slot_coef[((int64_t)bh * p.k + j) * 2 + 1] = shard_w[j];
-                }
-            }
-        }
-        if (p.row_max) p.row_max[bh] = M;
-        if (p.row_norm) p.row_norm[bh] = norm;
-    }
-    __syncthreads();
-    // weight of every partial: shard weight * exp(m_split - M_shard)
-    for (int i = tid; i < np; i += kCombineThreads) {
-        const int j = i / p.nsplit;
-        wt[i] = ls[i] > 0.0f ? shard_w[j] * __expf(wt[i] - Mj[j]) : 0.0f;
-    }
-    __syncthreads();
-
-    float4 a = make_float4(0.f, 0.f, 0.f, 0.f);
-#pragma unroll
-    for (int u = 0; u < kCombinePrefetch; ++u) {
-        const int i = sl + u * slices;
-        const float w = i < np ? wt[i] : 0.0f;
-        a.x = fmaf(w, pre[u].x, a.x);
-        a.y = fmaf(w, pre[u].y, a.y);
-        a.z = fmaf(w, pre[u].z, a.z);
-        a.w = fmaf(w, pre[u].w, a.w);
-    }
-    for (int i = sl + kCombinePrefetch * slices; i < np; i += slices) {
-        const float w = wt[i];
-        const float4 v = *reinterpret_cast<const float4 *>(acc + (int64_t)i * p.W);
-        a.x = fmaf(w, v.x, a.x);
-        a.y = fmaf(w, v.y, a.y);
-        a.z = fmaf(w, v.z, a.z);
-        a.w = fmaf(w, v.w, a.w);
-    }
-    red[tid] = a;
-    __syncthreads();
-    // fixed-order tree over the slices (slices is a power of two)
-    for (int half = slices >> 1; half >= 1; half >>= 1) {
-        if (sl < half) {
-            const float4 v = red[tid + half * cgroups];
-            float4 t = red[tid];
-            t.x += v.x;
-            t.y += v.y;
-            t.z += v.z;
-            t.w += v.w;
-            red[tid] = t;
-        }
-        __syncthreads();
-    }
-    if (tid < cgroups) {
-        const float4 t = red[tid];
-        if (p.rank == 0) {
-            *reinterpret_cast<float4 *>(p.y + (int64_t)bh * p.D + tid * 4) = t;
-        } else {
-            ycode[tid * 4 + 0] = t.x;
-            ycode[tid * 4 + 1] = t.y;
-            ycode[tid * 4 + 2] = t.z;
-            ycode[tid * 4 + 3] = t.w;
-        }
-    }
-    if (p.rank != 0) {  // value decoder: y = ycode U_V[h']
-        __syncthreads();
-        const T *U = static_cast<const T *>(p.U_V) + (int64_t)hk * p.rank * p.D;
-        for (int d = tid; d < p.D; d += kCombineThreads) {
-            float a2 = 0.0f;
-            for (int cidx = 0; cidx < p.rank; ++cidx)
-                a2 = fmaf(ycode[cidx], load_scalar<T>(U, (int64_t)cidx * p.D + d), a2);
-            p.y[(int64_t)bh * p.D + d] = a2;
-        }
-    }
+    combine_head<T, kCombineThreads>(p, blockIdx.x);
 }
 
 template <typename T, int W>
@@ -834,13 +670,16 @@ extern "C" size_t pikv_attn_workspace_bytes(const pikv_desc *desc, int32_t k) {
     return acc + ml + 256;
 }
 
-extern "C" int pikv_sharded_attn(const pikv_desc *desc, const void *q, const void *const *K_shards,
-                                 const void *const *V_shards, const void *U_K, const void *U_V,
-                                 const int32_t *n_valid, const int32_t *topk_idx,
-                                 const float *gates, int32_t k, int32_t combine, float scale,
-                                 float *y, float *row_max, float *row_norm, float *scores,
-                                 float *slot_coef, void *workspace, size_t workspace_bytes,
-                                 void *stream) {
+namespace pikv {
+
+// Validate, plan and launch the split pass only; fills the parameters of the merge pass.
+int launch_attn_partial(const pikv_desc *desc, const void *q, const void *const *K_shards,
+                        const void *const *V_shards, const void *U_K, const void *U_V,
+                        const int32_t *n_valid, const int32_t *topk_idx, const float *gates,
+                        int32_t k, int32_t combine, float scale, float *y, float *row_max,
+                        float *row_norm, float *scores, float *slot_coef, void *workspace,
+                        size_t workspace_bytes, void *stream, AttnPlan *plan_out,
+                        CombineParams *c_out) {
     AttnPlan plan;
     const int rc = make_attn_plan(desc, k, &plan);
     if (rc != PIKV_OK) return rc;
@@ -848,6 +687,7 @@ extern "C" int pikv_sharded_attn(const pikv_desc *desc, const void *q, const voi
     if (desc->rank > 0 && (!U_K || !U_V)) return PIKV_ERR_INVALID;
     if (combine != PIKV_COMBINE_LSE && combine != PIKV_COMBINE_LOCAL) return PIKV_ERR_INVALID;
     if (!(scale == scale)) return PIKV_ERR_INVALID;
+    *plan_out = plan;
     if (desc->B == 0) return PIKV_OK;
     const size_t need = pikv_attn_workspace_bytes(desc, k);
     if (!workspace || workspace_bytes < need) return PIKV_ERR_WORKSPACE;
@@ -890,10 +730,11 @@ extern "C" int pikv_sharded_attn(const pikv_desc *desc, const void *q, const voi
         hipLaunchKernelGGL(attn_partial_gqa128, dim3((unsigned)blocks64), dim3(kWavesPerBlock * kWave),
                            0, st, p);
         lrc = launch_status();
-    } else
+    } else {
         lrc = desc->dtype == PIKV_F32
                   ? launch_partial<float>(W, plan.heads_per_block, p, (int)blocks64, st)
                   : launch_partial<bf16>(W, plan.heads_per_block, p, (int)blocks64, st);
+    }
     if (lrc != PIKV_OK) return lrc;
 
     CombineParams c;
@@ -914,10 +755,35 @@ extern "C" int pikv_sharded_attn(const pikv_desc *desc, const void *q, const voi
     c.rank = desc->rank;
     c.nsplit = plan.nsplit;
     c.combine = combine;
+    *c_out = c;
+    return PIKV_OK;
+}
+
+}  // namespace pikv
+
+namespace pikv {
+int pikv_sharded_attn_merge(const pikv_desc *desc, const CombineParams *c, void *stream) {
     const dim3 cgrid(desc->B * desc->Hq), cblock(kCombineThreads);
     if (desc->dtype == PIKV_F32)
-        hipLaunchKernelGGL(attn_combine<float>, cgrid, cblock, 0, st, c);
+        hipLaunchKernelGGL(attn_combine<float>, cgrid, cblock, 0, as_stream(stream), *c);
     else
-        hipLaunchKernelGGL(attn_combine<bf16>, cgrid, cblock, 0, st, c);
+        hipLaunchKernelGGL(attn_combine<bf16>, cgrid, cblock, 0, as_stream(stream), *c);
     return launch_status();
+}
+}  // namespace pikv
+
+extern "C" int pikv_sharded_attn(const pikv_desc *desc, const void *q, const void *const *K_shards,
+                                 const void *const *V_shards, const void *U_K, const void *U_V,
+                                 const int32_t *n_valid, const int32_t *topk_idx,
+                                 const float *gates, int32_t k, int32_t combine, float scale,
+                                 float *y, float *row_max, float *row_norm, float *scores,
+                                 float *slot_coef, void *workspace, size_t workspace_bytes,
+                                 void *stream) {
+    AttnPlan plan;
+    CombineParams c;
+    const int rc = launch_attn_partial(desc, q, K_shards, V_shards, U_K, U_V, n_valid, topk_idx, gates,
+                                       k, combine, scale, y, row_max, row_norm, scores, slot_coef,
+                                       workspace, workspace_bytes, stream, &plan, &c);
+    if (rc != PIKV_OK || desc->B == 0) return rc;
+    return pikv_sharded_attn_merge(desc, &c, stream);
 }

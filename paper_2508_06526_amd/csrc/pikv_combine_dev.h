@@ -1,0 +1,233 @@
+// Merging the split partials of the attention pass (PiKV Algorithm 1, f_attn over C[g_t], with
+// the router gates): device code shared by the stand-alone combine kernel and the fused
+// post-attention kernel of the decode step.
+#pragma once
+
+#include "pikv_common.h"
+
+#include <math.h>
+
+namespace pikv {
+
+struct CombineParams {
+    const float *part_acc;
+    const float *part_ml;
+    const float *gates;
+    const void *U_V;
+    float *y;
+    float *row_max;
+    float *row_norm;
+    float *slot_coef;
+    int Hq, G, D, W, k, rr, rank, nsplit, combine;
+};
+
+constexpr int kCombinePrefetch = 4;         // partial rows each thread loads before the weights exist
+constexpr int kMaxPartialsPerHead = 2048;   // k * nsplit
+
+// (max, normaliser) of one selected shard from its nsplit partial (max, sum) pairs, computed by
+// a group of 8 adjacent lanes: lane `sub` takes splits sub, sub+8, ... in ascending order, the
+// 8 lane results are joined by an xor butterfly.  Every caller uses this one arrangement, so the
+// stand-alone and the fused kernels produce identical bits.  `get(s)` returns split s's pair;
+// all 8 lanes of a group must call together (pass nsplit = 0 for a padding group).
+template <class F>
+__device__ __forceinline__ void shard_stats8(int nsplit, int sub, F get, float *M_out, float *Z_out) {
+    float M = -INFINITY;
+    for (int s = sub; s < nsplit; s += 8) {
+        const float2 v = get(s);
+        M = v.y > 0.0f ? fmaxf(M, v.x) : M;
+    }
+    M = fmaxf(M, __shfl_xor(M, 1, kWave));
+    M = fmaxf(M, __shfl_xor(M, 2, kWave));
+    M = fmaxf(M, __shfl_xor(M, 4, kWave));
+    float Z = 0.0f;
+    for (int s = sub; s < nsplit; s += 8) {
+        const float2 v = get(s);
+        Z += v.y > 0.0f ? v.y * __expf(v.x - M) : 0.0f;
+    }
+    Z += __shfl_xor(Z, 1, kWave);
+    Z += __shfl_xor(Z, 2, kWave);
+    Z += __shfl_xor(Z, 4, kWave);
+    *M_out = M;
+    *Z_out = Z;
+}
+
+// The k shard weights of one query head in either combine mode, from the per-shard
+// (max, normaliser).  Outputs per shard j: weight w[j] of its un-normalised accumulator and
+// the (shift, coef) pair with p_i = coef * exp(s_i - shift); returns the row max / normaliser.
+__device__ __forceinline__ void head_weights(int k, const float *Mj, const float *Zj, const float *g,
+                                             int combine, float *w, float *shift, float *coef,
+                                             float *M_out, float *norm_out) {
+    float M = -INFINITY, norm = 0.0f;
+    for (int j = 0; j < k; ++j)
+        if (Zj[j] > 0.0f) M = fmaxf(M, Mj[j]);
+    if (combine == PIKV_COMBINE_LSE) {
+        for (int j = 0; j < k; ++j)
+            if (Zj[j] > 0.0f) norm += (g ? g[j] : 1.0f) * Zj[j] * __expf(Mj[j] - M);
+        for (int j = 0; j < k; ++j) {
+            const bool live = Zj[j] > 0.0f;
+            const float gj = g ? g[j] : 1.0f;
+            if (w) w[j] = live ? gj * __expf(Mj[j] - M) / norm : 0.0f;
+            shift[j] = live ? M : 0.0f;
+            coef[j] = live ? gj / norm : 0.0f;
+        }
+    } else {
+        for (int j = 0; j < k; ++j)
+            if (Zj[j] > 0.0f) norm += g ? g[j] : 1.0f;
+        for (int j = 0; j < k; ++j) {
+            const bool live = Zj[j] > 0.0f;
+            const float gj = g ? g[j] : 1.0f;
+            const float wj = live ? gj / (norm * Zj[j]) : 0.0f;
+            if (w) w[j] = wj;
+            shift[j] = live ? Mj[j] : 0.0f;
+            coef[j] = wj;
+        }
+    }
+    *M_out = M;
+    *norm_out = norm;
+}
+
+// One block (THREADS threads) merges the k * nsplit partials of head `bh`.  The partial
+// accumulators do not depend on the weights, so their loads are issued first and overlap the
+// whole weight computation:
+//   phase 0: every thread = (slice of partials, float4 column group) issues its first
+//            accumulator loads; (max, sum) of every partial goes to LDS.
+//   phase 1: 8 lanes per selected shard reduce its splits to (max, normaliser).
+//   phase 2: one thread forms the k gate-weighted shard weights in either combine mode.
+//   phase 3: weighted sum of the accumulators, slices reduced through LDS in fixed order,
+//            then (rank > 0) the value decoder y = ycode U_V[h'].
+template <typename T, int THREADS>
+__device__ __forceinline__ void combine_head(const CombineParams &p, int bh) {
+    const int b = bh / p.Hq, h = bh - b * p.Hq;
+    const int hk = h / p.G;
+    const int tid = threadIdx.x;
+    const int np = p.k * p.nsplit;
+
+    __shared__ float wt[kMaxPartialsPerHead];   // max of every partial, later its weight
+    __shared__ float ls[kMaxPartialsPerHead];
+    __shared__ float Mj[64], Zj[64], shard_w[64], sh_shift[64], sh_coef[64], g_s[64];
+    __shared__ float4 red[THREADS];
+    __shared__ float ycode[128];
+
+    const int cgroups = p.W / 4;                 // float4 column groups: 4..32
+    const int slices = THREADS / cgroups;        // partial slices
+    const int cg = tid % cgroups, sl = tid / cgroups;
+    const float *acc = p.part_acc + (int64_t)bh * np * p.W + cg * 4;
+    float4 pre[kCombinePrefetch];
+#pragma unroll
+    for (int u = 0; u < kCombinePrefetch; ++u) {
+        const int i = sl + u * slices;
+        pre[u] = i < np ? *reinterpret_cast<const float4 *>(acc + (int64_t)i * p.W)
+                        : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+
+    // the gates are read once into LDS: head_weights walks them several times
+    if (p.gates != nullptr && tid < p.k)
+        g_s[tid] = p.gates[(int64_t)(b * p.rr + (p.rr == 1 ? 0 : h)) * p.k + tid];
+    const float *ml = p.part_ml + (int64_t)bh * np * 2;
+    for (int i = tid; i < np; i += THREADS) {
+        const float2 v = *reinterpret_cast<const float2 *>(ml + 2 * i);
+        wt[i] = v.x;
+        ls[i] = v.y;
+    }
+    __syncthreads();
+    for (int j0 = 0; j0 < p.k; j0 += THREADS / 8) {   // 8 lanes per selected shard
+        const int j = j0 + tid / 8;
+        float M, Z;
+        shard_stats8(j < p.k ? p.nsplit : 0, tid & 7,
+                     [&](int sp) { return make_float2(wt[j * p.nsplit + sp], ls[j * p.nsplit + sp]); }, &M, &Z);
+        if (j < p.k && (tid & 7) == 0) {
+            Mj[j] = M;
+            Zj[j] = Z;
+        }
+    }
+    __syncthreads();
+    if (tid == 0) {
+        float M, norm;
+        head_weights(p.k, Mj, Zj, p.gates ? g_s : nullptr, p.combine, shard_w, sh_shift, sh_coef, &M,
+                     &norm);
+        if (p.slot_coef) {
+            for (int j = 0; j < p.k; ++j) {
+                p.slot_coef[((int64_t)bh * p.k + j) * 2 + 0] = sh_shift[j];
+                p.slot_coef[((int64_t)bh * p.k + j) * 2 + 1] = sh_coef[j];
+            }
+        }
+        if (p.row_max) p.row_max[bh] = M;
+        if (p.row_norm) p.row_norm[bh] = norm;
+    }
+    __syncthreads();
+    // weight of every partial: shard weight * exp(m_split - M_shard)
+    for (int i = tid; i < np; i += THREADS) {
+        const int j = i / p.nsplit;
+        wt[i] = ls[i] > 0.0f ? shard_w[j] * __expf(wt[i] - Mj[j]) : 0.0f;
+    }
+    __syncthreads();
+
+    float4 a = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+    for (int u = 0; u < kCombinePrefetch; ++u) {
+        const int i = sl + u * slices;
+        const float w = i < np ? wt[i] : 0.0f;
+        a.x = fmaf(w, pre[u].x, a.x);
+        a.y = fmaf(w, pre[u].y, a.y);
+        a.z = fmaf(w, pre[u].z, a.z);
+        a.w = fmaf(w, pre[u].w, a.w);
+    }
+    for (int i = sl + kCombinePrefetch * slices; i < np; i += slices) {
+        const float w = wt[i];
+        const float4 v = *reinterpret_cast<const float4 *>(acc + (int64_t)i * p.W);
+        a.x = fmaf(w, v.x, a.x);
+        a.y = fmaf(w, v.y, a.y);
+        a.z = fmaf(w, v.z, a.z);
+        a.w = fmaf(w, v.w, a.w);
+    }
+    red[tid] = a;
+    __syncthreads();
+    // fixed-order tree over the slices (slices is a power of two)
+    for (int half = slices >> 1; half >= 1; half >>= 1) {
+        if (sl < half) {
+            const float4 v = red[tid + half * cgroups];
+            float4 t = red[tid];
+            t.x += v.x;
+            t.y += v.y;
+            t.z += v.z;
+            t.w += v.w;
+            red[tid] = t;
+        }
+        __syncthreads();
+    }
+    if (tid < cgroups) {
+        const float4 t = red[tid];
+        if (p.rank == 0) {
+            *reinterpret_cast<float4 *>(p.y + (int64_t)bh * p.D + tid * 4) = t;
+        } else {
+            ycode[tid * 4 + 0] = t.x;
+            ycode[tid * 4 + 1] = t.y;
+            ycode[tid * 4 + 2] = t.z;
+            ycode[tid * 4 + 3] = t.w;
+        }
+    }
+    if (p.rank != 0) {  // value decoder: y = ycode U_V[h']
+        __syncthreads();
+        const T *U = static_cast<const T *>(p.U_V) + (int64_t)hk * p.rank * p.D;
+        for (int d = tid; d < p.D; d += THREADS) {
+            float a2 = 0.0f;
+            for (int cidx = 0; cidx < p.rank; ++cidx)
+                a2 = fmaf(ycode[cidx], load_scalar<T>(U, (int64_t)cidx * p.D + d), a2);
+            p.y[(int64_t)bh * p.D + d] = a2;
+        }
+    }
+}
+
+// Host side (pikv_attn.hip): validate, plan and launch the split pass only, and fill the
+// parameters of the merge pass.
+int launch_attn_partial(const pikv_desc *desc, const void *q, const void *const *K_shards,
+                        const void *const *V_shards, const void *U_K, const void *U_V,
+                        const int32_t *n_valid, const int32_t *topk_idx, const float *gates,
+                        int32_t k, int32_t combine, float scale, float *y, float *row_max,
+                        float *row_norm, float *scores, float *slot_coef, void *workspace,
+                        size_t workspace_bytes, void *stream, AttnPlan *plan_out,
+                        CombineParams *c_out);
+
+int pikv_sharded_attn_merge(const pikv_desc *desc, const CombineParams *c, void *stream);
+
+}  // namespace pikv

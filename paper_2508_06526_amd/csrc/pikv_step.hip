@@ -14,6 +14,7 @@
 // Separate launches for the first stage cost ~2.4 us of dispatch each on MI355X, more than
 // the work itself; fusing them removes two launches and two dependent memory round trips.
 #include "pikv_common.h"
+#include "pikv_combine_dev.h"
 #include "pikv_route_dev.h"
 
 namespace pikv {
@@ -132,6 +133,113 @@ __global__ __launch_bounds__(kRouteThreads) void step_pre(PreParams p) {
     }
 }
 
+// Post-attention stage of the fused step: the merge of the split partials (one block per
+// query head, as in the stand-alone combine kernel) and the utility update in ONE launch.
+// A utility block (256 slots of a visited shard x 4 groups of heads) cannot wait for the merge
+// blocks, so it recomputes the per-head softmax statistics itself from the (max, sum) pairs of
+// the partials - a few KiB from L2 and the same arithmetic, hence the same bits - while its
+// score loads are already in flight.
+constexpr int kPostThreads = 1024;     // same block shape as the stand-alone merge: identical bits
+constexpr int kPostSlots = 256;        // slots per utility block; 4 head groups per slot
+constexpr int kPostMaxShards = 2048;   // Hq * k
+constexpr int kPostPrefetchHeads = 8;  // score loads each thread issues before the statistics
+
+struct PostParams {
+    CombineParams c;
+    const float *scores;
+    const int32_t *n_valid;
+    const int32_t *topk;
+    float *utility;
+    int B, E, S, tiles;
+    float decay;
+};
+
+template <typename T>
+__global__ __launch_bounds__(kPostThreads) void step_post(PostParams p) {
+    const int ncomb = p.B * p.c.Hq;
+    if ((int)blockIdx.x < ncomb) {
+        combine_head<T, kPostThreads>(p.c, blockIdx.x);
+        return;
+    }
+    int bid = blockIdx.x - ncomb;
+    const int tile = bid % p.tiles;
+    bid /= p.tiles;
+    const int e = bid % p.E;
+    const int b = bid / p.E;
+    const int tid = threadIdx.x;
+    const int Hq = p.c.Hq, k = p.c.k, nsplit = p.c.nsplit;
+    const int np = k * nsplit;
+
+    int j = -1;
+    for (int jj = 0; jj < k; ++jj)
+        if (p.topk[(int64_t)b * k + jj] == e) j = jj;
+    const int n = p.n_valid[(int64_t)b * p.E + e];
+    const int i0 = tile * kPostSlots;
+    if (j < 0 || i0 >= n) return;
+
+    __shared__ float Mj_s[kPostMaxShards], Zj_s[kPostMaxShards];
+    __shared__ float shift_s[kPostMaxShards], coef_s[kPostMaxShards];
+    __shared__ float g_s[64];
+    __shared__ float part_s[4][kPostSlots];
+
+    // thread = (slot, head group); the heads are cut into 4 consecutive groups, each summed in
+    // ascending order, the groups joined as (g0 + g1) + (g2 + g3) - the order the stand-alone
+    // utility kernel uses too
+    const int slot = tid & (kPostSlots - 1), hg = tid / kPostSlots;
+    const int gsize = (Hq + 3) / 4;
+    const int h_lo = hg * gsize, h_hi = min(Hq, h_lo + gsize);
+    const int i = i0 + slot;
+    const bool live = i < n;
+    float sc[kPostPrefetchHeads];
+#pragma unroll
+    for (int t = 0; t < kPostPrefetchHeads; ++t) {
+        const int h = h_lo + t;
+        sc[t] = (h < h_hi && live) ? p.scores[(((int64_t)b * Hq + h) * k + j) * p.S + i] : 0.0f;
+    }
+    float *uptr = p.utility + ((int64_t)b * p.E + e) * p.S + i;
+    const float u_old = (live && hg == 0) ? *uptr : 0.0f;
+    if (p.c.gates != nullptr && tid < k) g_s[tid] = p.c.gates[(int64_t)b * k + tid];
+
+    // softmax statistics of every (head, selected shard): 8 lanes each, pairs read from L2
+    const float *ml = p.c.part_ml + (int64_t)b * Hq * np * 2;
+    for (int t0 = 0; t0 < Hq * k; t0 += kPostThreads / 8) {
+        const int t = t0 + tid / 8;
+        const bool real = t < Hq * k;
+        float M, Z;
+        shard_stats8(real ? nsplit : 0, tid & 7,
+                     [&](int sp) { return *reinterpret_cast<const float2 *>(ml + 2 * ((int64_t)t * nsplit + sp)); },
+                     &M, &Z);
+        if (real && (tid & 7) == 0) {
+            Mj_s[t] = M;
+            Zj_s[t] = Z;
+        }
+    }
+    __syncthreads();
+    for (int h = tid; h < Hq; h += kPostThreads) {
+        float M, norm;
+        head_weights(k, Mj_s + h * k, Zj_s + h * k, p.c.gates ? g_s : nullptr, p.c.combine, nullptr,
+                     shift_s + h * k, coef_s + h * k, &M, &norm);
+    }
+    __syncthreads();
+    float a = 0.0f;
+    if (live) {
+#pragma unroll
+        for (int t = 0; t < kPostPrefetchHeads; ++t) {
+            const int h = h_lo + t;
+            if (h < h_hi) a = fmaf(coef_s[h * k + j], __expf(sc[t] - shift_s[h * k + j]), a);
+        }
+        for (int h = h_lo + kPostPrefetchHeads; h < h_hi; ++h)
+            a = fmaf(coef_s[h * k + j],
+                     __expf(p.scores[(((int64_t)b * Hq + h) * k + j) * p.S + i] - shift_s[h * k + j]), a);
+    }
+    part_s[hg][slot] = a;
+    __syncthreads();
+    if (hg == 0 && live) {
+        const float total = (part_s[0][slot] + part_s[1][slot]) + (part_s[2][slot] + part_s[3][slot]);
+        *uptr = fmaf(p.decay, u_old, total);
+    }
+}
+
 }  // namespace
 }  // namespace pikv
 
@@ -194,9 +302,35 @@ extern "C" int pikv_decode_step(const pikv_desc *desc, const void *q, const void
         hipLaunchKernelGGL(step_pre<bf16>, dim3(desc->B * k), dim3(kRouteThreads), 0, st, p);
     int lrc = launch_status();
     if (lrc != PIKV_OK) return lrc;
-    lrc = pikv_sharded_attn(desc, q, K_shards, V_shards, U_K, U_V, n_valid, topk_idx, gates, k,
-                            combine, scale, y, row_max, row_norm, scores, slot_coef, workspace,
-                            workspace_bytes, stream);
+    AttnPlan plan;
+    CombineParams c;
+    lrc = launch_attn_partial(desc, q, K_shards, V_shards, U_K, U_V, n_valid, topk_idx, gates, k,
+                              combine, scale, y, row_max, row_norm, scores, slot_coef, workspace,
+                              workspace_bytes, stream, &plan, &c);
     if (lrc != PIKV_OK) return lrc;
-    return pikv_update_utility(desc, scores, slot_coef, n_valid, topk_idx, k, decay, utility, stream);
+    if ((int64_t)desc->Hq * k > kPostMaxShards) {
+        // too many partials to restage per utility block: separate merge and utility launches
+        lrc = pikv_sharded_attn_merge(desc, &c, stream);
+        if (lrc != PIKV_OK) return lrc;
+        return pikv_update_utility(desc, scores, slot_coef, n_valid, topk_idx, k, decay, utility,
+                                   stream);
+    }
+    PostParams pp;
+    pp.c = c;
+    pp.scores = scores;
+    pp.n_valid = n_valid;
+    pp.topk = topk_idx;
+    pp.utility = utility;
+    pp.B = desc->B;
+    pp.E = desc->E;
+    pp.S = desc->S;
+    pp.tiles = (desc->S + kPostSlots - 1) / kPostSlots;
+    pp.decay = decay;
+    const int64_t blocks = (int64_t)desc->B * desc->Hq + (int64_t)desc->B * desc->E * pp.tiles;
+    if (blocks > 0x7fffffff) return PIKV_ERR_UNSUPPORTED;
+    if (desc->dtype == PIKV_F32)
+        hipLaunchKernelGGL(step_post<float>, dim3((unsigned)blocks), dim3(kPostThreads), 0, st, pp);
+    else
+        hipLaunchKernelGGL(step_post<bf16>, dim3((unsigned)blocks), dim3(kPostThreads), 0, st, pp);
+    return launch_status();
 }

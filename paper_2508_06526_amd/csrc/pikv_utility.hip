@@ -71,22 +71,32 @@ __global__ __launch_bounds__(kUtilThreads) void utility_kernel(UtilParams p) {
 
     const int i = i0 + tid;
     if (i >= n) return;
-    float a = 0.0f;
-    int t = 0;
-    for (; t + 4 <= nact; t += 4) {   // four independent loads in flight per thread
-        const float s0 = p.scores[(int64_t)head_off[t + 0] * p.S + i];
-        const float s1 = p.scores[(int64_t)head_off[t + 1] * p.S + i];
-        const float s2 = p.scores[(int64_t)head_off[t + 2] * p.S + i];
-        const float s3 = p.scores[(int64_t)head_off[t + 3] * p.S + i];
-        a += head_coef[t + 0] * __expf(s0 - head_shift[t + 0]);
-        a += head_coef[t + 1] * __expf(s1 - head_shift[t + 1]);
-        a += head_coef[t + 2] * __expf(s2 - head_shift[t + 2]);
-        a += head_coef[t + 3] * __expf(s3 - head_shift[t + 3]);
+    // the active heads are cut into 4 consecutive groups, each summed in ascending order, the
+    // groups joined as (g0 + g1) + (g2 + g3): the fused step kernel spreads the groups over
+    // threads and must reproduce these bits
+    const int gsize = (nact + 3) / 4;
+    float part[4];
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+        const int lo = g * gsize, hi = min(nact, lo + gsize);
+        float a = 0.0f;
+        int t = lo;
+        for (; t + 4 <= hi; t += 4) {   // four independent loads in flight per thread
+            const float s0 = p.scores[(int64_t)head_off[t + 0] * p.S + i];
+            const float s1 = p.scores[(int64_t)head_off[t + 1] * p.S + i];
+            const float s2 = p.scores[(int64_t)head_off[t + 2] * p.S + i];
+            const float s3 = p.scores[(int64_t)head_off[t + 3] * p.S + i];
+            a = fmaf(head_coef[t + 0], __expf(s0 - head_shift[t + 0]), a);
+            a = fmaf(head_coef[t + 1], __expf(s1 - head_shift[t + 1]), a);
+            a = fmaf(head_coef[t + 2], __expf(s2 - head_shift[t + 2]), a);
+            a = fmaf(head_coef[t + 3], __expf(s3 - head_shift[t + 3]), a);
+        }
+        for (; t < hi; ++t)
+            a = fmaf(head_coef[t], __expf(p.scores[(int64_t)head_off[t] * p.S + i] - head_shift[t]), a);
+        part[g] = a;
     }
-    for (; t < nact; ++t)
-        a += head_coef[t] * __expf(p.scores[(int64_t)head_off[t] * p.S + i] - head_shift[t]);
     float *u = p.utility + ((int64_t)b * p.E + e) * p.S + i;
-    *u = fmaf(p.decay, *u, a);
+    *u = fmaf(p.decay, *u, (part[0] + part[1]) + (part[2] + part[3]));
 }
 
 }  // namespace
