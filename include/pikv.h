@@ -194,6 +194,14 @@ int pikv_decode_step(const pikv_desc *desc, const void *q, const void *W_r, cons
  * workspace after changing it.                                                             */
 void pikv_set_attn_split(int32_t nsplit);
 
+/* Profiling hook: two hipEvent_t (created with timing enabled, passed as void*) that every
+ * later pikv_sharded_attn / pikv_decode_step call records on its stream immediately before and
+ * after launching the split attention pass - the kernel that streams the K/V bytes - so that a
+ * caller can time exactly that kernel in its real context with hipEventElapsedTime.  NULL, NULL
+ * switches it off (the default).  Process-wide, not thread-safe; do not leave it set while a
+ * stream is being captured into a graph.                                                   */
+void pikv_set_profile_events(void *start_event, void *stop_event);
+
 /* Static description of a status code (host string, never NULL).                          */
 const char *pikv_strerror(int status);
 

@@ -16,7 +16,8 @@ F32, BF16 = 0, 1
 COMBINE_LSE, COMBINE_LOCAL = 0, 1
 
 EXPORTS = ("pikv_route", "pikv_attn_workspace_bytes", "pikv_sharded_attn", "pikv_update_utility",
-           "pikv_evict", "pikv_append", "pikv_strerror", "pikv_version", "pikv_set_attn_split", "pikv_decode_step")
+           "pikv_evict", "pikv_append", "pikv_strerror", "pikv_version", "pikv_set_attn_split", "pikv_decode_step",
+           "pikv_set_profile_events")
 
 
 class PikvError(RuntimeError):
@@ -72,6 +73,8 @@ def load_library():
     lib.pikv_decode_step.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, f32, f32,
                                      vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
     lib.pikv_decode_step.restype = C.c_int
+    lib.pikv_set_profile_events.argtypes = [vp, vp]
+    lib.pikv_set_profile_events.restype = None
     lib.pikv_set_attn_split.argtypes = [i32]
     lib.pikv_set_attn_split.restype = None
     lib.pikv_version.argtypes = []
@@ -150,6 +153,13 @@ def pikv_version() -> int:
 
 def pikv_set_attn_split(nsplit: int) -> None:
     load_library().pikv_set_attn_split(int(nsplit))
+
+
+def pikv_set_profile_events(start, stop) -> None:
+    """start/stop: torch.cuda.Event (timing enabled, already recorded once so that the HIP
+    event exists) or None/None to switch the hook off."""
+    h = lambda ev: None if ev is None else C.c_void_p(ev.cuda_event)
+    load_library().pikv_set_profile_events(h(start), h(stop))
 
 
 def pikv_route(x, W_r, bias, rows, d_r, E, k, topk_idx, gates, probs=None, stream=None):

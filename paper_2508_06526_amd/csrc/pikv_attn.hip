@@ -150,14 +150,27 @@ __global__ __launch_bounds__(kWavesPerBlock *kWave) void attn_partial(AttnParams
         for (int idx = tid; idx < GB * W; idx += blockDim.x)
             q_s[idx / W][idx % W] = p.scale * load_scalar<T>(qp, idx);   // W == D here
     } else {
+        // 8 lanes per (head, code column): 16-byte loads of the decoder row and of q, all
+        // independent, joined by an xor butterfly (fixed order)
         const T *U = static_cast<const T *>(p.U_K) + (int64_t)hk * p.rank * p.D;
-        for (int idx = tid; idx < GB * W; idx += blockDim.x) {
-            const int g = idx / W, col = idx - g * W;
+        const int chunks = p.D / EPL;
+        const int sub = tid & 7;
+        for (int idx0 = 0; idx0 < GB * W; idx0 += (kWavesPerBlock * kWave) / 8) {
+            const int idx = idx0 + (tid >> 3);
+            const bool real = idx < GB * W;
+            const int g = real ? idx / W : 0, col = real ? idx - g * W : 0;
             float a = 0.0f;
-            for (int d = 0; d < p.D; ++d)
-                a = fmaf(load_scalar<T>(U, (int64_t)col * p.D + d),
-                         load_scalar<T>(qp, (int64_t)g * p.D + d), a);
-            q_s[g][col] = p.scale * a;
+            for (int ch = sub; ch < chunks; ch += 8) {
+                float uf[EPL], qv[EPL];
+                Pack16<T>::widen(load16(U + (int64_t)col * p.D + ch * EPL), uf);
+                Pack16<T>::widen(load16(qp + (int64_t)g * p.D + ch * EPL), qv);
+#pragma unroll
+                for (int i = 0; i < EPL; ++i) a = fmaf(uf[i], qv[i], a);
+            }
+            a += __shfl_xor(a, 1, kWave);
+            a += __shfl_xor(a, 2, kWave);
+            a += __shfl_xor(a, 4, kWave);
+            if (real && sub == 0) q_s[g][col] = p.scale * a;
         }
     }
     __syncthreads();
@@ -579,11 +592,10 @@ __global__ __launch_bounds__(kWavesPerBlock *kWave, 3) void attn_partial_gqa128(
     }
 }
 
-constexpr int kCombineThreads = 1024;
-
-template <typename T>
-__global__ __launch_bounds__(kCombineThreads) void attn_combine(CombineParams p) {
-    combine_head<T, kCombineThreads>(p, blockIdx.x);
+template <typename T, int THREADS>
+__global__ __launch_bounds__(THREADS) void attn_combine(CombineParams p) {
+    __shared__ __attribute__((aligned(16))) unsigned char smem[combine_smem_bytes<THREADS>()];
+    combine_head<T, THREADS>(p, blockIdx.x, smem);
 }
 
 template <typename T, int W>
@@ -613,6 +625,7 @@ int launch_partial(int width, int gb, const AttnParams &p, int blocks, hipStream
 }  // namespace
 
 static int g_split_override = 0;   // tuning hook, see pikv_set_attn_split
+static hipEvent_t g_prof_start = nullptr, g_prof_stop = nullptr;   // see pikv_set_profile_events
 void g_split_override_set(int v) { g_split_override = v > 0 ? v : 0; }
 
 int make_attn_plan(const pikv_desc *d, int k, AttnPlan *plan) {
@@ -661,6 +674,17 @@ int make_attn_plan(const pikv_desc *d, int k, AttnPlan *plan) {
 using namespace pikv;
 
 extern "C" void pikv_set_attn_split(int32_t nsplit) { pikv::g_split_override_set(nsplit); }
+
+namespace pikv {
+void g_profile_events_set(void *start, void *stop) {
+    g_prof_start = static_cast<hipEvent_t>(start);
+    g_prof_stop = static_cast<hipEvent_t>(stop);
+}
+}  // namespace pikv
+
+extern "C" void pikv_set_profile_events(void *start, void *stop) {
+    pikv::g_profile_events_set(start, stop);
+}
 
 extern "C" size_t pikv_attn_workspace_bytes(const pikv_desc *desc, int32_t k) {
     AttnPlan plan;
@@ -726,6 +750,7 @@ int launch_attn_partial(const pikv_desc *desc, const void *q, const void *const 
     if (blocks64 > 0x7fffffff) return PIKV_ERR_UNSUPPORTED;
     hipStream_t st = as_stream(stream);
     int lrc;
+    if (g_prof_start) (void)hipEventRecord(g_prof_start, st);
     if (plan.gqa_mfma) {
         hipLaunchKernelGGL(attn_partial_gqa128, dim3((unsigned)blocks64), dim3(kWavesPerBlock * kWave),
                            0, st, p);
@@ -735,6 +760,7 @@ int launch_attn_partial(const pikv_desc *desc, const void *q, const void *const 
                   ? launch_partial<float>(W, plan.heads_per_block, p, (int)blocks64, st)
                   : launch_partial<bf16>(W, plan.heads_per_block, p, (int)blocks64, st);
     }
+    if (g_prof_stop) (void)hipEventRecord(g_prof_stop, st);
     if (lrc != PIKV_OK) return lrc;
 
     CombineParams c;
@@ -763,11 +789,16 @@ int launch_attn_partial(const pikv_desc *desc, const void *q, const void *const 
 
 namespace pikv {
 int pikv_sharded_attn_merge(const pikv_desc *desc, const CombineParams *c, void *stream) {
-    const dim3 cgrid(desc->B * desc->Hq), cblock(kCombineThreads);
-    if (desc->dtype == PIKV_F32)
-        hipLaunchKernelGGL(attn_combine<float>, cgrid, cblock, 0, as_stream(stream), *c);
-    else
-        hipLaunchKernelGGL(attn_combine<bf16>, cgrid, cblock, 0, as_stream(stream), *c);
+    const dim3 cgrid(desc->B * desc->Hq);
+    hipStream_t st = as_stream(stream);
+    const bool f32 = desc->dtype == PIKV_F32;
+    if (combine_threads(c->k * c->nsplit) == 256) {
+        if (f32) hipLaunchKernelGGL((attn_combine<float, 256>), cgrid, dim3(256), 0, st, *c);
+        else hipLaunchKernelGGL((attn_combine<bf16, 256>), cgrid, dim3(256), 0, st, *c);
+    } else {
+        if (f32) hipLaunchKernelGGL((attn_combine<float, 1024>), cgrid, dim3(1024), 0, st, *c);
+        else hipLaunchKernelGGL((attn_combine<bf16, 1024>), cgrid, dim3(1024), 0, st, *c);
+    }
     return launch_status();
 }
 }  // namespace pikv

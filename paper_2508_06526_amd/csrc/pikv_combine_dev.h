@@ -95,18 +95,30 @@ __device__ __forceinline__ void head_weights(int k, const float *Mj, const float
 //   phase 2: one thread forms the k gate-weighted shard weights in either combine mode.
 //   phase 3: weighted sum of the accumulators, slices reduced through LDS in fixed order,
 //            then (rank > 0) the value decoder y = ycode U_V[h'].
+// Bytes of LDS combine_head<., THREADS> carves from the buffer it is given.
+template <int THREADS>
+constexpr int combine_smem_bytes() {
+    return (2 * kMaxPartialsPerHead + 6 * 64 + 128) * 4 + THREADS * 16;
+}
+
+// Block size of the merge: one query head rarely has more than a few dozen partials; a small
+// block then has the same latency and leaves the rest of the GPU to other work.  The fused
+// and the stand-alone kernels use the same rule, which keeps their results bit-identical.
+inline int combine_threads(int np) { return np <= 32 ? 256 : 1024; }
+
 template <typename T, int THREADS>
-__device__ __forceinline__ void combine_head(const CombineParams &p, int bh) {
+__device__ __forceinline__ void combine_head(const CombineParams &p, int bh, unsigned char *smem) {
     const int b = bh / p.Hq, h = bh - b * p.Hq;
     const int hk = h / p.G;
     const int tid = threadIdx.x;
     const int np = p.k * p.nsplit;
 
-    __shared__ float wt[kMaxPartialsPerHead];   // max of every partial, later its weight
-    __shared__ float ls[kMaxPartialsPerHead];
-    __shared__ float Mj[64], Zj[64], shard_w[64], sh_shift[64], sh_coef[64], g_s[64];
-    __shared__ float4 red[THREADS];
-    __shared__ float ycode[128];
+    float4 *red = reinterpret_cast<float4 *>(smem);                  // [THREADS]
+    float *wt = reinterpret_cast<float *>(smem + THREADS * 16);     // max of every partial, later its weight
+    float *ls = wt + kMaxPartialsPerHead;
+    float *Mj = ls + kMaxPartialsPerHead, *Zj = Mj + 64, *shard_w = Zj + 64;
+    float *sh_shift = shard_w + 64, *sh_coef = sh_shift + 64, *g_s = sh_coef + 64;
+    float *ycode = g_s + 64;                                         // [128]
 
     const int cgroups = p.W / 4;                 // float4 column groups: 4..32
     const int slices = THREADS / cgroups;        // partial slices

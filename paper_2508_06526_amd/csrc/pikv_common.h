@@ -151,5 +151,6 @@ struct AttnPlan {
 };
 int make_attn_plan(const pikv_desc *d, int k, AttnPlan *plan);
 void g_split_override_set(int v);
+void g_profile_events_set(void *start, void *stop);
 
 }  // namespace pikv

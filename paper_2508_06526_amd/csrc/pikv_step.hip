@@ -139,8 +139,6 @@ __global__ __launch_bounds__(kRouteThreads) void step_pre(PreParams p) {
 // blocks, so it recomputes the per-head softmax statistics itself from the (max, sum) pairs of
 // the partials - a few KiB from L2 and the same arithmetic, hence the same bits - while its
 // score loads are already in flight.
-constexpr int kPostThreads = 1024;     // same block shape as the stand-alone merge: identical bits
-constexpr int kPostSlots = 256;        // slots per utility block; 4 head groups per slot
 constexpr int kPostMaxShards = 2048;   // Hq * k
 constexpr int kPostPrefetchHeads = 8;  // score loads each thread issues before the statistics
 
@@ -154,38 +152,46 @@ struct PostParams {
     float decay;
 };
 
-template <typename T>
-__global__ __launch_bounds__(kPostThreads) void step_post(PostParams p) {
+template <int THREADS>
+constexpr int post_smem_bytes() {
+    constexpr int util = (4 * kPostMaxShards + 64 + THREADS) * 4;
+    return util > combine_smem_bytes<THREADS>() ? util : combine_smem_bytes<THREADS>();
+}
+
+// Blocks [0, B*Hq) merge one query head each; the others update the utilities of THREADS/4
+// slots of the j-th selected shard of a sequence.  THREADS is the merge's block size
+// (combine_threads), so that the merge is bit-identical to the stand-alone kernel.
+template <typename T, int THREADS>
+__global__ __launch_bounds__(THREADS) void step_post(PostParams p) {
+    constexpr int kSlots = THREADS / 4;
+    __shared__ __attribute__((aligned(16))) unsigned char smem[post_smem_bytes<THREADS>()];
     const int ncomb = p.B * p.c.Hq;
     if ((int)blockIdx.x < ncomb) {
-        combine_head<T, kPostThreads>(p.c, blockIdx.x);
+        combine_head<T, THREADS>(p.c, blockIdx.x, smem);
         return;
     }
+    const int Hq = p.c.Hq, k = p.c.k, nsplit = p.c.nsplit;
+    const int np = k * nsplit;
     int bid = blockIdx.x - ncomb;
     const int tile = bid % p.tiles;
     bid /= p.tiles;
-    const int e = bid % p.E;
-    const int b = bid / p.E;
+    const int j = bid % k;
+    const int b = bid / k;
     const int tid = threadIdx.x;
-    const int Hq = p.c.Hq, k = p.c.k, nsplit = p.c.nsplit;
-    const int np = k * nsplit;
-
-    int j = -1;
-    for (int jj = 0; jj < k; ++jj)
-        if (p.topk[(int64_t)b * k + jj] == e) j = jj;
+    const int e = p.topk[(int64_t)b * k + j];
     const int n = p.n_valid[(int64_t)b * p.E + e];
-    const int i0 = tile * kPostSlots;
-    if (j < 0 || i0 >= n) return;
+    const int i0 = tile * kSlots;
+    if (i0 >= n) return;
 
-    __shared__ float Mj_s[kPostMaxShards], Zj_s[kPostMaxShards];
-    __shared__ float shift_s[kPostMaxShards], coef_s[kPostMaxShards];
-    __shared__ float g_s[64];
-    __shared__ float part_s[4][kPostSlots];
+    float *Mj_s = reinterpret_cast<float *>(smem), *Zj_s = Mj_s + kPostMaxShards;
+    float *shift_s = Zj_s + kPostMaxShards, *coef_s = shift_s + kPostMaxShards;
+    float *g_s = coef_s + kPostMaxShards;      // [64]
+    float *part_s = g_s + 64;                  // [4][kSlots]
 
     // thread = (slot, head group); the heads are cut into 4 consecutive groups, each summed in
     // ascending order, the groups joined as (g0 + g1) + (g2 + g3) - the order the stand-alone
     // utility kernel uses too
-    const int slot = tid & (kPostSlots - 1), hg = tid / kPostSlots;
+    const int slot = tid & (kSlots - 1), hg = tid / kSlots;
     const int gsize = (Hq + 3) / 4;
     const int h_lo = hg * gsize, h_hi = min(Hq, h_lo + gsize);
     const int i = i0 + slot;
@@ -202,7 +208,7 @@ __global__ __launch_bounds__(kPostThreads) void step_post(PostParams p) {
 
     // softmax statistics of every (head, selected shard): 8 lanes each, pairs read from L2
     const float *ml = p.c.part_ml + (int64_t)b * Hq * np * 2;
-    for (int t0 = 0; t0 < Hq * k; t0 += kPostThreads / 8) {
+    for (int t0 = 0; t0 < Hq * k; t0 += THREADS / 8) {
         const int t = t0 + tid / 8;
         const bool real = t < Hq * k;
         float M, Z;
@@ -215,7 +221,7 @@ __global__ __launch_bounds__(kPostThreads) void step_post(PostParams p) {
         }
     }
     __syncthreads();
-    for (int h = tid; h < Hq; h += kPostThreads) {
+    for (int h = tid; h < Hq; h += THREADS) {
         float M, norm;
         head_weights(k, Mj_s + h * k, Zj_s + h * k, p.c.gates ? g_s : nullptr, p.c.combine, nullptr,
                      shift_s + h * k, coef_s + h * k, &M, &norm);
@@ -232,10 +238,11 @@ __global__ __launch_bounds__(kPostThreads) void step_post(PostParams p) {
             a = fmaf(coef_s[h * k + j],
                      __expf(p.scores[(((int64_t)b * Hq + h) * k + j) * p.S + i] - shift_s[h * k + j]), a);
     }
-    part_s[hg][slot] = a;
+    part_s[hg * kSlots + slot] = a;
     __syncthreads();
     if (hg == 0 && live) {
-        const float total = (part_s[0][slot] + part_s[1][slot]) + (part_s[2][slot] + part_s[3][slot]);
+        const float total = (part_s[slot] + part_s[kSlots + slot]) +
+                            (part_s[2 * kSlots + slot] + part_s[3 * kSlots + slot]);
         *uptr = fmaf(p.decay, u_old, total);
     }
 }
@@ -324,13 +331,19 @@ extern "C" int pikv_decode_step(const pikv_desc *desc, const void *q, const void
     pp.B = desc->B;
     pp.E = desc->E;
     pp.S = desc->S;
-    pp.tiles = (desc->S + kPostSlots - 1) / kPostSlots;
+    const int threads = combine_threads(k * plan.nsplit);
+    pp.tiles = (desc->S + threads / 4 - 1) / (threads / 4);
     pp.decay = decay;
-    const int64_t blocks = (int64_t)desc->B * desc->Hq + (int64_t)desc->B * desc->E * pp.tiles;
+    const int64_t blocks = (int64_t)desc->B * desc->Hq + (int64_t)desc->B * k * pp.tiles;
     if (blocks > 0x7fffffff) return PIKV_ERR_UNSUPPORTED;
-    if (desc->dtype == PIKV_F32)
-        hipLaunchKernelGGL(step_post<float>, dim3((unsigned)blocks), dim3(kPostThreads), 0, st, pp);
-    else
-        hipLaunchKernelGGL(step_post<bf16>, dim3((unsigned)blocks), dim3(kPostThreads), 0, st, pp);
+    const dim3 grid((unsigned)blocks);
+    const bool f32 = desc->dtype == PIKV_F32;
+    if (threads == 256) {
+        if (f32) hipLaunchKernelGGL((step_post<float, 256>), grid, dim3(256), 0, st, pp);
+        else hipLaunchKernelGGL((step_post<bf16, 256>), grid, dim3(256), 0, st, pp);
+    } else {
+        if (f32) hipLaunchKernelGGL((step_post<float, 1024>), grid, dim3(1024), 0, st, pp);
+        else hipLaunchKernelGGL((step_post<bf16, 1024>), grid, dim3(1024), 0, st, pp);
+    }
     return launch_status();
 }
