@@ -27,6 +27,14 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
 
+# HBM bytes per launch of the dominant kernel as measured by rocprofv3 --pmc FETCH_SIZE /
+# WRITE_SIZE (two runs, scaled by what a plain 1 GiB device copy reads on the same counters);
+# the numbers and the commands are in the named files under profiles/.
+MEASURED_TRAFFIC = {
+    "c3_long_context": {"bytes_per_launch": int((128.21 + 5.59) * 2 ** 20),
+                        "source": "profiles/c3_long_context_hbm_traffic_pmc.txt"},
+}
+
 
 def parse_args():
     ap = argparse.ArgumentParser()
@@ -280,7 +288,9 @@ def main():
         "step_frac_of_hbm_peak": kv_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "roofline": {"bound": "hbm", "kernel": attn_kernel_name(geo),
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": MEASURED_TRAFFIC.get(args.config, {}).get("bytes_per_launch"),
+                     "traffic_source": MEASURED_TRAFFIC.get(args.config, {}).get("source"),
                      "bytes_per_launch": kv_bytes, "avg_ms": attn_avg_ms,
                      "median_ms": attn_ms[len(attn_ms) // 2],
                      "event_pair_raw_avg_ms": raw_avg_ms, "empty_event_pair_avg_ms": empty_avg_ms,
