@@ -1,13 +1,15 @@
 // PiKV routing (Section 3.2, Table 1 "TopK softmax" with the optional additive penalty):
-// one block per routed row computes the E logits of x W_r (+ bias), the softmax over all
-// experts and the k-hot mask, in a single launch.
+// one 1024-thread block per routed row computes the E logits of x W_r (+ bias), the softmax
+// over all experts and the k-hot mask, in a single launch.
 //
-// Threads are laid out as (row slice js, expert e): consecutive lanes read consecutive
-// elements of W_r, so a wave's load is one contiguous run of the row-major matrix.  The
-// slices are summed by a fixed-order LDS tree, which makes the logits (and therefore the
-// selection) independent of scheduling.  Selection is by rank counting: expert e's rank is
-// the number of experts that beat it under (logit descending, index ascending), so the
-// output order and the tie-break need no sorting network.
+//   route_vec_kernel : W_r rows that are a power-of-two number of 16-byte chunks (E = 8..64
+//                      in bf16, 4..64 in fp32): 16-byte loads, see pikv_route_dev.h.
+//   route_kernel     : any E <= 64: threads laid out as (row slice, expert) with scalar
+//                      element loads (consecutive lanes read consecutive elements of W_r),
+//                      slices summed by a fixed-order LDS tree.
+// Both make the logits (and therefore the selection) independent of scheduling.  Selection
+// is by rank counting: expert e's rank is the number of experts that beat it under (logit
+// descending, index ascending), so the output order and the tie-break need no sorting network.
 #include "pikv_common.h"
 #include "pikv_route_dev.h"
 

@@ -4,15 +4,17 @@
 //   step_pre   : per (sequence, selected position), a 1024-thread block routes the query
 //                (Section 3.2), then for its selected shard evicts the minimum-utility entry
 //                if the shard is full (Section 3.4) and inserts the new token's K/V rows in
-//                O(1) (Section 3.1).
-//                Everything that depends only on the selected expert id (entry count, table
-//                pointers, the shard's utilities) is fetched in one round trip; the new rows
-//                are fetched before the router result exists.
-//   attention  : the split flash-decode over the selected shards (pikv_sharded_attn).
-//   utility    : u <- decay * u + attention mass (pikv_update_utility).
+//                O(1) (Section 3.1).  Everything that depends only on the selected expert id
+//                (entry count, table pointers, the shard's utilities) is fetched in one round
+//                trip; the new rows are fetched before the router result exists.
+//   attention  : the split flash-decode pass over the selected shards (pikv_attn.hip).
+//   step_post  : merge of the split partials with the router gates and the utility update
+//                u <- decay * u + attention mass (Section 3.4, Table 3 H2O), in one launch.
 //
-// Separate launches for the first stage cost ~2.4 us of dispatch each on MI355X, more than
-// the work itself; fusing them removes two launches and two dependent memory round trips.
+// On MI355X even an empty kernel occupies the queue for ~1.5 us and each small kernel is a
+// chain of dependent memory round trips; six launches cost more in dispatch and latency than
+// in work next to a ~20 us attention pass.  The step is defined as exactly the sequence of
+// the separate C-ABI calls and shares every reduction order with them (bit-identical).
 #include "pikv_common.h"
 #include "pikv_combine_dev.h"
 #include "pikv_route_dev.h"
