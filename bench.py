@@ -57,13 +57,14 @@ def parse_args():
 
 # layer instances so that consecutive steps cannot be served from the 256 MB Infinity Cache
 DEFAULT_LAYERS = {"c1_tiny_f32": 1, "c2_bf16_decode": 2, "c3_long_context": 32, "c4_streaming": 2,
-                  "c5_compressed": 16}
+                  "c5_compressed": 16, "c3_long_context_tq4": 32}
 RECIPE = {  # how each configuration's inputs are drawn (workloads.make_device_layers arguments)
     "c1_tiny_f32": dict(w_sigma=1.0),
     "c2_bf16_decode": dict(kv="lognormal_token"),
     "c3_long_context": dict(zipf_s=1.1),
     "c4_streaming": dict(utility0="exp"),
     "c5_compressed": dict(zipf_s=1.1),
+    "c3_long_context_tq4": dict(zipf_s=1.1, w_sigma=0.01),
 }
 DECAY = {"c4_streaming": 0.9}
 
@@ -271,7 +272,7 @@ def main():
         attn_ms = [x - empty_avg_ms for x in raw_ms]
 
     ms_per_step = elapsed * 1e3 / K
-    qps = geo.B * K / elapsed
+    qps = geo.B * geo.tq * K / elapsed
     n_mean = float(torch.stack([L.t["n_valid"].float().mean() for L in layers]).mean().item())
     kv_bytes = geo.kv_bytes_per_step(n_mean)
     achieved = kv_bytes / (attn_avg_ms * 1e-3) / 1e9
@@ -281,7 +282,8 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if geo.dtype == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": args.config, "B": geo.B, "Hq": geo.Hq, "Hkv": geo.Hkv, "D": geo.D,
-                   "E": geo.E, "S": geo.S, "k": geo.k, "rank": geo.rank, "layers_cycled": n_layers,
+                   "E": geo.E, "S": geo.S, "k": geo.k, "rank": geo.rank, "queries_per_sequence": geo.tq,
+                   "layers_cycled": n_layers,
                    "launch": args.mode, "api": args.api,
                    "step": "route+evict1+append+attend+utility"},
         "step_effective_GBps": kv_bytes / (ms_per_step * 1e-3) / 1e9,
@@ -300,7 +302,7 @@ def main():
     if not args.no_cpu and args.cpu_steps != 0:
         n_cpu = args.cpu_steps if args.cpu_steps > 0 else min(n_layers, 8)
         per_step, n_done = cpu_baseline(torch, wl, layers, n_cpu)
-        out["cpu_baseline"] = {"value": geo.B / per_step, "unit": "queries/s",
+        out["cpu_baseline"] = {"value": geo.B * geo.tq / per_step, "unit": "queries/s",
                                "cores": int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1)),
                                "kind": "oracle",
                                "sample": "%d steps (layer instances) of %s: route+attend+utility, "

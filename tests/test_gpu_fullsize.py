@@ -28,6 +28,8 @@ FULL = {
     "c3_long_context": ([0], 1.0),
     "c4_streaming": ([3, 31], 0.9),
     "c5_compressed": ([1, 14], 1.0),
+    # "next" row: 4 draft queries per sequence share the selected shards (group of 16 query rows)
+    "c3_long_context_tq4": ([0], 1.0),
 }
 
 

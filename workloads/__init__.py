@@ -55,6 +55,7 @@ class Geometry:
     dtype: str = "bf16"           # 'f32' | 'bf16'
     per_head_routing: bool = False  # True: one routing decision per (sequence, head)
     name: str = ""
+    tq: int = 1                   # draft queries per sequence folded into Hq (multi-query tile)
 
     @property
     def G(self) -> int:
@@ -95,6 +96,17 @@ CONFIGS = {
     "c5_compressed": Geometry(B=16, Hq=32, Hkv=32, D=128, E=16, S=2048, k=2, rank=32,
                               name="c5_compressed"),
 }
+
+# Widening beyond the five specified workloads ("next" rows of the scope table).
+# Multi-query tile: Tq draft tokens of a sequence attend to the same selected shards in one pass
+# (speculative decoding).  Laid out as [B, Hkv, Tq*G, D] the Tq*G query rows of a kv head are
+# simply a larger grouped-query group, so the long-context workload with Tq = 4 is a geometry
+# with Hq = 4*32 query rows over the same 8 kv heads (group 16 = a full MFMA tile).
+EXTRA_CONFIGS = {
+    "c3_long_context_tq4": Geometry(B=1, Hq=128, Hkv=8, D=128, E=16, S=8192, k=4,
+                                    name="c3_long_context_tq4", tq=4),
+}
+CONFIGS.update(EXTRA_CONFIGS)
 
 
 def zipf_bias(E: int, s: float, rng: np.random.Generator) -> np.ndarray:
