@@ -384,3 +384,57 @@ int pikv_oracle_append(int B, int E, int S, int Hkv, int width, int dtype, int64
     }
     return 0;
 }
+
+/* --------------------------------------------------------- router penalties */
+/* Section 3.2, Table 1, column "Penalty Term": the additive per-expert term of the
+ * load-balanced router (row LB: -alpha * (mu_e - mean mu), mu_e = how often expert e has been
+ * selected so far) and of the cache-aware router (row P: -lambda * log(1 + miss_e)).
+ * `load` first absorbs this step's selections (rows x k expert ids), then the penalty is
+ * formed from the updated counters.  mode 0 = LB, 1 = P (needs `miss`).                   */
+int pikv_oracle_router_penalty(int mode, const int32_t *topk_idx, int rows, int k, int E,
+                               int32_t *load, const int32_t *miss, double coef, float *bias) {
+    if (E < 1 || rows < 0 || k < 0 || (mode != 0 && mode != 1) || (mode == 1 && !miss)) return -1;
+    for (int i = 0; i < rows * k; ++i) {
+        if (topk_idx[i] < 0 || topk_idx[i] >= E) return -1;
+        load[topk_idx[i]] += 1;
+    }
+    if (mode == 0) {
+        double mean = 0.0;
+        for (int e = 0; e < E; ++e) mean += (double)load[e];
+        mean /= (double)E;
+        for (int e = 0; e < E; ++e) bias[e] = (float)(-coef * ((double)load[e] - mean));
+    } else {
+        for (int e = 0; e < E; ++e) bias[e] = (float)(-coef * log(1.0 + (double)miss[e]));
+    }
+    return 0;
+}
+
+/* ------------------------------------------------------- compress on insert */
+/* Algorithm 1, (K^,V^) <- C_cmp(K_t,V_t) with the rank-r linear compressor of Section 3.3 /
+ * Table 2 (LoRA rows: the width-d' code is a linear map of the width-d vector):
+ * code[b][h'][c] = sum_d x[b][h'][d] * W_enc[h'][c][d], rounded once to the storage dtype
+ * (bfloat16: round to nearest even).                                                      */
+static uint16_t double_to_bf16(double v) {
+    float f = (float)v;                 /* double -> float, then float -> bf16, both RNE   */
+    uint32_t u;
+    memcpy(&u, &f, sizeof u);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+int pikv_oracle_compress(int B, int Hkv, int D, int rank, int dtype, const void *x,
+                         const void *W_enc, void *codes) {
+    if (B < 0 || Hkv < 1 || D < 1 || rank < 1) return -1;
+    for (int b = 0; b < B; ++b)
+        for (int h = 0; h < Hkv; ++h)
+            for (int c = 0; c < rank; ++c) {
+                double acc = 0.0;
+                for (int d = 0; d < D; ++d)
+                    acc += load_elem(x, ((int64_t)b * Hkv + h) * D + d, dtype) *
+                           load_elem(W_enc, ((int64_t)h * rank + c) * D + d, dtype);
+                const int64_t o = ((int64_t)b * Hkv + h) * rank + c;
+                if (dtype == ORACLE_F32) ((float *)codes)[o] = (float)acc;
+                else ((uint16_t *)codes)[o] = double_to_bf16(acc);
+            }
+    return 0;
+}

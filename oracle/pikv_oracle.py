@@ -40,7 +40,7 @@ def lib():
         # PIKV_ORACLE_LIB lets the mutation test load a deliberately broken build
         _lib = C.CDLL(os.environ.get("PIKV_ORACLE_LIB") or build())
         for name in ("pikv_oracle_route", "pikv_oracle_attend", "pikv_oracle_evict",
-                     "pikv_oracle_append"):
+                     "pikv_oracle_append", "pikv_oracle_router_penalty", "pikv_oracle_compress"):
             getattr(_lib, name).restype = C.c_int
     return _lib
 
@@ -196,3 +196,35 @@ def append(K_new, V_new, topk_idx, K_shards, V_shards, utility, n_valid, *, dtyp
                                   _ptr(_chk(n_valid, np.int32, "n_valid")))
     if rc:
         raise ValueError("pikv_oracle_append failed: %d" % rc)
+
+
+LB, CACHE_AWARE = 0, 1
+
+
+def router_penalty(mode, topk_idx, load, coef, miss=None):
+    """In place on load [E] int32 (absorbs topk_idx [rows,k]).  Returns bias f32 [E]."""
+    topk_idx = _chk(topk_idx, np.int32, "topk_idx")
+    load = _chk(load, np.int32, "load")
+    miss = _chk(miss, np.int32, "miss")
+    rows, k = topk_idx.shape
+    E = load.shape[0]
+    bias = np.zeros(E, np.float32)
+    rc = lib().pikv_oracle_router_penalty(mode, _ptr(topk_idx), rows, k, E, _ptr(load), _ptr(miss),
+                                          C.c_double(coef), _ptr(bias))
+    if rc:
+        raise ValueError("pikv_oracle_router_penalty failed: %d" % rc)
+    return bias
+
+
+def compress(x, W_enc, dtype="f32"):
+    """x [B,Hkv,D], W_enc [Hkv,rank,D] (storage dtype) -> codes [B,Hkv,rank] (storage dtype)."""
+    nd = _np_dtype(dtype)
+    x = _chk(x, nd, "x")
+    W_enc = _chk(W_enc, nd, "W_enc")
+    B, Hkv, D = x.shape
+    rank = W_enc.shape[1]
+    codes = np.zeros((B, Hkv, rank), nd)
+    rc = lib().pikv_oracle_compress(B, Hkv, D, rank, _dt(dtype), _ptr(x), _ptr(W_enc), _ptr(codes))
+    if rc:
+        raise ValueError("pikv_oracle_compress failed: %d" % rc)
+    return codes

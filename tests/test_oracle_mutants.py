@@ -38,6 +38,13 @@ MUTANTS = {
     "evict_keeps_lowest": ("if (x->u > y->u) return -1;\n    if (x->u < y->u) return 1;\n    return (x->slot",
                            "if (x->u > y->u) return 1;\n    if (x->u < y->u) return -1;\n    return (x->slot"),
     "append_keeps_old_utility": ("utility[be * S + slot] = 0.0f;", ""),
+    "load_penalty_sign_flipped": ("bias[e] = (float)(-coef * ((double)load[e] - mean));",
+                                  "bias[e] = (float)(coef * ((double)load[e] - mean));"),
+    "load_penalty_not_centred": ("mean /= (double)E;", "mean = 0.0;"),
+    "miss_penalty_without_log": ("bias[e] = (float)(-coef * log(1.0 + (double)miss[e]));",
+                                 "bias[e] = (float)(-coef * (double)miss[e]);"),
+    "encoder_transposed": ("load_elem(W_enc, ((int64_t)h * rank + c) * D + d, dtype)",
+                           "load_elem(W_enc, (((int64_t)h * D + d) * rank + c) % ((int64_t)Hkv * rank * D), dtype)"),
     "empty_shard_counted_in_local_norm": ("if (Z[j] > 0.0) norm += gsel ? (double)gsel[j] : 1.0;",
                                           "norm += gsel ? (double)gsel[j] : 1.0;"),
 }

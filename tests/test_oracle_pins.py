@@ -606,3 +606,73 @@ def test_streaming_step_reuses_the_evicted_slot_and_conserves_counts():
                 assert case.utility[b, e, victim] == 0
             else:
                 assert changed == []
+
+
+# ------------------------------------------------------------ router penalties
+def test_load_balance_penalty_closed_forms():
+    """Table 1 row LB: -alpha (mu_e - mean): sums to zero, vanishes for uniform load."""
+    load = np.zeros(4, np.int32)
+    idx = np.array([[0, 1], [0, 2], [0, 3]], np.int32)
+    bias = orc.router_penalty(orc.LB, idx, load, 0.5)
+    assert list(load) == [3, 1, 1, 1]
+    np.testing.assert_allclose(bias, -0.5 * (np.array([3, 1, 1, 1]) - 1.5), rtol=1e-7)
+    assert abs(bias.sum()) < 1e-6
+    # counters accumulate over calls; a second, balancing call makes the penalty vanish
+    bias = orc.router_penalty(orc.LB, np.array([[1, 2], [3, 1], [2, 3]], np.int32), load, 0.5)
+    assert list(load) == [3, 3, 3, 3] and (bias == 0).all()
+    # the over-used expert is pushed down, the others up, by amounts proportional to alpha
+    b1 = orc.router_penalty(orc.LB, idx, np.zeros(4, np.int32), 1.0)
+    b2 = orc.router_penalty(orc.LB, idx, np.zeros(4, np.int32), 2.0)
+    assert b1[0] < 0 < b1[1] and np.allclose(b2, 2 * b1)
+
+
+def test_cache_aware_penalty_is_minus_lambda_log1p_miss():
+    miss = np.array([0, 1, 9, 99], np.int32)
+    load = np.zeros(4, np.int32)
+    bias = orc.router_penalty(orc.CACHE_AWARE, np.array([[2, 3]], np.int32), load, 0.7, miss=miss)
+    np.testing.assert_allclose(bias, -0.7 * np.log1p(miss.astype(np.float64)), rtol=1e-6)
+    assert bias[0] == 0 and list(load) == [0, 0, 1, 1]
+
+
+def test_penalty_feeds_the_router_as_bias():
+    """Closing the loop: a heavily loaded expert drops out of the top-k."""
+    rng = np.random.default_rng(0)
+    x = rng.standard_normal((1, 8)).astype(np.float32)
+    W = rng.standard_normal((8, 4)).astype(np.float32)
+    idx0, _, _ = orc.route(x, W, 1)
+    load = np.zeros(4, np.int32)
+    load[idx0[0, 0]] = 1000
+    bias = orc.router_penalty(orc.LB, np.zeros((0, 1), np.int32), load, 1.0)
+    idx1, _, _ = orc.route(x, W, 1, bias=bias)
+    assert idx1[0, 0] != idx0[0, 0]
+
+
+# ------------------------------------------------------------ compress on insert
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_compress_is_a_matmul_with_the_encoder(dtype):
+    rng = np.random.default_rng(1)
+    B, Hkv, D, r = 3, 2, 16, 4
+    x = wl.encode(rng.standard_normal((B, Hkv, D)), dtype)
+    W = wl.encode(rng.standard_normal((Hkv, r, D)) / 4, dtype)
+    codes = orc.compress(x, W, dtype=dtype)
+    ref = np.einsum("bhd,hcd->bhc", wl.decode(x, dtype).astype(np.float64), wl.decode(W, dtype).astype(np.float64))
+    if dtype == "f32":
+        np.testing.assert_allclose(codes, ref, rtol=1e-6)
+    else:
+        np.testing.assert_array_equal(codes, wl.f32_to_bf16_bits(ref.astype(np.float32)))
+
+
+def test_compress_then_decode_with_orthonormal_rows_recovers_the_subspace():
+    """Encoder = decoder^T with orthonormal rows: decode(encode(x)) is the projection of x, and a
+    vector already in the row space comes back exactly (reconstruction error 0, Section 3.3)."""
+    rng = np.random.default_rng(2)
+    D, r = 16, 4
+    Q, _ = np.linalg.qr(rng.standard_normal((D, r)))
+    U = np.ascontiguousarray(Q.T[None].astype(np.float32))            # [1, r, D]
+    inside = (rng.standard_normal((1, 1, r)) @ U[0]).astype(np.float32)   # in the row space
+    codes = orc.compress(inside, U)
+    np.testing.assert_allclose(codes[0, 0] @ U[0], inside[0, 0], rtol=1e-5, atol=1e-6)
+    crop = np.zeros((1, r, D), np.float32)
+    crop[0, np.arange(r), np.arange(r)] = 1                          # Table 2 "crop to r"
+    x = rng.standard_normal((2, 1, D)).astype(np.float32)
+    np.testing.assert_array_equal(orc.compress(x, crop), x[:, :, :r])
