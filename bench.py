@@ -49,6 +49,12 @@ def parse_args():
     ap.add_argument("--cpu-steps", type=int, default=-1, help="oracle steps timed (0: skip, -1: auto)")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--balance", action="store_true",
+                    help="widened row: keep the load-balance router penalty on the device and feed "
+                         "it back as the routing bias (one extra small launch per step)")
+    ap.add_argument("--compress", action="store_true",
+                    help="widened row (rank > 0 workloads): compress the new token's full-width K/V "
+                         "to codes inside the step (one extra small launch)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run a plain 1 GiB device copy 8 times and exit (reference for the "
                          "rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")
@@ -84,6 +90,16 @@ class Layer:
         self.fused = shared.get("fused", False) and not g.per_head_routing
 
     def step(self):
+        pk, g, t, s = self.pk, self.geo, self.t, self.sh
+        if s.get("compress"):
+            pk.pikv_compress(self.desc, s["K_full"], s["Wenc_K"], s["K_new"], s["V_full"], s["Wenc_V"],
+                             s["V_new"])
+        self._step()
+        if s.get("balance"):
+            pk.pikv_router_penalty(pk.PENALTY_LOAD_BALANCE, s["topk"], g.route_rows, g.k, g.E,
+                                   t["load"], None, 0.01, t["bias"])
+
+    def _step(self):
         pk, g, t, s = self.pk, self.geo, self.t, self.sh
         if self.fused:
             pk.pikv_decode_step(self.desc, t["q"], t["W_r"], t["bias"], s["K_new"], s["V_new"],
@@ -210,6 +226,20 @@ def main():
     raw = wl.make_device_layers(geo, n_layers, args.seed, dev, **RECIPE[args.config])
     shared = make_shared(pk, torch, geo, dev)
     shared["fused"] = args.api == "fused"
+    if args.balance:
+        shared["balance"] = True
+        for t in raw:
+            t["load"] = torch.zeros(geo.E, device=dev, dtype=torch.int32)
+            t["bias"] = torch.zeros(geo.E, device=dev)
+    if args.compress and geo.rank:
+        tdt = torch.bfloat16 if geo.dtype == "bf16" else torch.float32
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(777)
+        rn = lambda *sh: torch.randn(*sh, device=dev, generator=gen)
+        shared.update(compress=True,
+                      K_full=rn(geo.B, geo.Hkv, geo.D).to(tdt), V_full=rn(geo.B, geo.Hkv, geo.D).to(tdt),
+                      Wenc_K=(rn(geo.Hkv, geo.rank, geo.D) / geo.D ** 0.5).to(tdt),
+                      Wenc_V=(rn(geo.Hkv, geo.rank, geo.D) / geo.D ** 0.5).to(tdt))
     layers = [Layer(pk, torch, geo, t, shared) for t in raw]
     torch.cuda.synchronize()
 
@@ -284,7 +314,8 @@ def main():
         "config": {"workload": args.config, "B": geo.B, "Hq": geo.Hq, "Hkv": geo.Hkv, "D": geo.D,
                    "E": geo.E, "S": geo.S, "k": geo.k, "rank": geo.rank, "queries_per_sequence": geo.tq,
                    "layers_cycled": n_layers,
-                   "launch": args.mode, "api": args.api,
+                   "launch": args.mode, "api": args.api, "balance": bool(args.balance),
+                   "compress_on_insert": bool(args.compress and geo.rank),
                    "step": "route+evict1+append+attend+utility"},
         "step_effective_GBps": kv_bytes / (ms_per_step * 1e-3) / 1e9,
         "step_frac_of_hbm_peak": kv_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,

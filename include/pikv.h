@@ -188,6 +188,31 @@ int pikv_decode_step(const pikv_desc *desc, const void *q, const void *W_r, cons
                      float *y, float *row_max, float *row_norm, float *scores, float *slot_coef,
                      void *workspace, size_t workspace_bytes, void *stream);
 
+/* Section 3.2, Table 1, column "Penalty Term": the additive per-expert term of the penalised
+ * routers, kept on the device so that routing feeds back into itself without the host:
+ *   PIKV_PENALTY_LOAD_BALANCE (row LB):  bias_e = -coef * (load_e - mean_e' load_e')
+ *   PIKV_PENALTY_CACHE_AWARE  (row P):   bias_e = -coef * log(1 + miss_e)
+ * `load` [E] int32 is a running count of how often each expert was selected; the call first
+ * adds this step's selections topk_idx [rows,k] to it (rows*k may be 0), then writes
+ * bias [E] float32, to be passed as `bias` to the next pikv_route / pikv_decode_step.
+ * `miss` [E] int32 (cache-aware mode only) is maintained by the caller.
+ * Errors: INVALID for unknown mode, null load/bias, E not in 1..64, null miss in cache-aware
+ * mode, NaN coef.                                                                          */
+typedef enum { PIKV_PENALTY_LOAD_BALANCE = 0, PIKV_PENALTY_CACHE_AWARE = 1 } pikv_penalty;
+int pikv_router_penalty(int32_t mode, const int32_t *topk_idx, int32_t rows, int32_t k, int32_t E,
+                        int32_t *load, const int32_t *miss, float coef, float *bias, void *stream);
+
+/* Algorithm 1, (K^, V^) <- C_cmp(K_t, V_t) for the rank-r linear compressor (Section 3.3,
+ * Table 2 LoRA rows): codes[b][h'][c] = sum_d x[b][h'][d] * W_enc[h'][c][d], fp32 accumulate,
+ * rounded once to the storage dtype (bf16: nearest even), for the new token's keys and - in the
+ * same launch, when the three V arguments are given - values.  The codes are what pikv_append /
+ * pikv_decode_step insert when desc->rank > 0.
+ *   K_full, V_full [B,Hkv,D] dtype;  Wenc_K, Wenc_V [Hkv,rank,D] dtype;
+ *   K_codes, V_codes [B,Hkv,rank] dtype out.  V_full = Wenc_V = V_codes = NULL: keys only.
+ * Errors: descriptor errors, INVALID for rank == 0, null K arguments, partly given V arguments. */
+int pikv_compress(const pikv_desc *desc, const void *K_full, const void *Wenc_K, void *K_codes,
+                  const void *V_full, const void *Wenc_V, void *V_codes, void *stream);
+
 /* Tuning hook: force the number of row-range splits per (head group, selected shard) used
  * by pikv_sharded_attn and pikv_attn_workspace_bytes (process-wide; 0 restores the built-in
  * choice of one round of resident blocks).  Change it only between calls, and size the

@@ -14,10 +14,11 @@ _LIB_PATH = os.path.join(_HERE, "libpikv.so")
 
 F32, BF16 = 0, 1
 COMBINE_LSE, COMBINE_LOCAL = 0, 1
+PENALTY_LOAD_BALANCE, PENALTY_CACHE_AWARE = 0, 1
 
 EXPORTS = ("pikv_route", "pikv_attn_workspace_bytes", "pikv_sharded_attn", "pikv_update_utility",
            "pikv_evict", "pikv_append", "pikv_strerror", "pikv_version", "pikv_set_attn_split", "pikv_decode_step",
-           "pikv_set_profile_events")
+           "pikv_set_profile_events", "pikv_router_penalty", "pikv_compress")
 
 
 class PikvError(RuntimeError):
@@ -73,6 +74,10 @@ def load_library():
     lib.pikv_decode_step.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, f32, f32,
                                      vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
     lib.pikv_decode_step.restype = C.c_int
+    lib.pikv_router_penalty.argtypes = [i32, vp, i32, i32, i32, vp, vp, f32, vp, vp]
+    lib.pikv_router_penalty.restype = C.c_int
+    lib.pikv_compress.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp]
+    lib.pikv_compress.restype = C.c_int
     lib.pikv_set_profile_events.argtypes = [vp, vp]
     lib.pikv_set_profile_events.restype = None
     lib.pikv_set_attn_split.argtypes = [i32]
@@ -215,3 +220,15 @@ def pikv_decode_step(desc, q, W_r, bias, K_new, V_new, K_shards, V_shards, U_K, 
         _p(topk_idx), _p(gates), _p(evicted_idx), _p(evicted_cnt), _p(y), _p(row_max), _p(row_norm),
         _p(scores), _p(slot_coef), _p(workspace), ws_bytes, _stream(stream))
     _check(st, "pikv_decode_step")
+
+
+def pikv_router_penalty(mode, topk_idx, rows, k, E, load, miss, coef, bias, stream=None):
+    st = load_library().pikv_router_penalty(mode, _p(topk_idx), rows, k, E, _p(load), _p(miss),
+                                            float(coef), _p(bias), _stream(stream))
+    _check(st, "pikv_router_penalty")
+
+
+def pikv_compress(desc, K_full, Wenc_K, K_codes, V_full=None, Wenc_V=None, V_codes=None, stream=None):
+    st = load_library().pikv_compress(C.byref(desc), _p(K_full), _p(Wenc_K), _p(K_codes), _p(V_full),
+                                      _p(Wenc_V), _p(V_codes), _stream(stream))
+    _check(st, "pikv_compress")

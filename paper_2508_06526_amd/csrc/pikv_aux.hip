@@ -1,0 +1,133 @@
+// Two small stages around the hot path:
+//
+//   router_penalty : the additive per-expert term of PiKV's penalised routers (Section 3.2,
+//                    Table 1, column "Penalty Term"): load balancing, -alpha (mu_e - mean mu)
+//                    with mu_e = how often expert e has been selected, and cache-aware routing,
+//                    -lambda log(1 + miss_e).  One wavefront: lane e owns expert e, absorbs this
+//                    step's selections into the load counter (integer, order-free) and writes
+//                    the bias that the next pikv_route / pikv_decode_step call adds to the logits.
+//   compress_rows  : Algorithm 1, (K^, V^) <- C_cmp(K_t, V_t) for the rank-r linear compressor of
+//                    Section 3.3 (Table 2, LoRA rows): code = W_enc x, rounded once to the storage
+//                    type.  One block per (sequence, kv head, K or V); 8 lanes per code element read the
+//                    encoder row and the vector with 16-byte loads and join by an xor butterfly.
+#include "pikv_common.h"
+
+#include <math.h>
+
+namespace pikv {
+namespace {
+
+__global__ __launch_bounds__(kWave) void router_penalty(int mode, const int32_t *topk, int n_sel, int E,
+                                                        int32_t *load, const int32_t *miss, float coef,
+                                                        float *bias) {
+    const int e = threadIdx.x;
+    int cnt = 0;
+    for (int i = 0; i < n_sel; ++i) cnt += (topk[i] == e);
+    int mine = 0;
+    if (e < E) {
+        mine = load[e] + cnt;
+        load[e] = mine;
+    }
+    if (mode == 0) {
+        // exact integer total, then one division: the mean does not depend on lane order
+        int total = mine;
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) total += __shfl_xor(total, off, kWave);
+        const float mean = (float)total / (float)E;
+        if (e < E) bias[e] = -coef * ((float)mine - mean);
+    } else {
+        if (e < E) bias[e] = -coef * log1pf((float)miss[e]);
+    }
+}
+
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+
+template <typename T>
+__device__ __forceinline__ void store_elem(T *p, int64_t i, float v);
+template <>
+__device__ __forceinline__ void store_elem<float>(float *p, int64_t i, float v) {
+    p[i] = v;
+}
+template <>
+__device__ __forceinline__ void store_elem<bf16>(bf16 *p, int64_t i, float v) {
+    const f32x2_t pair = {v, 0.0f};
+    const bf16x2_t r = __builtin_convertvector(pair, bf16x2_t);     // round to nearest even
+    p[i].bits = (uint16_t)(__builtin_bit_cast(uint32_t, r) & 0xffffu);
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void compress_rows(const T *xK, const T *WK, T *codesK, const T *xV,
+                                                     const T *WV, T *codesV, int Hkv, int D, int rank) {
+    constexpr int EPL = Pack16<T>::N;
+    const T *x = blockIdx.y == 0 ? xK : xV;    // grid.y: 0 = keys, 1 = values
+    const T *W_enc = blockIdx.y == 0 ? WK : WV;
+    T *codes = blockIdx.y == 0 ? codesK : codesV;
+    const int bh = blockIdx.x;                 // b * Hkv + h
+    const int h = bh % Hkv;
+    const int tid = threadIdx.x, sub = tid & 7;
+    const int chunks = D / EPL;
+    const T *xv = x + (int64_t)bh * D;
+    const T *W = W_enc + (int64_t)h * rank * D;
+    for (int c0 = 0; c0 < rank; c0 += 256 / 8) {
+        const int c = c0 + (tid >> 3);
+        const bool real = c < rank;
+        float a = 0.0f;
+        if (real) {
+            for (int ch = sub; ch < chunks; ch += 8) {
+                float wf[EPL], xf[EPL];
+                Pack16<T>::widen(load16(W + (int64_t)c * D + ch * EPL), wf);
+                Pack16<T>::widen(load16(xv + ch * EPL), xf);
+#pragma unroll
+                for (int i = 0; i < EPL; ++i) a = fmaf(wf[i], xf[i], a);
+            }
+        }
+        a += __shfl_xor(a, 1, kWave);
+        a += __shfl_xor(a, 2, kWave);
+        a += __shfl_xor(a, 4, kWave);
+        if (real && sub == 0) store_elem<T>(codes, (int64_t)bh * rank + c, a);
+    }
+}
+
+}  // namespace
+}  // namespace pikv
+
+using namespace pikv;
+
+extern "C" int pikv_router_penalty(int32_t mode, const int32_t *topk_idx, int32_t rows, int32_t k,
+                                   int32_t E, int32_t *load, const int32_t *miss, float coef,
+                                   float *bias, void *stream) {
+    if (mode != PIKV_PENALTY_LOAD_BALANCE && mode != PIKV_PENALTY_CACHE_AWARE) return PIKV_ERR_INVALID;
+    if (!load || !bias || E < 1 || E > 64 || rows < 0 || k < 0) return PIKV_ERR_INVALID;
+    if ((int64_t)rows * k > 0 && !topk_idx) return PIKV_ERR_INVALID;
+    if (mode == PIKV_PENALTY_CACHE_AWARE && !miss) return PIKV_ERR_INVALID;
+    if (!(coef == coef)) return PIKV_ERR_INVALID;
+    if ((int64_t)rows * k > 0x7fffffff) return PIKV_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL(router_penalty, dim3(1), dim3(kWave), 0, as_stream(stream), mode, topk_idx,
+                       rows * k, E, load, miss, coef, bias);
+    return launch_status();
+}
+
+extern "C" int pikv_compress(const pikv_desc *desc, const void *K_full, const void *Wenc_K,
+                             void *K_codes, const void *V_full, const void *Wenc_V, void *V_codes,
+                             void *stream) {
+    const int rc = check_desc(desc);
+    if (rc != PIKV_OK) return rc;
+    if (desc->rank == 0 || !K_full || !Wenc_K || !K_codes) return PIKV_ERR_INVALID;
+    const bool both = V_full || Wenc_V || V_codes;
+    if (both && (!V_full || !Wenc_V || !V_codes)) return PIKV_ERR_INVALID;
+    if (desc->B == 0) return PIKV_OK;
+    const dim3 grid(desc->B * desc->Hkv, both ? 2 : 1), block(256);
+    hipStream_t st = as_stream(stream);
+    if (desc->dtype == PIKV_F32)
+        hipLaunchKernelGGL(compress_rows<float>, grid, block, 0, st, static_cast<const float *>(K_full),
+                           static_cast<const float *>(Wenc_K), static_cast<float *>(K_codes),
+                           static_cast<const float *>(V_full), static_cast<const float *>(Wenc_V),
+                           static_cast<float *>(V_codes), desc->Hkv, desc->D, desc->rank);
+    else
+        hipLaunchKernelGGL(compress_rows<bf16>, grid, block, 0, st, static_cast<const bf16 *>(K_full),
+                           static_cast<const bf16 *>(Wenc_K), static_cast<bf16 *>(K_codes),
+                           static_cast<const bf16 *>(V_full), static_cast<const bf16 *>(Wenc_V),
+                           static_cast<bf16 *>(V_codes), desc->Hkv, desc->D, desc->rank);
+    return launch_status();
+}

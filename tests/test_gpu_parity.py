@@ -463,3 +463,113 @@ def test_fused_decode_step_without_insert_and_unsupported_shapes():
                             d2.n_valid, d2.utility, g2.k, pk.COMBINE_LSE, 0.0, 1.0, d2.topk, d2.gates,
                             None, None, d2.y, d2.row_max, d2.row_norm, d2.scores, d2.slot_coef, d2.workspace)
     assert ei.value.status == -2
+
+
+# ------------------------------------------------ widened rows: router penalties, compress-on-insert
+@pytest.mark.parametrize("mode", [0, 1], ids=["load_balance", "cache_aware"])
+def test_router_penalty_matches_oracle_and_closes_the_loop(mode):
+    """Table 1 penalty terms kept on the device: counters exact, bias to fp32 rounding, and the
+    penalised routing decisions of a 10-step chain equal the oracle's."""
+    from gpu_harness import dev_storage
+    g = wl.Geometry(B=6, Hq=4, Hkv=4, D=64, E=8, S=16, k=2, dtype="bf16")
+    case = wl.make_host_case(g, seed=51)
+    dc = DeviceCase(case)
+    rng = np.random.default_rng(3)
+    miss_h = rng.integers(0, 50, size=g.E).astype(np.int32)
+    load_h = np.zeros(g.E, np.int32)
+    load_d = torch.zeros(g.E, device=DEV, dtype=torch.int32)
+    miss_d = torch.from_numpy(miss_h).to(DEV)
+    bias_d = torch.zeros(g.E, device=DEV)
+    dc.bias = bias_d
+    coef = 0.05 if mode == 0 else 0.3
+    bias_h = np.zeros(g.E, np.float32)
+    for step in range(10):
+        probe = case.clone()
+        probe.q = wl.draw_queries(g, 300 + step)
+        probe.bias = bias_h
+        ensure_route_margin(probe, g.k)
+        dc.q.copy_(dev_storage(probe.q, g.dtype))
+        dc.route()
+        x = np.ascontiguousarray(probe.q.reshape(g.route_rows, g.d_r))
+        idx, _, _ = orc.route(x, case.W_r, g.k, bias=bias_h, dtype=g.dtype)
+        np.testing.assert_array_equal(t2n(dc.topk), idx)
+        pk.pikv_router_penalty(mode, dc.topk, g.route_rows, g.k, g.E, load_d, miss_d, coef, bias_d)
+        bias_h = orc.router_penalty(mode, idx, load_h, coef, miss=miss_h)
+        np.testing.assert_array_equal(t2n(load_d), load_h)
+        np.testing.assert_allclose(t2n(bias_d), bias_h, rtol=1e-5, atol=1e-6)
+    assert load_h.sum() == 10 * g.route_rows * g.k
+
+
+@pytest.mark.parametrize("spec", [
+    dict(B=16, Hq=32, Hkv=32, D=128, E=2, S=8, k=1, dtype="bf16", rank=32),     # config-5 shape
+    dict(B=3, Hq=4, Hkv=2, D=64, E=2, S=8, k=1, dtype="bf16", rank=16),
+    dict(B=2, Hq=2, Hkv=2, D=128, E=2, S=8, k=1, dtype="f32", rank=64),
+], ids=["c5_shape", "rank16", "f32_rank64"])
+def test_compress_matches_oracle(spec):
+    """codes = W_enc x: fp32 storage to rounding error; bf16 storage equal to the oracle's
+    round-to-nearest-even code except where fp32 vs fp64 summation straddles a rounding
+    boundary (then exactly one bf16 step away)."""
+    from gpu_harness import dev_storage
+    g = wl.Geometry(**spec)
+    rng = np.random.default_rng(9)
+    x = wl.encode(rng.standard_normal((g.B, g.Hkv, g.D)), g.dtype)
+    W = wl.encode(rng.standard_normal((g.Hkv, g.rank, g.D)) / np.sqrt(g.D), g.dtype)
+    ref = orc.compress(x, W, dtype=g.dtype)
+    desc = pk.make_desc(g.B, g.Hq, g.Hkv, g.D, g.E, g.S, rank=g.rank,
+                        dtype=pk.binding.F32 if g.dtype == "f32" else pk.binding.BF16)
+    out = torch.zeros((g.B, g.Hkv, g.rank), device=DEV,
+                      dtype=torch.float32 if g.dtype == "f32" else torch.bfloat16)
+    pk.pikv_compress(desc, dev_storage(x, g.dtype), dev_storage(W, g.dtype), out)
+    torch.cuda.synchronize()
+    got = wl.to_host(out, g.dtype)
+    if g.dtype == "f32":
+        np.testing.assert_allclose(got, ref, rtol=1e-5, atol=1e-6)
+    else:
+        same = got == ref
+        assert same.mean() > 0.99
+        step = np.abs(got.astype(np.int32) - ref.astype(np.int32))
+        assert step.max() <= 1                                  # adjacent bf16 bit patterns
+
+
+def test_compress_then_insert_then_attend_streams_like_the_oracle():
+    """Config-5 style step with compress-on-insert: full-width new K/V -> codes -> fused step."""
+    from gpu_harness import dev_storage
+    g = wl.Geometry(B=3, Hq=4, Hkv=4, D=128, E=8, S=40, k=2, dtype="bf16", rank=32)
+    case = wl.make_host_case(g, seed=61, utility0="exp")
+    ensure_route_margin(case, g.k)
+    rng = np.random.default_rng(5)
+    WK = wl.encode(rng.standard_normal((g.Hkv, g.rank, g.D)) / np.sqrt(g.D), "bf16")
+    WV = wl.encode(rng.standard_normal((g.Hkv, g.rank, g.D)) / np.sqrt(g.D), "bf16")
+    kfull = wl.encode(rng.standard_normal((g.B, g.Hkv, g.D)), "bf16")
+    vfull = wl.encode(rng.standard_normal((g.B, g.Hkv, g.D)), "bf16")
+    dc = DeviceCase(case)
+    kc = torch.zeros((g.B, g.Hkv, g.rank), device=DEV, dtype=torch.bfloat16)
+    vc = torch.zeros_like(kc)
+    pk.pikv_compress(dc.desc, dev_storage(kfull, "bf16"), dev_storage(WK, "bf16"), kc,
+                     dev_storage(vfull, "bf16"), dev_storage(WV, "bf16"), vc)
+    np.testing.assert_array_equal(np.abs(wl.to_host(vc, "bf16").astype(np.int32) -
+                                         orc.compress(vfull, WV, dtype="bf16").astype(np.int32)) <= 1, True)
+    ei = torch.full((g.B, g.E, 1), -1, device=DEV, dtype=torch.int32)
+    ec = torch.zeros((g.B, g.E), device=DEV, dtype=torch.int32)
+    pk.pikv_decode_step(dc.desc, dc.q, dc.W_r, dc.bias, kc, vc, dc.K_tab, dc.V_tab, dc.U_K, dc.U_V,
+                        dc.n_valid, dc.utility, g.k, pk.COMBINE_LSE, 0.0, 1.0, dc.topk, dc.gates, ei, ec,
+                        dc.y, dc.row_max, dc.row_norm, dc.scores, dc.slot_coef, dc.workspace)
+    torch.cuda.synchronize()
+    # oracle on the GPU's own codes (the codes themselves are checked in test_compress_matches_oracle)
+    kc_h, vc_h = wl.to_host(kc, "bf16"), wl.to_host(vc, "bf16")
+    ref = case.clone()
+    x = np.ascontiguousarray(case.q.reshape(g.route_rows, g.d_r))
+    idx, gates, _ = orc.route(x, ref.W_r, g.k, dtype=g.dtype)
+    np.testing.assert_array_equal(t2n(dc.topk), idx)
+    mask = np.zeros((g.B, g.E), np.int32)
+    for b in range(g.B):
+        mask[b, idx[b]] = 1
+    ridx, rcnt = orc.evict(ref.utility, ref.n_valid, g.S - 1, shard_mask=mask, max_evict=1)
+    orc.append(kc_h, vc_h, idx, ref.K_shards, ref.V_shards, ref.utility, ref.n_valid, dtype="bf16",
+               reuse_idx=ridx, reuse_cnt=rcnt)
+    out = oracle_step(ref, idx, gates, orc.COMBINE_LSE, utility=ref.utility, decay=1.0)
+    ok, emax, l2 = y_tolerance_ok(t2n(dc.y), out["y"], g.dtype)
+    assert ok, (emax, l2)
+    assert_utility_close(t2n(dc.utility), ref.utility)
+    for s in range(g.B * g.E):
+        np.testing.assert_array_equal(dc.shard_host("K", s), ref.K_shards[s])
