@@ -573,3 +573,56 @@ def test_compress_then_insert_then_attend_streams_like_the_oracle():
     assert_utility_close(t2n(dc.utility), ref.utility)
     for s in range(g.B * g.E):
         np.testing.assert_array_equal(dc.shard_host("K", s), ref.K_shards[s])
+
+
+def test_strided_shards_on_the_matrix_core_kernel_and_the_fused_step():
+    """Rows padded to a larger pitch and extra slots per head (stride_s > width, stride_h > S*stride_s)
+    through the grouped-query MFMA kernel, both via the separate calls and the fused step."""
+    g = wl.Geometry(B=2, Hq=8, Hkv=2, D=128, E=8, S=150, k=2, dtype="bf16")
+    case = wl.make_host_case(g, seed=71, n_valid="ragged", utility0="exp")
+    case.n_valid[case.n_valid == g.S] = g.S - 1
+    ensure_route_margin(case, g.k)
+    x = np.ascontiguousarray(case.q.reshape(g.route_rows, g.d_r))
+    idx, gates, _ = orc.route(x, case.W_r, g.k, dtype=g.dtype)
+    u_ref = case.utility.copy()
+    ref = oracle_step(case, idx, gates, orc.COMBINE_LSE, utility=u_ref, decay=0.5)
+    for fused in (False, True):
+        dc = DeviceCase(case, stride_pad=(16, 7))
+        if fused:
+            pk.pikv_decode_step(dc.desc, dc.q, dc.W_r, dc.bias, None, None, dc.K_tab, dc.V_tab, None, None,
+                                dc.n_valid, dc.utility, g.k, pk.COMBINE_LSE, 0.0, 0.5, dc.topk, dc.gates,
+                                None, None, dc.y, dc.row_max, dc.row_norm, dc.scores, dc.slot_coef,
+                                dc.workspace)
+        else:
+            dc.route()
+            dc.attend()
+            dc.update_utility(0.5)
+        np.testing.assert_array_equal(t2n(dc.topk), idx)
+        ok, emax, l2 = y_tolerance_ok(t2n(dc.y), ref["y"], g.dtype)
+        assert ok, (fused, emax, l2)
+        assert_utility_close(t2n(dc.utility), u_ref)
+
+
+def test_fused_step_with_many_heads_times_shards_uses_the_separate_merge():
+    """Hq * k beyond what a utility block restages: the step falls back to separate merge and
+    utility launches and still equals the separate calls bit for bit."""
+    g = wl.Geometry(B=1, Hq=64, Hkv=64, D=16, E=64, S=24, k=40, dtype="bf16")
+    case = wl.make_host_case(g, seed=72, utility0="exp", w_sigma=0.2)
+    ensure_route_margin(case, g.k, margin=1e-4)
+    dA, dB = DeviceCase(case), DeviceCase(case)
+    pk.pikv_decode_step(dA.desc, dA.q, dA.W_r, dA.bias, None, None, dA.K_tab, dA.V_tab, None, None,
+                        dA.n_valid, dA.utility, g.k, pk.COMBINE_LSE, 0.0, 1.0, dA.topk, dA.gates,
+                        None, None, dA.y, dA.row_max, dA.row_norm, dA.scores, dA.slot_coef, dA.workspace)
+    dB.route()
+    dB.attend()
+    dB.update_utility(1.0)
+    for name in ("topk", "y", "utility"):
+        np.testing.assert_array_equal(t2n(getattr(dA, name)), t2n(getattr(dB, name)))
+    x = np.ascontiguousarray(case.q.reshape(g.route_rows, g.d_r))
+    idx, gates, _ = orc.route(x, case.W_r, g.k, dtype=g.dtype)
+    np.testing.assert_array_equal(t2n(dA.topk), idx)
+    u_ref = case.utility.copy()
+    ref = oracle_step(case, idx, gates, orc.COMBINE_LSE, utility=u_ref)
+    ok, emax, l2 = y_tolerance_ok(t2n(dA.y), ref["y"], g.dtype)
+    assert ok, (emax, l2)
+    assert_utility_close(t2n(dA.utility), u_ref)
