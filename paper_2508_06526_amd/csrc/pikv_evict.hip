@@ -4,43 +4,60 @@
 //   evict_select : one block per (sequence, expert).  The entries to drop are the
 //                  n - capacity smallest under (utility ascending, slot descending), i.e.
 //                  the complement of the `capacity` best under (utility descending, slot
-//                  ascending).  An 8-bit most-significant-digit radix select over the
-//                  order-preserving integer image of the fp32 utilities finds the cut value
-//                  exactly (no floating-point comparison is ever redone in a different
-//                  order), then one pass in slot order, driven by block-wide prefix sums,
-//                  emits the evicted slots ascending and (optionally) compacts the
+//                  ascending).  A bit-by-bit select over the order-preserving integer image
+//                  of the fp32 utilities, held in registers, finds the cut value exactly
+//                  (no floating-point comparison is ever redone in a different order),
+//                  then one pass in slot order, driven by block-wide ranks of one-bit
+//                  flags, emits the evicted slots ascending and (optionally) compacts the
 //                  utilities in place.
 //   evict_move   : one block per (shard, kv head) slides the kept K and V rows down,
-//                  chunk by chunk in ascending order (a destination never lies above its
-//                  source, so reading a chunk fully before writing it is enough).
+//                  a pass of rows at a time in ascending order (a destination never lies
+//                  above its source, so holding a pass in registers before writing it is
+//                  enough).
 //   append_rows  : one block per (sequence, selected expert) writes the new entry.
 #include "pikv_common.h"
 
 namespace pikv {
 namespace {
 
-constexpr int kEvictThreads = 256;
+constexpr int kEvictThreads = 256;   // evict_move and append_rows
+constexpr int kSelThreads = 1024;    // evict_select
+constexpr int kSelWaves = kSelThreads / kWave;
+constexpr int kSelCache = 24;        // keys a thread keeps in registers (n <= 24576)
 
-// Inclusive prefix sum over the 256 threads of the block; *total receives the block sum.
-__device__ __forceinline__ int block_scan_incl(int v, int *wave_sums, int *total) {
-    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
+// Block-wide sum of a count every lane of a wave already agrees on.  Two buffers used in
+// turn make one barrier per call enough: a buffer is rewritten two calls later, and every
+// wave has left the reads of call i before any wave passes the barrier of call i+1.
+__device__ __forceinline__ int block_sum_waves(int wave_total, int (*buf)[kSelWaves], int &turn) {
+    int *slot = buf[turn & 1];
+    ++turn;
+    if ((threadIdx.x & (kWave - 1)) == 0) slot[threadIdx.x >> 6] = wave_total;
+    __syncthreads();
+    int all = 0;
 #pragma unroll
-    for (int off = 1; off < kWave; off <<= 1) {
-        const int t = __shfl_up(v, off, kWave);
-        if (lane >= off) v += t;
-    }
-    __syncthreads();                      // protects wave_sums from the previous use
-    if (lane == kWave - 1) wave_sums[wave] = v;
+    for (int w = 0; w < kSelWaves; ++w) all += slot[w];
+    return all;
+}
+
+// Exclusive block-wide rank of a one-bit flag in thread order; *total receives the block sum.
+__device__ __forceinline__ int block_rank_flag(bool flag, int (*buf)[kSelWaves], int &turn,
+                                               int *total) {
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
+    const uint64_t votes = __ballot(flag);
+    const int in_wave = __popcll(votes & ((1ull << lane) - 1ull));
+    int *slot = buf[turn & 1];
+    ++turn;
+    if (lane == 0) slot[wave] = __popcll(votes);
     __syncthreads();
     int before = 0, all = 0;
 #pragma unroll
-    for (int w = 0; w < kEvictThreads / kWave; ++w) {
-        const int s = wave_sums[w];
+    for (int w = 0; w < kSelWaves; ++w) {
+        const int s = slot[w];
         if (w < wave) before += s;
         all += s;
     }
     *total = all;
-    return v + before;
+    return before + in_wave;
 }
 
 struct EvictParams {
@@ -52,14 +69,96 @@ struct EvictParams {
     int E, S, capacity, sel_k, max_evict, compact;
 };
 
-__global__ __launch_bounds__(kEvictThreads) void evict_select(EvictParams p) {
+// General case: drop the `ngone` worst of `n` entries.  The cut (the ngone-th smallest key)
+// is found one bit at a time from the top: count the candidates whose next bit is 0 and
+// step into the half that holds the wanted rank.  With CACHED the keys sit in registers
+// (slot i = tid + j * kSelThreads lives in keys[j]), so all 32 steps touch no memory.
+template <bool CACHED>
+__device__ __forceinline__ void select_many(const EvictParams &p, int be, float *u, int n,
+                                            int ngone, int (*buf)[kSelWaves]) {
+    const int tid = threadIdx.x;
+    const int nchunk = (n + kSelThreads - 1) / kSelThreads;
+    uint32_t keys[CACHED ? kSelCache : 1];
+    if (CACHED) {
+#pragma unroll
+        for (int j = 0; j < kSelCache; ++j) {
+            const int i = tid + j * kSelThreads;
+            keys[j] = (j < nchunk && i < n) ? order_key(u[i]) : 0u;
+        }
+    }
+    int turn = 0;
+    uint32_t prefix = 0;
+    int remaining = ngone;   // rank still to locate among the keys that match `prefix`
+    int cand = n;            // how many keys match `prefix` on the bits decided so far
+    for (int bit = 31; bit >= 0; --bit) {
+        int zeros = 0;       // wave-uniform: candidates in this wave whose `bit` is 0
+        auto tally = [&](uint32_t key, int i) {
+            const bool hit = i < n && ((uint64_t)(key ^ prefix) >> (bit + 1)) == 0 &&
+                             ((key >> bit) & 1u) == 0;
+            zeros += __popcll(__ballot(hit));
+        };
+        if (CACHED) {
+#pragma unroll
+            for (int j = 0; j < kSelCache; ++j)
+                if (j < nchunk) tally(keys[j], tid + j * kSelThreads);
+        } else {
+            for (int j = 0; j < nchunk; ++j) {
+                const int i = tid + j * kSelThreads;
+                tally(i < n ? order_key(u[i]) : 0u, i);
+            }
+        }
+        const int tot0 = block_sum_waves(zeros, buf, turn);
+        if (remaining > tot0) {
+            remaining -= tot0;
+            cand -= tot0;
+            prefix |= 1u << bit;
+        } else {
+            cand = tot0;
+        }
+    }
+    const uint32_t cut = prefix;          // keys < cut go; of the keys == cut (`cand` of
+    const int keep_eq = cand - remaining; // them), the first keep_eq in slot order stay
+
+    int eq_seen = 0, gone_seen = 0;       // running totals over the chunks already done
+    auto emit = [&](uint32_t key, int i) {
+        const bool valid = i < n;
+        float ui = 0.0f;
+        if (valid && p.compact) ui = u[i];
+        const bool is_eq = valid && key == cut, is_less = valid && key < cut;
+        int eq_total, gone_total;
+        const int eq_rank = eq_seen + block_rank_flag(is_eq, buf, turn, &eq_total);
+        const bool gone = is_less || (is_eq && eq_rank >= keep_eq);
+        const int gone_before = gone_seen + block_rank_flag(gone, buf, turn, &gone_total);
+        if (valid) {
+            if (gone) {
+                if (gone_before < p.max_evict)
+                    p.evicted_idx[(int64_t)be * p.max_evict + gone_before] = i;
+            }
+            else if (p.compact && gone_before > 0)
+                u[i - gone_before] = ui;  // this chunk's reads ended before the barriers above
+        }
+        eq_seen += eq_total;
+        gone_seen += gone_total;
+    };
+    if (CACHED) {
+#pragma unroll
+        for (int j = 0; j < kSelCache; ++j)
+            if (j < nchunk) emit(keys[j], tid + j * kSelThreads);
+    } else {
+        for (int j = 0; j < nchunk; ++j) {
+            const int i = tid + j * kSelThreads;
+            emit(i < n ? order_key(u[i]) : 0u, i);
+        }
+    }
+}
+
+__global__ __launch_bounds__(kSelThreads) void evict_select(EvictParams p) {
     const int be = blockIdx.x;
     const int b = be / p.E, e = be - b * p.E;
     const int tid = threadIdx.x;
 
-    __shared__ int hist[256];
-    __shared__ int wave_sums[kEvictThreads / kWave];
-    __shared__ int pick_digit, pick_before;
+    __shared__ int wave_cnt[2][kSelWaves];
+    __shared__ uint64_t wave_best[kSelWaves];
 
     bool selected = true;
     if (p.sel_idx) {
@@ -79,18 +178,16 @@ __global__ __launch_bounds__(kEvictThreads) void evict_select(EvictParams p) {
         // One composite 64-bit value per entry orders both at once.
         uint64_t best = ~0ull;
         const int n4 = (p.S % 4 == 0) ? (n / 4) * 4 : 0;   // float4 reads need aligned rows
-        for (int i = tid * 4; i < n4; i += kEvictThreads * 4) {
+        for (int i = tid * 4; i < n4; i += kSelThreads * 4) {
             const float4 v = *reinterpret_cast<const float4 *>(u + i);
-            const uint64_t c0 = ((uint64_t)order_key(v.x) << 32) | (uint32_t)(0x7fffffff - i);
-            const uint64_t c1 = ((uint64_t)order_key(v.y) << 32) | (uint32_t)(0x7fffffff - (i + 1));
-            const uint64_t c2 = ((uint64_t)order_key(v.z) << 32) | (uint32_t)(0x7fffffff - (i + 2));
-            const uint64_t c3 = ((uint64_t)order_key(v.w) << 32) | (uint32_t)(0x7fffffff - (i + 3));
+            const uint64_t c0 = evict_composite(v.x, i), c1 = evict_composite(v.y, i + 1);
+            const uint64_t c2 = evict_composite(v.z, i + 2), c3 = evict_composite(v.w, i + 3);
             const uint64_t a = c0 < c1 ? c0 : c1, b2 = c2 < c3 ? c2 : c3;
             const uint64_t c = a < b2 ? a : b2;
             best = c < best ? c : best;
         }
-        for (int i = n4 + tid; i < n; i += kEvictThreads) {
-            const uint64_t c = ((uint64_t)order_key(u[i]) << 32) | (uint32_t)(0x7fffffff - i);
+        for (int i = n4 + tid; i < n; i += kSelThreads) {
+            const uint64_t c = evict_composite(u[i], i);
             best = c < best ? c : best;
         }
 #pragma unroll
@@ -98,75 +195,23 @@ __global__ __launch_bounds__(kEvictThreads) void evict_select(EvictParams p) {
             const uint64_t o = __shfl_xor(best, off, kWave);
             best = o < best ? o : best;
         }
-        __shared__ uint64_t wave_best[kEvictThreads / kWave];
         if ((tid & (kWave - 1)) == 0) wave_best[tid >> 6] = best;
         __syncthreads();
         if (tid == 0) {
             uint64_t m = wave_best[0];
 #pragma unroll
-            for (int w = 1; w < kEvictThreads / kWave; ++w) m = wave_best[w] < m ? wave_best[w] : m;
-            p.evicted_idx[(int64_t)be * p.max_evict] = 0x7fffffff - (int)(uint32_t)(m & 0xffffffffu);
+            for (int w = 1; w < kSelWaves; ++w) m = wave_best[w] < m ? wave_best[w] : m;
+            p.evicted_idx[(int64_t)be * p.max_evict] = evict_composite_slot(m);
             p.evicted_cnt[be] = 1;
             p.n_valid[be] = p.capacity;
         }
         return;
     }
 
-    // radix select: value of the ngone-th smallest key
-    uint32_t prefix = 0, mask = 0;
-    int remaining = ngone;   // rank still to locate among the keys matching `prefix`
-    int count_eq = 0;
-    for (int shift = 24; shift >= 0; shift -= 8) {
-        hist[tid] = 0;
-        __syncthreads();
-        for (int i = tid; i < n; i += kEvictThreads) {
-            const uint32_t key = order_key(u[i]);
-            if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 0xff], 1);
-        }
-        __syncthreads();
-        const int mine = hist[tid];
-        int total;
-        const int incl = block_scan_incl(mine, wave_sums, &total);
-        if (incl - mine < remaining && remaining <= incl) {
-            pick_digit = tid;
-            pick_before = incl - mine;
-        }
-        __syncthreads();
-        prefix |= (uint32_t)pick_digit << shift;
-        mask |= 0xffu << shift;
-        remaining -= pick_before;
-        count_eq = hist[pick_digit];
-        __syncthreads();
-    }
-    const uint32_t cut = prefix;            // keys < cut go; of the keys == cut, the
-    const int keep_eq = count_eq - remaining;  // first keep_eq in slot order stay
-
-    int eq_seen = 0, gone_seen = 0;         // running totals over the chunks already done
-    for (int base = 0; base < n; base += kEvictThreads) {
-        const int i = base + tid;
-        float ui = 0.0f;
-        int is_eq = 0, is_less = 0;
-        if (i < n) {
-            ui = u[i];
-            const uint32_t key = order_key(ui);
-            is_eq = key == cut;
-            is_less = key < cut;
-        }
-        int eq_total, gone_total;
-        const int eq_incl = block_scan_incl(is_eq, wave_sums, &eq_total);
-        const int eq_rank = eq_seen + eq_incl - is_eq;           // equal keys before slot i
-        const int gone = is_less | (is_eq & (eq_rank >= keep_eq));
-        const int gone_incl = block_scan_incl(gone, wave_sums, &gone_total);
-        const int gone_before = gone_seen + gone_incl - gone;
-        if (i < n) {
-            if (gone)
-                p.evicted_idx[(int64_t)be * p.max_evict + gone_before] = i;
-            else if (p.compact && gone_before > 0)
-                u[i - gone_before] = ui;    // reads of this chunk finished at the scans' barriers
-        }
-        eq_seen += eq_total;
-        gone_seen += gone_total;
-    }
+    if (n <= kSelCache * kSelThreads)
+        select_many<true>(p, be, u, n, ngone, wave_cnt);
+    else
+        select_many<false>(p, be, u, n, ngone, wave_cnt);
     if (tid == 0) {
         p.evicted_cnt[be] = ngone;
         p.n_valid[be] = p.capacity;
@@ -180,45 +225,85 @@ struct MoveParams {
     const int32_t *evicted_idx;
     const int32_t *evicted_cnt;
     int64_t stride_h_bytes, stride_s_bytes;
-    int row_chunks;      // 16-byte chunks per row
+    int row_chunks;      // 16-byte chunks per row, 1..kEvictThreads
     int max_evict;
 };
 
+constexpr int kMoveRows = 8;                             // rows a thread carries per pass
+constexpr int kMoveFlagWords = kEvictThreads * kMoveRows / 32;
+static_assert(kMoveFlagWords == kWave, "one wave ranks the flag words");
+
 __global__ __launch_bounds__(kEvictThreads) void evict_move(MoveParams p) {
     const int be = blockIdx.x, hk = blockIdx.y;
+    const int tid = threadIdx.x;
     const int cnt = p.evicted_cnt[be];
     if (cnt <= 0) return;
     const int n_old = p.n_valid[be] + cnt;
     const int32_t *gone = p.evicted_idx + (int64_t)be * p.max_evict;
-    const int rows_per_pass = kEvictThreads / p.row_chunks;
-    const int rsub = threadIdx.x / p.row_chunks, csub = threadIdx.x % p.row_chunks;
+    const int group_rows = kEvictThreads / p.row_chunks;   // rows covered by one sweep of the block
+    const int pass_rows = group_rows * kMoveRows;
+    const int rsub = tid / p.row_chunks, csub = tid - rsub * p.row_chunks;
+    const bool lane_used = rsub < group_rows;
     char *Kb = static_cast<char *>(p.K[be]) + hk * p.stride_h_bytes + csub * 16;
     char *Vb = static_cast<char *>(p.V[be]) + hk * p.stride_h_bytes + csub * 16;
-    for (int base = gone[0]; base < n_old; base += rows_per_pass) {
-        const int row = base + rsub;
-        const bool active = rsub < rows_per_pass && row < n_old;
-        int before = 0;
-        bool dropped = false;
-        uint4 kv = make_uint4(0, 0, 0, 0), vv = kv;
-        if (active) {
-            int lo = 0, hi = cnt;            // number of evicted slots < row
-            while (lo < hi) {
-                const int mid = (lo + hi) >> 1;
-                if (gone[mid] < row) lo = mid + 1; else hi = mid;
-            }
-            before = lo;
-            dropped = lo < cnt && gone[lo] == row;
-            if (!dropped) {
-                kv = *reinterpret_cast<const uint4 *>(Kb + row * p.stride_s_bytes);
-                vv = *reinterpret_cast<const uint4 *>(Vb + row * p.stride_s_bytes);
+
+    // One bit per row of the pass: set = the row is evicted.  The list is ascending, so the
+    // evicted rows of a pass are the next entries after the `run` ones already passed.
+    __shared__ uint32_t flags[kMoveFlagWords];
+    __shared__ int flags_before[kMoveFlagWords + 1];   // set bits in the words below; [last] = all
+    int run = 0;
+    for (int base = gone[0]; base < n_old; base += pass_rows) {
+        if (tid < kMoveFlagWords) flags[tid] = 0u;
+        __syncthreads();
+        for (int x = tid; x < pass_rows; x += kEvictThreads) {
+            if (run + x < cnt) {
+                const int off = gone[run + x] - base;
+                if (off < pass_rows) atomicOr(&flags[off >> 5], 1u << (off & 31));
             }
         }
         __syncthreads();
-        if (active && !dropped && before > 0) {
-            *reinterpret_cast<uint4 *>(Kb + (row - before) * p.stride_s_bytes) = kv;
-            *reinterpret_cast<uint4 *>(Vb + (row - before) * p.stride_s_bytes) = vv;
+        if (tid < kWave) {               // the first wave ranks the 64 words
+            const int mine = __popc(flags[tid]);
+            int incl = mine;
+#pragma unroll
+            for (int off = 1; off < kWave; off <<= 1) {
+                const int t = __shfl_up(incl, off, kWave);
+                if (tid >= off) incl += t;
+            }
+            flags_before[tid] = incl - mine;
+            if (tid == kWave - 1) flags_before[kMoveFlagWords] = incl;
         }
         __syncthreads();
+        uint4 kv[kMoveRows], vv[kMoveRows];
+        int dst[kMoveRows];
+#pragma unroll
+        for (int r = 0; r < kMoveRows; ++r) {
+            const int off = r * group_rows + rsub;
+            const int row = base + off;
+            dst[r] = -1;
+            kv[r] = make_uint4(0, 0, 0, 0);
+            vv[r] = kv[r];
+            if (lane_used && row < n_old) {
+                const int word = off >> 5, pos = off & 31;
+                const uint32_t mine = flags[word];
+                const int before = run + flags_before[word] + __popc(mine & ((1u << pos) - 1u));
+                if (!((mine >> pos) & 1u) && before > 0) {
+                    dst[r] = row - before;
+                    kv[r] = *reinterpret_cast<const uint4 *>(Kb + row * p.stride_s_bytes);
+                    vv[r] = *reinterpret_cast<const uint4 *>(Vb + row * p.stride_s_bytes);
+                }
+            }
+        }
+        const int passed = flags_before[kMoveFlagWords];
+        __syncthreads();                 // every row of the pass is in registers
+#pragma unroll
+        for (int r = 0; r < kMoveRows; ++r) {
+            if (dst[r] >= 0) {
+                *reinterpret_cast<uint4 *>(Kb + dst[r] * p.stride_s_bytes) = kv[r];
+                *reinterpret_cast<uint4 *>(Vb + dst[r] * p.stride_s_bytes) = vv[r];
+            }
+        }
+        run += passed;
     }
 }
 
@@ -280,6 +365,8 @@ extern "C" int pikv_evict(const pikv_desc *desc, float *utility, int32_t *n_vali
     if (sel_idx && (sel_k < 1 || sel_k > desc->E)) return PIKV_ERR_INVALID;
     if (compact && (!K_shards || !V_shards)) return PIKV_ERR_INVALID;
     if (desc->B == 0) return PIKV_OK;
+    const int row_chunks = desc_width(desc) * elem_bytes(desc->dtype) / 16;
+    if (compact && (row_chunks < 1 || row_chunks > kEvictThreads)) return PIKV_ERR_UNSUPPORTED;
     hipStream_t st = as_stream(stream);
     EvictParams p;
     p.utility = utility;
@@ -293,7 +380,7 @@ extern "C" int pikv_evict(const pikv_desc *desc, float *utility, int32_t *n_vali
     p.sel_k = sel_k;
     p.max_evict = max_evict;
     p.compact = compact ? 1 : 0;
-    hipLaunchKernelGGL(evict_select, dim3(desc->B * desc->E), dim3(kEvictThreads), 0, st, p);
+    hipLaunchKernelGGL(evict_select, dim3(desc->B * desc->E), dim3(kSelThreads), 0, st, p);
     int lrc = launch_status();
     if (lrc != PIKV_OK || !compact) return lrc;
     MoveParams m;
@@ -305,7 +392,7 @@ extern "C" int pikv_evict(const pikv_desc *desc, float *utility, int32_t *n_vali
     const int eb = elem_bytes(desc->dtype);
     m.stride_h_bytes = desc->stride_h * eb;
     m.stride_s_bytes = desc->stride_s * eb;
-    m.row_chunks = desc_width(desc) * eb / 16;
+    m.row_chunks = row_chunks;
     m.max_evict = max_evict;
     hipLaunchKernelGGL(evict_move, dim3(desc->B * desc->E, desc->Hkv), dim3(kEvictThreads), 0, st,
                        m);
