@@ -141,11 +141,13 @@ int pikv_update_utility(const pikv_desc *desc, const float *scores, const float 
  *            -1, and the shard is left untouched, if n - capacity > max_evict)
  *   compact  != 0: move the kept rows of K, V (all kv heads) and utility down to slots
  *            0..capacity-1 in ascending original order (K_shards/V_shards required).
+ *            A moved utility keeps its value; a negative zero may come back as +0.
  *            == 0: rows stay where they are; the evicted slots are holes the caller must
  *            refill with pikv_append (reuse_idx) before the next attention call.
  *   n_valid  [B,E] int32, in place: becomes capacity for shards that evicted.
  * Errors: INVALID for null utility/n_valid/evicted_*, capacity < 0, max_evict < 1,
- * sel_k not in 1..E when sel_idx is given, compact without shard tables.                   */
+ * sel_k not in 1..E when sel_idx is given, compact without shard tables; UNSUPPORTED for
+ * compact with rows wider than 4096 bytes.                                                  */
 int pikv_evict(const pikv_desc *desc, float *utility, int32_t *n_valid, int32_t capacity,
                const int32_t *sel_idx, int32_t sel_k, int32_t *evicted_idx,
                int32_t *evicted_cnt, int32_t max_evict, int32_t compact,

@@ -4,13 +4,13 @@
 //   evict_select : one block per (sequence, expert).  The entries to drop are the
 //                  n - capacity smallest under (utility ascending, slot descending), i.e.
 //                  the complement of the `capacity` best under (utility descending, slot
-//                  ascending).  A bit-by-bit select over the order-preserving integer image
+//                  ascending).  A two-bits-a-step select over the order-preserving integer image
 //                  of the fp32 utilities, held in registers, finds the cut value exactly
 //                  (no floating-point comparison is ever redone in a different order),
-//                  then one pass in slot order, driven by block-wide ranks of one-bit
-//                  flags, emits the evicted slots ascending and (optionally) compacts the
-//                  utilities in place.
-//   evict_move   : one block per (shard, kv head) slides the kept K and V rows down,
+//                  then one pass in slot order, driven by a block-wide prefix sum of the
+//                  per-thread counts, emits the evicted slots ascending and (optionally)
+//                  compacts the utilities in place.
+//   evict_move   : one block per (shard, kv head, K or V, row slice) slides the kept rows down,
 //                  a pass of rows at a time in ascending order (a destination never lies
 //                  above its source, so holding a pass in registers before writing it is
 //                  enough).
@@ -20,41 +20,55 @@
 namespace pikv {
 namespace {
 
-constexpr int kEvictThreads = 256;   // evict_move and append_rows
-constexpr int kSelThreads = 1024;    // evict_select
-constexpr int kSelWaves = kSelThreads / kWave;
-constexpr int kSelCache = 24;        // keys a thread keeps in registers (n <= 24576)
+constexpr int kEvictThreads = 256;   // every kernel of this file
+constexpr int kSelWaves = kEvictThreads / kWave;
+constexpr int kSelCache = 128;       // keys a thread can keep in registers (n <= 32768);
+                                     // at most 255: the digit counts of a step are bytes
 
-// Block-wide sum of a count every lane of a wave already agrees on.  Two buffers used in
-// turn make one barrier per call enough: a buffer is rewritten two calls later, and every
-// wave has left the reads of call i before any wave passes the barrier of call i+1.
-__device__ __forceinline__ int block_sum_waves(int wave_total, int (*buf)[kSelWaves], int &turn) {
-    int *slot = buf[turn & 1];
-    ++turn;
-    if ((threadIdx.x & (kWave - 1)) == 0) slot[threadIdx.x >> 6] = wave_total;
-    __syncthreads();
-    int all = 0;
+struct SelShared {
+    int cnt[2][3 * kSelWaves];       // per-wave digit counts of a select step, two buffers in turn
+    int scan[2][kSelWaves];          // per-wave totals of a block scan, two buffers in turn
+    uint64_t wave_best[kSelWaves];
+};
+// Both pairs of buffers are used in turn, which makes one barrier per use enough: a buffer
+// is rewritten two uses later, and every wave has left the reads of use i before any wave
+// passes the barrier of use i+1.
+
+// Exclusive prefix sum of v over the block in thread order.
+__device__ __forceinline__ int block_scan_excl(int v, SelShared &sh, int &turn) {
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
+    int incl = v;
 #pragma unroll
-    for (int w = 0; w < kSelWaves; ++w) all += slot[w];
-    return all;
+    for (int off = 1; off < kWave; off <<= 1) {
+        const int t = __shfl_up(incl, off, kWave);
+        if (lane >= off) incl += t;
+    }
+    int *slot = sh.scan[turn & 1];
+    ++turn;
+    if (lane == kWave - 1) slot[wave] = incl;
+    __syncthreads();
+    int before = 0;
+#pragma unroll
+    for (int w = 0; w < kSelWaves - 1; ++w)
+        if (w < wave) before += slot[w];
+    return before + incl - v;
 }
 
 // Exclusive block-wide rank of a one-bit flag in thread order; *total receives the block sum.
-__device__ __forceinline__ int block_rank_flag(bool flag, int (*buf)[kSelWaves], int &turn,
-                                               int *total) {
+__device__ __forceinline__ int block_rank_flag(bool flag, SelShared &sh, int &turn, int *total) {
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
     const uint64_t votes = __ballot(flag);
     const int in_wave = __popcll(votes & ((1ull << lane) - 1ull));
-    int *slot = buf[turn & 1];
+    int *slot = sh.scan[turn & 1];
     ++turn;
     if (lane == 0) slot[wave] = __popcll(votes);
     __syncthreads();
     int before = 0, all = 0;
 #pragma unroll
     for (int w = 0; w < kSelWaves; ++w) {
-        const int s = slot[w];
-        if (w < wave) before += s;
-        all += s;
+        const int c = slot[w];
+        if (w < wave) before += c;
+        all += c;
     }
     *total = all;
     return before + in_wave;
@@ -69,96 +83,227 @@ struct EvictParams {
     int E, S, capacity, sel_k, max_evict, compact;
 };
 
-// General case: drop the `ngone` worst of `n` entries.  The cut (the ngone-th smallest key)
-// is found one bit at a time from the top: count the candidates whose next bit is 0 and
-// step into the half that holds the wanted rank.  With CACHED the keys sit in registers
-// (slot i = tid + j * kSelThreads lives in keys[j]), so all 32 steps touch no memory.
-template <bool CACHED>
-__device__ __forceinline__ void select_many(const EvictParams &p, int be, float *u, int n,
-                                            int ngone, int (*buf)[kSelWaves]) {
-    const int tid = threadIdx.x;
-    const int nchunk = (n + kSelThreads - 1) / kSelThreads;
-    uint32_t keys[CACHED ? kSelCache : 1];
-    if (CACHED) {
-#pragma unroll
-        for (int j = 0; j < kSelCache; ++j) {
-            const int i = tid + j * kSelThreads;
-            keys[j] = (j < nchunk && i < n) ? order_key(u[i]) : 0u;
-        }
-    }
-    int turn = 0;
-    uint32_t prefix = 0;
-    int remaining = ngone;   // rank still to locate among the keys that match `prefix`
-    int cand = n;            // how many keys match `prefix` on the bits decided so far
-    for (int bit = 31; bit >= 0; --bit) {
-        int zeros = 0;       // wave-uniform: candidates in this wave whose `bit` is 0
-        auto tally = [&](uint32_t key, int i) {
-            const bool hit = i < n && ((uint64_t)(key ^ prefix) >> (bit + 1)) == 0 &&
-                             ((key >> bit) & 1u) == 0;
-            zeros += __popcll(__ballot(hit));
-        };
-        if (CACHED) {
-#pragma unroll
-            for (int j = 0; j < kSelCache; ++j)
-                if (j < nchunk) tally(keys[j], tid + j * kSelThreads);
-        } else {
-            for (int j = 0; j < nchunk; ++j) {
-                const int i = tid + j * kSelThreads;
-                tally(i < n ? order_key(u[i]) : 0u, i);
-            }
-        }
-        const int tot0 = block_sum_waves(zeros, buf, turn);
-        if (remaining > tot0) {
-            remaining -= tot0;
-            cand -= tot0;
-            prefix |= 1u << bit;
-        } else {
-            cand = tot0;
-        }
-    }
-    const uint32_t cut = prefix;          // keys < cut go; of the keys == cut (`cand` of
-    const int keep_eq = cand - remaining; // them), the first keep_eq in slot order stay
+// fp32 value whose order_key is `key` (a negative zero comes back as positive zero)
+__device__ __forceinline__ float key_value(uint32_t key) {
+    return __uint_as_float((key & 0x80000000u) ? (key & 0x7fffffffu) : ~key);
+}
 
-    int eq_seen = 0, gone_seen = 0;       // running totals over the chunks already done
-    auto emit = [&](uint32_t key, int i) {
-        const bool valid = i < n;
-        float ui = 0.0f;
-        if (valid && p.compact) ui = u[i];
-        const bool is_eq = valid && key == cut, is_less = valid && key < cut;
-        int eq_total, gone_total;
-        const int eq_rank = eq_seen + block_rank_flag(is_eq, buf, turn, &eq_total);
-        const bool gone = is_less || (is_eq && eq_rank >= keep_eq);
-        const int gone_before = gone_seen + block_rank_flag(gone, buf, turn, &gone_total);
-        if (valid) {
-            if (gone) {
-                if (gone_before < p.max_evict)
-                    p.evicted_idx[(int64_t)be * p.max_evict + gone_before] = i;
-            }
-            else if (p.compact && gone_before > 0)
-                u[i - gone_before] = ui;  // this chunk's reads ended before the barriers above
+// Sum over the 64 lanes of a wave, returned in every lane.
+__device__ __forceinline__ int wave_sum(int v) {
+    v += __builtin_amdgcn_update_dpp(0, v, 0xB1, 0xf, 0xf, true);    // lane ^ 1
+    v += __builtin_amdgcn_update_dpp(0, v, 0x4E, 0xf, 0xf, true);    // lane ^ 2
+    v += __builtin_amdgcn_update_dpp(0, v, 0x141, 0xf, 0xf, true);   // mirror within 8
+    v += __builtin_amdgcn_update_dpp(0, v, 0x140, 0xf, 0xf, true);   // mirror within 16
+    v += __shfl_xor(v, 16, kWave);
+    v += __shfl_xor(v, 32, kWave);
+    return v;
+}
+
+// The cut of the general case (drop the `ngone` worst of `n`) is the ngone-th smallest key,
+// found two bits at a time from the top.  With x = key ^ prefix, the candidates whose next
+// digit is below d are exactly the keys with x < d << shift, so three compares per key give
+// the cumulative digit counts and the step enters the digit that holds the wanted rank.
+struct CutSearch {
+    uint32_t prefix = 0;
+    int remaining;           // rank still to locate among the keys that match `prefix`
+    int cand;                // how many keys match `prefix` on the digits decided so far
+    int turn = 0;
+    __device__ CutSearch(int n, int ngone) : remaining(ngone), cand(n) {}
+
+    // c1..c3: this thread's candidates with digit < 1, < 2, < 3.  With PACKED the caller
+    // promises at most 512 per thread, so a wave's totals fit 16 bits and c1, c2 travel
+    // through the lane sums as one word.
+    template <bool PACKED>
+    __device__ __forceinline__ void step(int shift, int c1, int c2, int c3, SelShared &sh) {
+        const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
+        if (PACKED) {
+            const int c12 = wave_sum(c1 | (c2 << 16));
+            c1 = c12 & 0xffff;
+            c2 = (int)((uint32_t)c12 >> 16);
+        } else {
+            c1 = wave_sum(c1);
+            c2 = wave_sum(c2);
         }
-        eq_seen += eq_total;
-        gone_seen += gone_total;
-    };
-    if (CACHED) {
+        c3 = wave_sum(c3);
+        int *slot = sh.cnt[turn & 1];
+        ++turn;
+        if (lane == 0) {
+            slot[wave] = c1;
+            slot[kSelWaves + wave] = c2;
+            slot[2 * kSelWaves + wave] = c3;
+        }
+        __syncthreads();
+        // lanes 0..11 fetch the 3 x 4 counts; quad sums leave the totals in lanes 0, 4, 8
+        int v = lane < 3 * kSelWaves ? slot[lane] : 0;
+        v += __builtin_amdgcn_update_dpp(0, v, 0xB1, 0xf, 0xf, true);
+        v += __builtin_amdgcn_update_dpp(0, v, 0x4E, 0xf, 0xf, true);
+        static_assert(kSelWaves == 4, "quad sums");
+        const int C1 = __builtin_amdgcn_readlane(v, 0);
+        const int C2 = __builtin_amdgcn_readlane(v, 4);
+        const int C3 = __builtin_amdgcn_readlane(v, 8);
+        if (remaining <= C1) {
+            cand = C1;
+        } else if (remaining <= C2) {
+            prefix |= 1u << shift;
+            remaining -= C1;
+            cand = C2 - C1;
+        } else if (remaining <= C3) {
+            prefix |= 2u << shift;
+            remaining -= C2;
+            cand = C3 - C2;
+        } else {
+            prefix |= 3u << shift;
+            remaining -= C3;
+            cand -= C3;
+        }
+    }
+};
+
+// Keys in registers: thread t owns the `per` consecutive slots from t * per (per a multiple
+// of 4, at most NCH), so the 16 steps touch no memory and slot order is thread order.  Slots
+// past n hold the largest key: its digit is always 3, which no cumulative count includes.
+template <int NCH>
+__device__ __forceinline__ void select_cached(const EvictParams &p, int be, float *u, int n,
+                                              int ngone, SelShared &sh) {
+    const int tid = threadIdx.x;
+    const int per = (n + kEvictThreads * 4 - 1) / (kEvictThreads * 4) * 4;
+    const int first = tid * per;
+    // The row is 16-byte aligned and S is a multiple of 4 (the caller checked), so a group
+    // of four that starts below n lies inside the row; groups past n re-read the first one.
+    // No branch around the loads: all of them are in flight together.
+    uint32_t keys[NCH];
 #pragma unroll
-        for (int j = 0; j < kSelCache; ++j)
-            if (j < nchunk) emit(keys[j], tid + j * kSelThreads);
-    } else {
-        for (int j = 0; j < nchunk; ++j) {
-            const int i = tid + j * kSelThreads;
-            emit(i < n ? order_key(u[i]) : 0u, i);
+    for (int j0 = 0; j0 < NCH; j0 += 4) {
+        const int i0 = first + j0;
+        const bool any = j0 < per && i0 < n;
+        const float4 v = *reinterpret_cast<const float4 *>(u + (any ? i0 : 0));
+        keys[j0] = any ? order_key(v.x) : 0xffffffffu;
+        keys[j0 + 1] = (any && i0 + 1 < n) ? order_key(v.y) : 0xffffffffu;
+        keys[j0 + 2] = (any && i0 + 2 < n) ? order_key(v.z) : 0xffffffffu;
+        keys[j0 + 3] = (any && i0 + 3 < n) ? order_key(v.w) : 0xffffffffu;
+    }
+    CutSearch cs(n, ngone);
+    for (int shift = 30; shift >= 0; shift -= 2) {
+        // One byte of `acc` per digit value; a key off the prefix has x >> shift >= 4 and is
+        // counted with digit 3, which no cumulative count includes.  No compare, no carry.
+        uint32_t acc = 0;
+#pragma unroll
+        for (int j0 = 0; j0 < NCH; j0 += 4) {
+            if (j0 < per) {
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    const uint32_t digit = min((keys[j0 + t] ^ cs.prefix) >> shift, 3u);
+                    acc += 1u << (digit << 3);
+                }
+            }
+        }
+        const int c1 = acc & 0xff;
+        const int c2 = c1 + ((acc >> 8) & 0xff);
+        const int c3 = c2 + ((acc >> 16) & 0xff);
+        cs.step<true>(shift, c1, c2, c3, sh);
+    }
+    const uint32_t cut = cs.prefix;               // keys < cut go; of the keys == cut (`cand`
+    const int keep_eq = cs.cand - cs.remaining;   // of them) the first keep_eq in slot order stay
+
+    constexpr int kWords = (NCH + 31) / 32;
+    uint32_t gone[kWords];
+#pragma unroll
+    for (int w = 0; w < kWords; ++w) gone[w] = 0;
+    int n_eq = 0, n_gone = 0;
+#pragma unroll
+    for (int j = 0; j < NCH; ++j) {
+        const bool valid = j < per && first + j < n;
+        const bool g = valid && (keys[j] < cut || (keep_eq == 0 && keys[j] == cut));
+        gone[j >> 5] |= (g ? 1u : 0u) << (j & 31);
+        n_gone += g;
+        n_eq += valid && keys[j] == cut;
+    }
+    if (keep_eq > 0) {                            // ties at the cut: the earliest keep_eq stay
+        int eq_rank = block_scan_excl(n_eq, sh, cs.turn);
+#pragma unroll
+        for (int j = 0; j < NCH; ++j) {
+            const bool valid = j < per && first + j < n;
+            if (valid && keys[j] == cut) {
+                if (eq_rank >= keep_eq) {
+                    gone[j >> 5] |= 1u << (j & 31);
+                    ++n_gone;
+                }
+                ++eq_rank;
+            }
+        }
+    }
+    int rank = block_scan_excl(n_gone, sh, cs.turn);   // evicted slots before my first slot
+    int32_t *out = p.evicted_idx + (int64_t)be * p.max_evict;
+    // In-place compaction is safe here: every utility is already held as a key.
+#pragma unroll
+    for (int j0 = 0; j0 < NCH; j0 += 4) {
+        if (j0 < per) {
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const int j = j0 + t, i = first + j;
+                if (i < n) {
+                    if ((gone[j >> 5] >> (j & 31)) & 1u) {
+                        if (rank < p.max_evict) out[rank] = i;
+                        ++rank;
+                    } else if (p.compact && rank > 0) {
+                        u[i - rank] = key_value(keys[j]);
+                    }
+                }
+            }
         }
     }
 }
 
-__global__ __launch_bounds__(kSelThreads) void evict_select(EvictParams p) {
+// More keys than the registers hold: every step re-reads them (slot i = tid + j * 256).
+__device__ __forceinline__ void select_stream(const EvictParams &p, int be, float *u, int n,
+                                              int ngone, SelShared &sh) {
+    const int tid = threadIdx.x;
+    const int nchunk = (n + kEvictThreads - 1) / kEvictThreads;
+    CutSearch cs(n, ngone);
+    for (int shift = 30; shift >= 0; shift -= 2) {
+        const uint32_t t1 = 1u << shift, t2 = 2u << shift, t3 = 3u << shift;
+        int c1 = 0, c2 = 0, c3 = 0;
+        for (int j = 0; j < nchunk; ++j) {
+            const int i = tid + j * kEvictThreads;
+            const uint32_t x = (i < n ? order_key(u[i]) : 0xffffffffu) ^ cs.prefix;
+            c1 += x < t1;
+            c2 += x < t2;
+            c3 += x < t3;
+        }
+        cs.step<false>(shift, c1, c2, c3, sh);
+    }
+    const uint32_t cut = cs.prefix;
+    const int keep_eq = cs.cand - cs.remaining;
+    int32_t *out = p.evicted_idx + (int64_t)be * p.max_evict;
+    int eq_seen = 0, gone_seen = 0;       // running totals over the chunks already done
+    for (int j = 0; j < nchunk; ++j) {
+        const int i = tid + j * kEvictThreads;
+        const bool valid = i < n;
+        const float ui = valid ? u[i] : 0.0f;
+        const uint32_t key = order_key(ui);
+        const bool is_eq = valid && key == cut, is_less = valid && key < cut;
+        int eq_total, gone_total;
+        const int eq_rank = eq_seen + block_rank_flag(is_eq, sh, cs.turn, &eq_total);
+        const bool gone = is_less || (is_eq && eq_rank >= keep_eq);
+        const int gone_before = gone_seen + block_rank_flag(gone, sh, cs.turn, &gone_total);
+        if (valid) {
+            if (gone) {
+                if (gone_before < p.max_evict) out[gone_before] = i;
+            } else if (p.compact && gone_before > 0) {
+                u[i - gone_before] = ui;  // this chunk's reads ended before the barriers above
+            }
+        }
+        eq_seen += eq_total;
+        gone_seen += gone_total;
+    }
+}
+
+__global__ __launch_bounds__(kEvictThreads) void evict_select(EvictParams p) {
     const int be = blockIdx.x;
     const int b = be / p.E, e = be - b * p.E;
     const int tid = threadIdx.x;
 
-    __shared__ int wave_cnt[2][kSelWaves];
-    __shared__ uint64_t wave_best[kSelWaves];
+    __shared__ SelShared sh;
 
     bool selected = true;
     if (p.sel_idx) {
@@ -178,7 +323,7 @@ __global__ __launch_bounds__(kSelThreads) void evict_select(EvictParams p) {
         // One composite 64-bit value per entry orders both at once.
         uint64_t best = ~0ull;
         const int n4 = (p.S % 4 == 0) ? (n / 4) * 4 : 0;   // float4 reads need aligned rows
-        for (int i = tid * 4; i < n4; i += kSelThreads * 4) {
+        for (int i = tid * 4; i < n4; i += kEvictThreads * 4) {
             const float4 v = *reinterpret_cast<const float4 *>(u + i);
             const uint64_t c0 = evict_composite(v.x, i), c1 = evict_composite(v.y, i + 1);
             const uint64_t c2 = evict_composite(v.z, i + 2), c3 = evict_composite(v.w, i + 3);
@@ -186,7 +331,7 @@ __global__ __launch_bounds__(kSelThreads) void evict_select(EvictParams p) {
             const uint64_t c = a < b2 ? a : b2;
             best = c < best ? c : best;
         }
-        for (int i = n4 + tid; i < n; i += kSelThreads) {
+        for (int i = n4 + tid; i < n; i += kEvictThreads) {
             const uint64_t c = evict_composite(u[i], i);
             best = c < best ? c : best;
         }
@@ -195,12 +340,12 @@ __global__ __launch_bounds__(kSelThreads) void evict_select(EvictParams p) {
             const uint64_t o = __shfl_xor(best, off, kWave);
             best = o < best ? o : best;
         }
-        if ((tid & (kWave - 1)) == 0) wave_best[tid >> 6] = best;
+        if ((tid & (kWave - 1)) == 0) sh.wave_best[tid >> 6] = best;
         __syncthreads();
         if (tid == 0) {
-            uint64_t m = wave_best[0];
+            uint64_t m = sh.wave_best[0];
 #pragma unroll
-            for (int w = 1; w < kSelWaves; ++w) m = wave_best[w] < m ? wave_best[w] : m;
+            for (int w = 1; w < kSelWaves; ++w) m = sh.wave_best[w] < m ? sh.wave_best[w] : m;
             p.evicted_idx[(int64_t)be * p.max_evict] = evict_composite_slot(m);
             p.evicted_cnt[be] = 1;
             p.n_valid[be] = p.capacity;
@@ -208,10 +353,12 @@ __global__ __launch_bounds__(kSelThreads) void evict_select(EvictParams p) {
         return;
     }
 
-    if (n <= kSelCache * kSelThreads)
-        select_many<true>(p, be, u, n, ngone, wave_cnt);
-    else
-        select_many<false>(p, be, u, n, ngone, wave_cnt);
+    // keys held per thread: the next size that covers n; beyond the largest, re-read them
+    const bool vec = p.S % 4 == 0 && (reinterpret_cast<uintptr_t>(p.utility) & 15) == 0;
+    if (!vec || n > kSelCache * kEvictThreads) select_stream(p, be, u, n, ngone, sh);
+    else if (n <= 8 * kEvictThreads) select_cached<8>(p, be, u, n, ngone, sh);
+    else if (n <= 32 * kEvictThreads) select_cached<32>(p, be, u, n, ngone, sh);
+    else select_cached<kSelCache>(p, be, u, n, ngone, sh);
     if (tid == 0) {
         p.evicted_cnt[be] = ngone;
         p.n_valid[be] = p.capacity;
@@ -225,7 +372,7 @@ struct MoveParams {
     const int32_t *evicted_idx;
     const int32_t *evicted_cnt;
     int64_t stride_h_bytes, stride_s_bytes;
-    int row_chunks;      // 16-byte chunks per row, 1..kEvictThreads
+    int row_chunks;      // 16-byte chunks of a row that one block moves, 1..kEvictThreads
     int max_evict;
 };
 
@@ -234,7 +381,10 @@ constexpr int kMoveFlagWords = kEvictThreads * kMoveRows / 32;
 static_assert(kMoveFlagWords == kWave, "one wave ranks the flag words");
 
 __global__ __launch_bounds__(kEvictThreads) void evict_move(MoveParams p) {
+    // blockIdx.z: bit 0 picks K or V, the rest picks the column slice of the row
     const int be = blockIdx.x, hk = blockIdx.y;
+    const bool is_v = blockIdx.z & 1;
+    const int slice = blockIdx.z >> 1;
     const int tid = threadIdx.x;
     const int cnt = p.evicted_cnt[be];
     if (cnt <= 0) return;
@@ -244,8 +394,8 @@ __global__ __launch_bounds__(kEvictThreads) void evict_move(MoveParams p) {
     const int pass_rows = group_rows * kMoveRows;
     const int rsub = tid / p.row_chunks, csub = tid - rsub * p.row_chunks;
     const bool lane_used = rsub < group_rows;
-    char *Kb = static_cast<char *>(p.K[be]) + hk * p.stride_h_bytes + csub * 16;
-    char *Vb = static_cast<char *>(p.V[be]) + hk * p.stride_h_bytes + csub * 16;
+    char *Xb = static_cast<char *>(is_v ? p.V[be] : p.K[be]) + hk * p.stride_h_bytes +
+               (slice * p.row_chunks + csub) * 16;
 
     // One bit per row of the pass: set = the row is evicted.  The list is ascending, so the
     // evicted rows of a pass are the next entries after the `run` ones already passed.
@@ -274,23 +424,21 @@ __global__ __launch_bounds__(kEvictThreads) void evict_move(MoveParams p) {
             if (tid == kWave - 1) flags_before[kMoveFlagWords] = incl;
         }
         __syncthreads();
-        uint4 kv[kMoveRows], vv[kMoveRows];
+        uint4 held[kMoveRows];
         int dst[kMoveRows];
 #pragma unroll
         for (int r = 0; r < kMoveRows; ++r) {
             const int off = r * group_rows + rsub;
             const int row = base + off;
             dst[r] = -1;
-            kv[r] = make_uint4(0, 0, 0, 0);
-            vv[r] = kv[r];
+            held[r] = make_uint4(0, 0, 0, 0);
             if (lane_used && row < n_old) {
                 const int word = off >> 5, pos = off & 31;
                 const uint32_t mine = flags[word];
                 const int before = run + flags_before[word] + __popc(mine & ((1u << pos) - 1u));
                 if (!((mine >> pos) & 1u) && before > 0) {
                     dst[r] = row - before;
-                    kv[r] = *reinterpret_cast<const uint4 *>(Kb + row * p.stride_s_bytes);
-                    vv[r] = *reinterpret_cast<const uint4 *>(Vb + row * p.stride_s_bytes);
+                    held[r] = *reinterpret_cast<const uint4 *>(Xb + row * p.stride_s_bytes);
                 }
             }
         }
@@ -298,10 +446,7 @@ __global__ __launch_bounds__(kEvictThreads) void evict_move(MoveParams p) {
         __syncthreads();                 // every row of the pass is in registers
 #pragma unroll
         for (int r = 0; r < kMoveRows; ++r) {
-            if (dst[r] >= 0) {
-                *reinterpret_cast<uint4 *>(Kb + dst[r] * p.stride_s_bytes) = kv[r];
-                *reinterpret_cast<uint4 *>(Vb + dst[r] * p.stride_s_bytes) = vv[r];
-            }
+            if (dst[r] >= 0) *reinterpret_cast<uint4 *>(Xb + dst[r] * p.stride_s_bytes) = held[r];
         }
         run += passed;
     }
@@ -380,7 +525,7 @@ extern "C" int pikv_evict(const pikv_desc *desc, float *utility, int32_t *n_vali
     p.sel_k = sel_k;
     p.max_evict = max_evict;
     p.compact = compact ? 1 : 0;
-    hipLaunchKernelGGL(evict_select, dim3(desc->B * desc->E), dim3(kSelThreads), 0, st, p);
+    hipLaunchKernelGGL(evict_select, dim3(desc->B * desc->E), dim3(kEvictThreads), 0, st, p);
     int lrc = launch_status();
     if (lrc != PIKV_OK || !compact) return lrc;
     MoveParams m;
@@ -392,10 +537,12 @@ extern "C" int pikv_evict(const pikv_desc *desc, float *utility, int32_t *n_vali
     const int eb = elem_bytes(desc->dtype);
     m.stride_h_bytes = desc->stride_h * eb;
     m.stride_s_bytes = desc->stride_s * eb;
-    m.row_chunks = row_chunks;
+    // K and V move in separate blocks; rows of 256 bytes or more are also cut in two slices
+    const int slices = (row_chunks >= 16 && row_chunks % 2 == 0) ? 2 : 1;
+    m.row_chunks = row_chunks / slices;
     m.max_evict = max_evict;
-    hipLaunchKernelGGL(evict_move, dim3(desc->B * desc->E, desc->Hkv), dim3(kEvictThreads), 0, st,
-                       m);
+    hipLaunchKernelGGL(evict_move, dim3(desc->B * desc->E, desc->Hkv, 2 * slices),
+                       dim3(kEvictThreads), 0, st, m);
     return launch_status();
 }
 

@@ -217,7 +217,8 @@ def run_gpu_evict(g, u, n, capacity, sel=None, max_evict=None, compact=False, ca
     return dc, t2n(eidx), t2n(ecnt)
 
 
-@pytest.mark.parametrize("S,capacity", [(256, 192), (1000, 1), (16, 6), (2048, 2047), (5000, 4096), (300, 0)])
+@pytest.mark.parametrize("S,capacity", [(256, 192), (1000, 1), (16, 6), (2048, 2047), (5000, 4096), (300, 0),
+                                        (3000, 2000), (12000, 9000), (20000, 100), (40000, 30000), (1001, 700), (255, 100)])
 @pytest.mark.parametrize("ties", [False, True], ids=["distinct", "ties"])
 def test_evict_matches_oracle_bit_exact(S, capacity, ties):
     g = wl.Geometry(B=2, Hq=2, Hkv=2, D=16, E=3, S=S, k=2, dtype="bf16")
@@ -266,7 +267,10 @@ def test_evict_special_values_and_selection_list():
     dict(B=1, Hq=4, Hkv=4, D=64, E=4, S=256, k=2, dtype="f32", per_head_routing=True),   # config 1: 256 -> 192
     dict(B=2, Hq=4, Hkv=2, D=128, E=3, S=700, k=2, dtype="bf16"),
     dict(B=1, Hq=2, Hkv=2, D=128, E=2, S=300, k=2, dtype="bf16", rank=32),
-], ids=["c1", "bf16_d128", "rank32"])
+    dict(B=1, Hq=2, Hkv=2, D=128, E=2, S=3000, k=2, dtype="bf16"),       # many passes of the row mover
+    dict(B=1, Hq=2, Hkv=1, D=128, E=2, S=600, k=1, dtype="f32"),         # 512-byte rows
+    dict(B=1, Hq=2, Hkv=2, D=16, E=2, S=2500, k=1, dtype="bf16"),        # 32-byte rows
+], ids=["c1", "bf16_d128", "rank32", "bf16_s3000", "f32_d128", "bf16_d16"])
 def test_evict_with_compaction_moves_rows_like_oracle(spec):
     g = wl.Geometry(**spec)
     case = wl.make_host_case(g, seed=21, n_valid="ragged", utility0="exp")
