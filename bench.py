@@ -55,6 +55,13 @@ def parse_args():
     ap.add_argument("--compress", action="store_true",
                     help="widened row (rank > 0 workloads): compress the new token's full-width K/V "
                          "to codes inside the step (one extra small launch)")
+    ap.add_argument("--k", type=int, default=0,
+                    help="sanity ratio: override the configuration's k (k = E is dense attention)")
+    ap.add_argument("--rank", type=int, default=-1,
+                    help="sanity ratio: override the configuration's code rank (0 = full-width K/V)")
+    ap.add_argument("--histogram", type=int, default=0, metavar="N",
+                    help="route N random queries through layer 0's router and print the empirical "
+                         "expert popularity to stderr")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run a plain 1 GiB device copy 8 times and exit (reference for the "
                          "rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")
@@ -195,6 +202,26 @@ def cpu_baseline(torch, wl, layers, n_steps):
     return dt / max(1, len(prepared)), len(prepared)
 
 
+def expert_histogram(pk, torch, geo, t, n_queries, dev):
+    """Empirical expert popularity of the configuration's router over a stream of random queries."""
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(4242)
+    x = torch.randn((n_queries, geo.d_r), device=dev, generator=gen).to(t["W_r"].dtype)
+    idx = torch.zeros((n_queries, geo.k), device=dev, dtype=torch.int32)
+    gates = torch.zeros((n_queries, geo.k), device=dev)
+    pk.pikv_route(x, t["W_r"], t["bias"], n_queries, geo.d_r, geo.E, geo.k, idx, gates, None)
+    torch.cuda.synchronize()
+    counts = torch.bincount(idx.flatten().long(), minlength=geo.E).cpu().tolist()
+    top1 = torch.bincount(idx[:, 0].long(), minlength=geo.E).cpu().tolist()
+    total = float(sum(counts))
+    order = sorted(range(geo.E), key=lambda e: -counts[e])
+    print("expert popularity over %d random queries (top-%d selections), most popular first:" %
+          (n_queries, geo.k), file=sys.stderr)
+    for r, e in enumerate(order):
+        print("  rank %2d expert %2d: share %.4f (top-1 share %.4f)" %
+              (r + 1, e, counts[e] / total, top1[e] / float(n_queries)), file=sys.stderr)
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -222,6 +249,10 @@ def main():
         print(json.dumps({"calibrate_copy_bytes_read": n, "calibrate_copy_bytes_written": n, "launches": 8}))
         return
     geo = wl.CONFIGS[args.config]
+    if args.k > 0 or args.rank >= 0:
+        import dataclasses
+        geo = dataclasses.replace(geo, k=args.k if args.k > 0 else geo.k,
+                                  rank=args.rank if args.rank >= 0 else geo.rank)
     n_layers = args.layers or DEFAULT_LAYERS[args.config]
     raw = wl.make_device_layers(geo, n_layers, args.seed, dev, **RECIPE[args.config])
     shared = make_shared(pk, torch, geo, dev)
@@ -242,6 +273,8 @@ def main():
                       Wenc_V=(rn(geo.Hkv, geo.rank, geo.D) / geo.D ** 0.5).to(tdt))
     layers = [Layer(pk, torch, geo, t, shared) for t in raw]
     torch.cuda.synchronize()
+    if args.histogram > 0:
+        expert_histogram(pk, torch, geo, raw[0], args.histogram, dev)
 
     stream = torch.cuda.Stream()          # default priority; all library calls go here
     K, W = args.steps, args.warmup
@@ -312,7 +345,8 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if geo.dtype == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": args.config, "B": geo.B, "Hq": geo.Hq, "Hkv": geo.Hkv, "D": geo.D,
-                   "E": geo.E, "S": geo.S, "k": geo.k, "rank": geo.rank, "queries_per_sequence": geo.tq,
+                   "E": geo.E, "S": geo.S, "k": geo.k, "rank": geo.rank,
+                   "overrides": {"k": args.k or None, "rank": args.rank if args.rank >= 0 else None}, "queries_per_sequence": geo.tq,
                    "layers_cycled": n_layers,
                    "launch": args.mode, "api": args.api, "balance": bool(args.balance),
                    "compress_on_insert": bool(args.compress and geo.rank),
