@@ -20,6 +20,8 @@
  *              keep the `capacity` highest-utility entries of a shard.
  *   append   - Algorithm 1, Insert: constant-time write of one new entry per selected
  *              shard into a fixed-capacity buffer (Section 3.1, storage invariants).
+ *   policies - Section 3.4 / Table 3 rows SL, LRU, LRU+: utilities from per-entry
+ *              insertion / last-access stamps and access counts, fed to the same evict.
  *
  * Every sum is a double; inputs (float or bfloat16 bit patterns) are widened exactly;
  * each output is rounded to float once.  No online softmax, no split reductions, no
@@ -28,7 +30,8 @@
  * Pins (tests marked "not gpu"): softmax/sigmoid closed forms, brute-force sorts,
  * k = E routed attention == dense attention computed by an independent numpy routine,
  * constant-V / zero-q special cases, GQA replication, crop-decoder == zero padding,
- * utility mass conservation, brute-force eviction.  Nothing in the paper prints a
+ * utility mass conservation, brute-force eviction, LRU == sort by access stamp, the
+ * sliding-window property, exact small-integer LRU+ values.  Nothing in the paper prints a
  * worked numeric example, so the choice between readings of the paper (which vector is
  * routed, how gates enter, utility granularity, decay form) is pinned by the task
  * statement only; the arithmetic of each reading is pinned as listed.
@@ -438,3 +441,83 @@ int pikv_oracle_compress(int B, int Hkv, int D, int rank, int dtype, const void 
             }
     return 0;
 }
+
+/* ------------------------------------------------------- scheduling policies */
+/* Section 3.4, Table 3: utilities built from integer bookkeeping per entry instead of the
+ * attention mass: r_i = recency = steps since the entry was last accessed, f_i = how often
+ * it has been accessed, and the step it was inserted at.  `now` is the caller's step
+ * counter.  Rows of the table covered here:
+ *   SL    u_i = 1 if the entry was inserted inside the last `window` steps, else 0
+ *         (the indicator of the table with t_i read as the insertion step and the
+ *         threshold tau = now - window);
+ *   LRU   u_i = -r_i;
+ *   LRU+  u_i = -r_i + lambda * f_i, rounded once to float (a fused multiply-add);
+ *   H2O   u_i = the accumulated attention (copied through, so that one call serves all).
+ * protect > 0 shields the entries younger than `protect` steps: their utility is +inf.  */
+
+/* Insert bookkeeping (Algorithm 1 Insert): the entry that pikv_oracle_append is about to
+ * write for each selected shard - into the first freed slot if an eviction freed one,
+ * else at slot n; a full shard is an error, as it is for the append - starts with
+ * birth = last access = now and frequency 0.  Call with n_valid as it is BEFORE the append. */
+int pikv_oracle_policy_stamp(int B, int E, int S, int k, const int32_t *topk_idx,
+                             const int32_t *reuse_idx, const int32_t *reuse_cnt, int max_evict,
+                             const int32_t *n_valid, int now, int32_t *birth,
+                             int32_t *last_access, int32_t *freq) {
+    if (B < 0 || E < 1 || S < 1 || k < 1 || k > E) return -1;
+    for (int b = 0; b < B; ++b) {
+        for (int j = 0; j < k; ++j) {
+            const int e = topk_idx[(int64_t)b * k + j];
+            if (e < 0 || e >= E) return -1;
+            const int64_t be = (int64_t)b * E + e;
+            int slot = n_valid[be];
+            if (reuse_cnt && reuse_cnt[be] > 0) slot = reuse_idx[be * max_evict];
+            if (slot < 0 || slot >= S || n_valid[be] >= S) return -3;
+            birth[be * S + slot] = now;
+            last_access[be * S + slot] = now;
+            freq[be * S + slot] = 0;
+        }
+    }
+    return 0;
+}
+
+/* An entry counts as accessed in a step when the attention mass it received in that
+ * step, a_i = sum over query heads of its probability, exceeds `threshold` (>= 0).      */
+int pikv_oracle_policy_access(int B, int E, int S, const int32_t *n_valid, const float *mass,
+                              float threshold, int now, int32_t *last_access, int32_t *freq) {
+    if (B < 0 || E < 1 || S < 1 || !(threshold >= 0.0f)) return -1;
+    for (int64_t be = 0; be < (int64_t)B * E; ++be) {
+        for (int i = 0; i < n_valid[be]; ++i) {
+            if (mass[be * S + i] > threshold) {
+                last_access[be * S + i] = now;
+                freq[be * S + i] += 1;
+            }
+        }
+    }
+    return 0;
+}
+
+int pikv_oracle_policy_utility(int policy, int B, int E, int S, const int32_t *n_valid, int now,
+                               float lambda, int window, int protect, const int32_t *birth,
+                               const int32_t *last_access, const int32_t *freq,
+                               const float *h2o, float *out) {
+    if (B < 0 || E < 1 || S < 1 || policy < 0 || policy > 3) return -1;
+    if (policy == 0 && !h2o) return -1;
+    for (int64_t be = 0; be < (int64_t)B * E; ++be) {
+        for (int i = 0; i < n_valid[be]; ++i) {
+            const int64_t x = be * S + i;
+            float u;
+            if (policy == 0) {
+                u = h2o[x];
+            } else if (policy == 1) {
+                u = (now - birth[x] < window) ? 1.0f : 0.0f;
+            } else {
+                const float r = (float)(now - last_access[x]);
+                u = (policy == 2) ? -r : fmaf(lambda, (float)freq[x], -r);
+            }
+            if (protect > 0 && now - birth[x] < protect) u = INFINITY;
+            out[x] = u;
+        }
+    }
+    return 0;
+}
+

@@ -40,7 +40,9 @@ def lib():
         # PIKV_ORACLE_LIB lets the mutation test load a deliberately broken build
         _lib = C.CDLL(os.environ.get("PIKV_ORACLE_LIB") or build())
         for name in ("pikv_oracle_route", "pikv_oracle_attend", "pikv_oracle_evict",
-                     "pikv_oracle_append", "pikv_oracle_router_penalty", "pikv_oracle_compress"):
+                     "pikv_oracle_append", "pikv_oracle_router_penalty", "pikv_oracle_compress",
+                     "pikv_oracle_policy_stamp", "pikv_oracle_policy_access",
+                     "pikv_oracle_policy_utility"):
             getattr(_lib, name).restype = C.c_int
     return _lib
 
@@ -228,3 +230,58 @@ def compress(x, W_enc, dtype="f32"):
     if rc:
         raise ValueError("pikv_oracle_compress failed: %d" % rc)
     return codes
+
+
+POLICY_H2O, POLICY_SL, POLICY_LRU, POLICY_LRU_PLUS = 0, 1, 2, 3
+
+
+def policy_stamp(topk_idx, n_valid, now, birth, last_access, freq, reuse_idx=None, reuse_cnt=None):
+    """In place on birth/last_access/freq [B,E,S] int32: bookkeeping of the entry the next append
+    writes (n_valid as it is before that append)."""
+    topk_idx = _chk(topk_idx, np.int32, "topk_idx")
+    n_valid = _chk(n_valid, np.int32, "n_valid")
+    for a, nm in ((birth, "birth"), (last_access, "last_access"), (freq, "freq")):
+        _chk(a, np.int32, nm)
+    reuse_idx = _chk(reuse_idx, np.int32, "reuse_idx")
+    reuse_cnt = _chk(reuse_cnt, np.int32, "reuse_cnt")
+    B, E, S = birth.shape
+    max_evict = 0 if reuse_idx is None else reuse_idx.shape[2]
+    rc = lib().pikv_oracle_policy_stamp(B, E, S, topk_idx.shape[1], _ptr(topk_idx), _ptr(reuse_idx),
+                                        _ptr(reuse_cnt), max_evict, _ptr(n_valid), int(now),
+                                        _ptr(birth), _ptr(last_access), _ptr(freq))
+    if rc:
+        raise ValueError("pikv_oracle_policy_stamp failed: %d" % rc)
+
+
+def policy_access(mass, n_valid, threshold, now, last_access, freq):
+    """In place on last_access/freq: entries whose attention mass of this step (mass [B,E,S] f32)
+    exceeds threshold are accessed at step `now`."""
+    mass = _chk(mass, np.float32, "mass")
+    n_valid = _chk(n_valid, np.int32, "n_valid")
+    _chk(last_access, np.int32, "last_access")
+    _chk(freq, np.int32, "freq")
+    B, E, S = mass.shape
+    rc = lib().pikv_oracle_policy_access(B, E, S, _ptr(n_valid), _ptr(mass), C.c_float(threshold),
+                                         int(now), _ptr(last_access), _ptr(freq))
+    if rc:
+        raise ValueError("pikv_oracle_policy_access failed: %d" % rc)
+
+
+def policy_utility(policy, n_valid, now, birth, last_access, freq, *, lam=0.0, window=0, protect=0,
+                   h2o=None, out=None):
+    """Utility f32 [B,E,S] of a Table 3 policy from the integer bookkeeping (entries >= n untouched)."""
+    n_valid = _chk(n_valid, np.int32, "n_valid")
+    for a, nm in ((birth, "birth"), (last_access, "last_access"), (freq, "freq")):
+        _chk(a, np.int32, nm)
+    h2o = _chk(h2o, np.float32, "h2o")
+    B, E, S = birth.shape
+    if out is None:
+        out = np.zeros((B, E, S), np.float32)
+    _chk(out, np.float32, "out")
+    rc = lib().pikv_oracle_policy_utility(int(policy), B, E, S, _ptr(n_valid), int(now),
+                                          C.c_float(lam), int(window), int(protect), _ptr(birth),
+                                          _ptr(last_access), _ptr(freq), _ptr(h2o), _ptr(out))
+    if rc:
+        raise ValueError("pikv_oracle_policy_utility failed: %d" % rc)
+    return out
+

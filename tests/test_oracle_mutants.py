@@ -45,6 +45,21 @@ MUTANTS = {
                                  "bias[e] = (float)(-coef * (double)miss[e]);"),
     "encoder_transposed": ("load_elem(W_enc, ((int64_t)h * rank + c) * D + d, dtype)",
                            "load_elem(W_enc, (((int64_t)h * D + d) * rank + c) % ((int64_t)Hkv * rank * D), dtype)"),
+    "lru_sign_flipped": ("u = (policy == 2) ? -r : fmaf(lambda, (float)freq[x], -r);",
+                         "u = (policy == 2) ? r : fmaf(lambda, (float)freq[x], -r);"),
+    "lru_plus_rounded_twice": ("fmaf(lambda, (float)freq[x], -r);", "(float)(lambda * (float)freq[x]) - r;"),
+    "lru_plus_frequency_sign": ("fmaf(lambda, (float)freq[x], -r);", "fmaf(-lambda, (float)freq[x], -r);"),
+    "window_off_by_one": ("u = (now - birth[x] < window) ? 1.0f : 0.0f;",
+                          "u = (now - birth[x] <= window) ? 1.0f : 0.0f;"),
+    "protect_compare_reversed": ("if (protect > 0 && now - birth[x] < protect) u = INFINITY;",
+                                 "if (protect > 0 && now - birth[x] > protect) u = INFINITY;"),
+    "access_counts_equal_as_above": ("if (mass[be * S + i] > threshold) {", "if (mass[be * S + i] >= threshold) {"),
+    "access_frequency_not_counted": ("freq[be * S + i] += 1;", ""),
+    "access_touches_dead_slots": ("for (int i = 0; i < n_valid[be]; ++i) {\n            if (mass",
+                                  "for (int i = 0; i < S; ++i) {\n            if (mass"),
+    "stamp_ignores_freed_slot": ("if (reuse_cnt && reuse_cnt[be] > 0) slot = reuse_idx[be * max_evict];\n            if (slot < 0 || slot >= S || n_valid[be] >= S) return -3;\n            birth",
+                                 "if (slot < 0 || slot >= S || n_valid[be] >= S) return -3;\n            birth"),
+    "stamp_keeps_old_frequency": ("freq[be * S + slot] = 0;", ""),
     "empty_shard_counted_in_local_norm": ("if (Z[j] > 0.0) norm += gsel ? (double)gsel[j] : 1.0;",
                                           "norm += gsel ? (double)gsel[j] : 1.0;"),
 }

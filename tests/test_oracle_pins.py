@@ -676,3 +676,151 @@ def test_compress_then_decode_with_orthonormal_rows_recovers_the_subspace():
     crop[0, np.arange(r), np.arange(r)] = 1                          # Table 2 "crop to r"
     x = rng.standard_normal((2, 1, D)).astype(np.float32)
     np.testing.assert_array_equal(orc.compress(x, crop), x[:, :, :r])
+
+
+# ------------------------------------------------------------ scheduling policies (Table 3)
+def _policy_state(B, E, S):
+    return (np.zeros((B, E, S), np.int32), np.zeros((B, E, S), np.int32), np.zeros((B, E, S), np.int32))
+
+
+def test_lru_eviction_drops_the_entries_accessed_longest_ago():
+    """Table 3 row LRU (u = -recency) through the same eviction: the survivors are the `capacity`
+    most recently accessed entries, found here by a plain sort of the access stamps."""
+    rng = np.random.default_rng(5)
+    B, E, S, cap, now = 2, 3, 40, 25, 1000
+    birth, last, freq = _policy_state(B, E, S)
+    last[:] = rng.integers(0, 900, size=(B, E, S))                       # repeated stamps: ties by slot
+    last[0, 0, :] = rng.permutation(S) * 3                               # distinct stamps
+    n = np.full((B, E), S, np.int32)
+    u = orc.policy_utility(orc.POLICY_LRU, n, now, birth, last, freq)
+    np.testing.assert_array_equal(u, -(now - last).astype(np.float32))
+    ridx, rcnt = orc.evict(u.copy(), n.copy(), cap)
+    for b in range(B):
+        for e in range(E):
+            order = sorted(range(S), key=lambda i: (last[b, e, i], -i))   # oldest first, higher slot first
+            assert sorted(order[:S - cap]) == list(ridx[b, e, :rcnt[b, e]])
+
+
+def test_lru_plus_interpolates_between_recency_and_frequency():
+    rng = np.random.default_rng(6)
+    B, E, S, now = 1, 2, 30, 500
+    birth, last, freq = _policy_state(B, E, S)
+    last[:] = rng.integers(0, now, size=(B, E, S))
+    freq[:] = rng.integers(0, 50, size=(B, E, S))
+    n = np.full((B, E), S, np.int32)
+    lru = orc.policy_utility(orc.POLICY_LRU, n, now, birth, last, freq)
+    # lambda = 0: the frequency term vanishes
+    np.testing.assert_array_equal(orc.policy_utility(orc.POLICY_LRU_PLUS, n, now, birth, last, freq, lam=0.0), lru)
+    # exact small-integer arithmetic: -r + 0.5 f is representable
+    u = orc.policy_utility(orc.POLICY_LRU_PLUS, n, now, birth, last, freq, lam=0.5)
+    np.testing.assert_array_equal(u, (-(now - last) + 0.5 * freq).astype(np.float32))
+    # a large lambda orders by frequency first (least-frequently-used goes first)
+    big = orc.policy_utility(orc.POLICY_LRU_PLUS, n, now, birth, last, freq, lam=1.0e4)
+    ridx, rcnt = orc.evict(big.copy(), n.copy(), S - 5)
+    for e in range(E):
+        gone_f = freq[0, e, ridx[0, e, :5]]
+        kept_f = np.delete(freq[0, e], ridx[0, e, :5])
+        assert gone_f.max() <= kept_f.min()
+    # the result is rounded once: a product that needs the fused form
+    lam = np.float32(1.0 + 2.0 ** -12)
+    freq[0, 0, 0], last[0, 0, 0] = 4097, now - 4097
+    u = orc.policy_utility(orc.POLICY_LRU_PLUS, n, now, birth, last, freq, lam=float(lam))
+    exact = float(lam) * 4097.0 - 4097.0                                  # exact in double
+    assert u[0, 0, 0] == np.float32(exact) and u[0, 0, 0] != np.float32(np.float32(lam * np.float32(4097)) - np.float32(4097))
+
+
+def test_sliding_window_policy_keeps_exactly_the_last_window_insertions():
+    """Table 3 row SL: entries inserted one per step; after each insertion the shard is cut back to
+    `window` entries with the indicator utility: what stays is the sliding window of the stream."""
+    B, E, S, window = 1, 1, 12, 5
+    birth, last, freq = _policy_state(B, E, S)
+    n = np.zeros((B, E), np.int32)
+    topk = np.zeros((1, 1), np.int32)
+    reuse_idx = np.zeros((B, E, 1), np.int32)
+    reuse_cnt = np.zeros((B, E), np.int32)
+    for now in range(40):
+        orc.policy_stamp(topk, n, now, birth, last, freq, reuse_idx, reuse_cnt)
+        slot = reuse_idx[0, 0, 0] if reuse_cnt[0, 0] > 0 else n[0, 0]
+        assert birth[0, 0, slot] == now and last[0, 0, slot] == now and freq[0, 0, slot] == 0
+        n[0, 0] += 1                                     # the insert itself (a freed slot is refilled)
+        reuse_cnt[:] = 0
+        u = orc.policy_utility(orc.POLICY_SL, n, now, birth, last, freq, window=window)
+        live = birth[0, 0, :n[0, 0]]
+        np.testing.assert_array_equal(u[0, 0, :n[0, 0]], (now - live < window).astype(np.float32))
+        if n[0, 0] > window:
+            idx, cnt = orc.evict(u.copy(), n, window, max_evict=1)     # n becomes window: one hole
+            assert cnt[0, 0] == 1
+            reuse_idx[0, 0, 0], reuse_cnt[0, 0] = idx[0, 0, 0], 1
+            hole = idx[0, 0, 0]
+            kept = [birth[0, 0, i] for i in range(window + 1) if i != hole]
+            assert sorted(kept) == list(range(now - window + 1, now + 1))
+
+
+def test_protected_recent_entries_are_never_evicted():
+    rng = np.random.default_rng(8)
+    B, E, S, now, protect = 1, 2, 50, 200, 10
+    birth, last, freq = _policy_state(B, E, S)
+    birth[:] = rng.integers(150, now + 1, size=(B, E, S))
+    last[:] = rng.integers(0, 100, size=(B, E, S))                       # young entries look stale to LRU
+    n = np.full((B, E), S, np.int32)
+    u = orc.policy_utility(orc.POLICY_LRU, n, now, birth, last, freq, protect=protect)
+    young = now - birth < protect
+    assert np.isposinf(u[young]).all() and np.isfinite(u[~young]).all()
+    cap = int(young.sum(axis=2).max()) + 3
+    ridx, rcnt = orc.evict(u.copy(), n.copy(), cap)
+    for e in range(E):
+        assert not young[0, e, ridx[0, e, :rcnt[0, e]]].any()
+    # H2O passes the accumulated attention through (same shielding)
+    h2o = rng.random((B, E, S)).astype(np.float32)
+    u0 = orc.policy_utility(orc.POLICY_H2O, n, now, birth, last, freq, h2o=h2o)
+    np.testing.assert_array_equal(u0, h2o)
+
+
+def test_access_bookkeeping_counts_steps_above_the_threshold():
+    rng = np.random.default_rng(9)
+    B, E, S, steps, thr = 2, 2, 16, 25, 0.3
+    birth, last, freq = _policy_state(B, E, S)
+    last[:] = -1
+    n = np.array([[16, 9], [0, 12]], np.int32)
+    masses = rng.random((steps, B, E, S)).astype(np.float32)
+    masses[3, 0, 0, 0] = thr                                             # equal is not above
+    for t in range(steps):
+        before = last.copy()
+        orc.policy_access(masses[t], n, np.float32(thr), t, last, freq)
+        hit = (masses[t] > np.float32(thr)) & (np.arange(S) < n[:, :, None])
+        assert (last[hit] == t).all() and (last[~hit] == before[~hit]).all()
+    live = np.arange(S) < n[:, :, None]
+    above = masses > np.float32(thr)
+    np.testing.assert_array_equal(freq, (above.sum(axis=0) * live).astype(np.int32))
+    last_ref = np.where(above.any(axis=0), steps - 1 - np.argmax(above[::-1], axis=0), -1)
+    np.testing.assert_array_equal(last[live], last_ref[live])
+    assert (last[~live] == -1).all()
+
+
+def test_policy_stamp_marks_the_slot_the_append_writes():
+    """The bookkeeping call and the insert must agree on the slot: the entry whose utility the
+    append resets is the entry stamped."""
+    g = wl.Geometry(B=2, Hq=2, Hkv=2, D=8, E=3, S=6, k=2, dtype="f32")
+    case = wl.make_host_case(g, seed=4, n_valid="ragged", utility0="exp")
+    case.n_valid[:] = np.array([[6, 3, 0], [5, 4, 2]], np.int32)
+    case.utility += 1.0
+    topk = np.array([[0, 1], [1, 2]], np.int32)
+    reuse_idx = np.zeros((g.B, g.E, 1), np.int32)
+    reuse_cnt = np.zeros((g.B, g.E), np.int32)
+    reuse_idx[0, 0, 0], reuse_cnt[0, 0] = 4, 1                         # shard (0,0) is full, slot 4 freed
+    case.n_valid[0, 0] = 5
+    birth, last, freq = _policy_state(g.B, g.E, g.S)
+    birth[:], last[:], freq[:] = -5, -5, 9
+    orc.policy_stamp(topk, case.n_valid, 77, birth, last, freq, reuse_idx, reuse_cnt)
+    K_new, V_new = wl.draw_new_kv(g, seed=1)
+    u = case.utility.copy()
+    orc.append(K_new, V_new, topk, case.K_shards, case.V_shards, u, case.n_valid.copy(), dtype=g.dtype,
+               reuse_idx=reuse_idx, reuse_cnt=reuse_cnt)
+    stamped = birth == 77
+    np.testing.assert_array_equal(stamped, (u == 0) & (case.utility != 0))
+    assert (last[stamped] == 77).all() and (freq[stamped] == 0).all()
+    assert (birth[~stamped] == -5).all() and (freq[~stamped] == 9).all()
+    assert stamped.sum() == 4 and stamped[0, 0, 4] and stamped[0, 1, 3] and stamped[1, 1, 4] and stamped[1, 2, 2]
+    full = np.full((g.B, g.E), g.S, np.int32)
+    with pytest.raises(ValueError):                                     # no room: an error, as for the append
+        orc.policy_stamp(topk, full, 78, birth, last, freq)
