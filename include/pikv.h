@@ -215,6 +215,50 @@ int pikv_router_penalty(int32_t mode, const int32_t *topk_idx, int32_t rows, int
 int pikv_compress(const pikv_desc *desc, const void *K_full, const void *Wenc_K, void *K_codes,
                   const void *V_full, const void *Wenc_V, void *V_codes, void *stream);
 
+/* Section 3.4, Table 3: scheduling policies other than H2O.  Their utilities come from
+ * integer bookkeeping per cache entry, all [B,E,S] int32 device arrays owned by the caller:
+ *   birth        the step the entry was inserted at
+ *   last_access  the step the entry was last accessed at
+ *   freq         how often the entry has been accessed
+ * `now` is the caller's step counter.  An entry is accessed in a step when the attention
+ * mass it received in that step, a_i = sum over the query heads that read it of its
+ * probability, exceeds `threshold` (>= 0).  Slots are stable under pikv_evict with
+ * compact == 0, which is the mode these arrays are meant for (compaction does not move them).
+ *
+ * pikv_policy_stamp: bookkeeping of the entry the next pikv_append writes (Algorithm 1
+ * Insert) - call it BEFORE that pikv_append, with the same topk_idx / reuse_idx / reuse_cnt /
+ * n_valid; the slot rule is the append's (first freed slot, else slot n, nothing if the shard
+ * is full): birth = last_access = now, freq = 0.  UNSUPPORTED for per-head routing.
+ *
+ * pikv_update_utility_tracked: pikv_update_utility plus the access bookkeeping in the same pass
+ * over the scores.  utility may be NULL (bookkeeping only).
+ *
+ * pikv_policy_utility: out[b][e][i] for i < n_valid[b][e] (float32 [B,E,S], other slots untouched):
+ *   PIKV_POLICY_H2O       h2o[b][e][i] (the accumulated attention, copied through)
+ *   PIKV_POLICY_SL        1 if now - birth < window, else 0 (row SL with t_i the insertion step
+ *                         and the threshold tau = now - window)
+ *   PIKV_POLICY_LRU       -(now - last_access)
+ *   PIKV_POLICY_LRU_PLUS  -(now - last_access) + lambda * freq, one fused multiply-add in fp32
+ * protect > 0: entries with now - birth < protect get +inf (never evicted while others remain).
+ * Pass `out` as the utility of pikv_evict.  Arrays a policy does not read may be NULL.
+ * Errors: descriptor errors; INVALID for null required arrays, unknown policy, negative
+ * window / protect / threshold, NaN lambda.                                                   */
+typedef enum {
+    PIKV_POLICY_H2O = 0, PIKV_POLICY_SL = 1, PIKV_POLICY_LRU = 2, PIKV_POLICY_LRU_PLUS = 3
+} pikv_policy;
+int pikv_policy_stamp(const pikv_desc *desc, const int32_t *topk_idx, int32_t k,
+                      const int32_t *reuse_idx, const int32_t *reuse_cnt, int32_t max_evict,
+                      const int32_t *n_valid, int32_t now, int32_t *birth, int32_t *last_access,
+                      int32_t *freq, void *stream);
+int pikv_update_utility_tracked(const pikv_desc *desc, const float *scores, const float *slot_coef,
+                                const int32_t *n_valid, const int32_t *topk_idx, int32_t k,
+                                float decay, float *utility, float threshold, int32_t now,
+                                int32_t *last_access, int32_t *freq, void *stream);
+int pikv_policy_utility(const pikv_desc *desc, int32_t policy, const int32_t *n_valid, int32_t now,
+                        float lambda, int32_t window, int32_t protect, const int32_t *birth,
+                        const int32_t *last_access, const int32_t *freq, const float *h2o,
+                        float *out, void *stream);
+
 /* Tuning hook: force the number of row-range splits per (head group, selected shard) used
  * by pikv_sharded_attn and pikv_attn_workspace_bytes (process-wide; 0 restores the built-in
  * choice of one round of resident blocks).  Change it only between calls, and size the

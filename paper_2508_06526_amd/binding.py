@@ -15,10 +15,12 @@ _LIB_PATH = os.path.join(_HERE, "libpikv.so")
 F32, BF16 = 0, 1
 COMBINE_LSE, COMBINE_LOCAL = 0, 1
 PENALTY_LOAD_BALANCE, PENALTY_CACHE_AWARE = 0, 1
+POLICY_H2O, POLICY_SL, POLICY_LRU, POLICY_LRU_PLUS = 0, 1, 2, 3
 
 EXPORTS = ("pikv_route", "pikv_attn_workspace_bytes", "pikv_sharded_attn", "pikv_update_utility",
            "pikv_evict", "pikv_append", "pikv_strerror", "pikv_version", "pikv_set_attn_split", "pikv_decode_step",
-           "pikv_set_profile_events", "pikv_router_penalty", "pikv_compress")
+           "pikv_set_profile_events", "pikv_router_penalty", "pikv_compress", "pikv_policy_stamp",
+           "pikv_update_utility_tracked", "pikv_policy_utility")
 
 
 class PikvError(RuntimeError):
@@ -65,6 +67,12 @@ def load_library():
     lib.pikv_sharded_attn.restype = C.c_int
     lib.pikv_update_utility.argtypes = [dp, vp, vp, vp, vp, i32, f32, vp, vp]
     lib.pikv_update_utility.restype = C.c_int
+    lib.pikv_policy_stamp.argtypes = [dp, vp, i32, vp, vp, i32, vp, i32, vp, vp, vp, vp]
+    lib.pikv_policy_stamp.restype = C.c_int
+    lib.pikv_update_utility_tracked.argtypes = [dp, vp, vp, vp, vp, i32, f32, vp, f32, i32, vp, vp, vp]
+    lib.pikv_update_utility_tracked.restype = C.c_int
+    lib.pikv_policy_utility.argtypes = [dp, i32, vp, i32, f32, i32, i32, vp, vp, vp, vp, vp, vp]
+    lib.pikv_policy_utility.restype = C.c_int
     lib.pikv_evict.argtypes = [dp, vp, vp, i32, vp, i32, vp, vp, i32, i32, vp, vp, vp]
     lib.pikv_evict.restype = C.c_int
     lib.pikv_append.argtypes = [dp, vp, vp, vp, i32, vp, vp, i32, vp, vp, vp, vp, vp]
@@ -232,3 +240,29 @@ def pikv_compress(desc, K_full, Wenc_K, K_codes, V_full=None, Wenc_V=None, V_cod
     st = load_library().pikv_compress(C.byref(desc), _p(K_full), _p(Wenc_K), _p(K_codes), _p(V_full),
                                       _p(Wenc_V), _p(V_codes), _stream(stream))
     _check(st, "pikv_compress")
+
+
+def pikv_policy_stamp(desc, topk_idx, k, reuse_idx, reuse_cnt, max_evict, n_valid, now, birth,
+                      last_access, freq, stream=None):
+    st = load_library().pikv_policy_stamp(C.byref(desc), _p(topk_idx), k, _p(reuse_idx), _p(reuse_cnt),
+                                          max_evict, _p(n_valid), int(now), _p(birth), _p(last_access),
+                                          _p(freq), _stream(stream))
+    _check(st, "pikv_policy_stamp")
+
+
+def pikv_update_utility_tracked(desc, scores, slot_coef, n_valid, topk_idx, k, decay, utility, threshold,
+                                now, last_access, freq, stream=None):
+    st = load_library().pikv_update_utility_tracked(C.byref(desc), _p(scores), _p(slot_coef), _p(n_valid),
+                                                    _p(topk_idx), k, float(decay), _p(utility),
+                                                    float(threshold), int(now), _p(last_access), _p(freq),
+                                                    _stream(stream))
+    _check(st, "pikv_update_utility_tracked")
+
+
+def pikv_policy_utility(desc, policy, n_valid, now, lam, window, protect, birth, last_access, freq, h2o,
+                        out, stream=None):
+    st = load_library().pikv_policy_utility(C.byref(desc), int(policy), _p(n_valid), int(now), float(lam),
+                                            int(window), int(protect), _p(birth), _p(last_access),
+                                            _p(freq), _p(h2o), _p(out), _stream(stream))
+    _check(st, "pikv_policy_utility")
+

@@ -13,7 +13,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpikv.so")
-SOURCES = ["pikv_api.hip", "pikv_route.hip", "pikv_attn.hip", "pikv_utility.hip", "pikv_evict.hip", "pikv_step.hip", "pikv_aux.hip"]
+SOURCES = ["pikv_api.hip", "pikv_route.hip", "pikv_attn.hip", "pikv_utility.hip", "pikv_evict.hip", "pikv_step.hip", "pikv_aux.hip",
+           "pikv_policy.hip"]
 
 # packed-fp32 instructions are switched off for all device code (the compiler would
 # otherwise form v_pk_*_f32 from ordinary float math)

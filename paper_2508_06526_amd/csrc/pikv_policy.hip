@@ -1,0 +1,146 @@
+// PiKV scheduling policies other than H2O (Section 3.4, Table 3 rows SL, LRU, LRU+): per-entry
+// utilities formed from integer bookkeeping - the step an entry was inserted at, the step
+// it was last accessed at, and how often it has been accessed - and handed to the same
+// eviction (evict_select reads a utility array, whoever wrote it).
+//
+//   policy_stamp   : bookkeeping of the entry the next insert writes (Algorithm 1 Insert):
+//                    birth = last access = now, access count 0.  One block per (sequence,
+//                    selected position), same slot rule as append_rows.
+//   policy_utility : one thread per live entry; reads three ints, writes one float.
+#include "pikv_common.h"
+
+#include <math.h>
+
+namespace pikv {
+namespace {
+
+constexpr int kPolicyThreads = 256;
+
+struct StampParams {
+    const int32_t *topk;
+    const int32_t *reuse_idx;
+    const int32_t *reuse_cnt;
+    const int32_t *n_valid;
+    int32_t *birth;
+    int32_t *last_access;
+    int32_t *freq;
+    int E, S, k, max_evict, now, rows;
+};
+
+__global__ __launch_bounds__(kWave) void policy_stamp(StampParams p) {
+    const int r = blockIdx.x * kWave + threadIdx.x;     // (sequence, selected position)
+    if (r >= p.rows) return;
+    const int b = r / p.k;
+    const int e = p.topk[r];
+    const int64_t be = (int64_t)b * p.E + e;
+    const int n = p.n_valid[be];
+    int slot = n;
+    if (p.reuse_cnt && p.reuse_cnt[be] > 0) slot = p.reuse_idx[be * p.max_evict];
+    if (n >= p.S || slot < 0 || slot >= p.S) return;    // full shard: the insert drops the entry
+    const int64_t at = be * p.S + slot;
+    p.birth[at] = p.now;
+    p.last_access[at] = p.now;
+    p.freq[at] = 0;
+}
+
+struct PolicyParams {
+    const int32_t *n_valid;
+    const int32_t *birth;
+    const int32_t *last_access;
+    const int32_t *freq;
+    const float *h2o;
+    float *out;
+    int S, tiles, policy, now, window, protect;
+    float lambda;
+};
+
+__global__ __launch_bounds__(kPolicyThreads) void policy_utility(PolicyParams p) {
+    const int be = blockIdx.x / p.tiles, tile = blockIdx.x - be * p.tiles;
+    const int i = tile * kPolicyThreads + threadIdx.x;
+    if (i >= p.n_valid[be]) return;
+    const int64_t at = (int64_t)be * p.S + i;
+    float u;
+    if (p.policy == PIKV_POLICY_H2O) {
+        u = p.h2o[at];
+    } else if (p.policy == PIKV_POLICY_SL) {
+        u = (p.now - p.birth[at] < p.window) ? 1.0f : 0.0f;
+    } else {
+        const float r = (float)(p.now - p.last_access[at]);
+        u = (p.policy == PIKV_POLICY_LRU) ? -r : fmaf(p.lambda, (float)p.freq[at], -r);
+    }
+    if (p.protect > 0 && p.now - p.birth[at] < p.protect) u = INFINITY;
+    p.out[at] = u;
+}
+
+}  // namespace
+}  // namespace pikv
+
+using namespace pikv;
+
+extern "C" int pikv_policy_stamp(const pikv_desc *desc, const int32_t *topk_idx, int32_t k,
+                                 const int32_t *reuse_idx, const int32_t *reuse_cnt,
+                                 int32_t max_evict, const int32_t *n_valid, int32_t now,
+                                 int32_t *birth, int32_t *last_access, int32_t *freq,
+                                 void *stream) {
+    const int rc = check_desc(desc);
+    if (rc != PIKV_OK) return rc;
+    if (!topk_idx || !n_valid || !birth || !last_access || !freq) return PIKV_ERR_INVALID;
+    if (k < 1 || k > desc->E) return PIKV_ERR_INVALID;
+    if ((reuse_idx == nullptr) != (reuse_cnt == nullptr)) return PIKV_ERR_INVALID;
+    if (reuse_idx && max_evict < 1) return PIKV_ERR_INVALID;
+    if (desc->route_rows_per_seq != 1) return PIKV_ERR_UNSUPPORTED;   // one insert per sequence
+    if (desc->B == 0) return PIKV_OK;
+    StampParams p;
+    p.topk = topk_idx;
+    p.reuse_idx = reuse_idx;
+    p.reuse_cnt = reuse_cnt;
+    p.n_valid = n_valid;
+    p.birth = birth;
+    p.last_access = last_access;
+    p.freq = freq;
+    p.E = desc->E;
+    p.S = desc->S;
+    p.k = k;
+    p.max_evict = max_evict;
+    p.now = now;
+    p.rows = desc->B * k;
+    hipLaunchKernelGGL(policy_stamp, dim3((p.rows + kWave - 1) / kWave), dim3(kWave), 0,
+                       as_stream(stream), p);
+    return launch_status();
+}
+
+extern "C" int pikv_policy_utility(const pikv_desc *desc, int32_t policy, const int32_t *n_valid,
+                                   int32_t now, float lambda, int32_t window, int32_t protect,
+                                   const int32_t *birth, const int32_t *last_access,
+                                   const int32_t *freq, const float *h2o, float *out,
+                                   void *stream) {
+    const int rc = check_desc(desc);
+    if (rc != PIKV_OK) return rc;
+    if (!n_valid || !out) return PIKV_ERR_INVALID;
+    if (policy < PIKV_POLICY_H2O || policy > PIKV_POLICY_LRU_PLUS) return PIKV_ERR_INVALID;
+    if (policy == PIKV_POLICY_H2O && !h2o) return PIKV_ERR_INVALID;
+    if ((policy == PIKV_POLICY_SL || protect > 0) && !birth) return PIKV_ERR_INVALID;
+    if (policy >= PIKV_POLICY_LRU && !last_access) return PIKV_ERR_INVALID;
+    if (policy == PIKV_POLICY_LRU_PLUS && (!freq || !(lambda == lambda))) return PIKV_ERR_INVALID;
+    if (window < 0 || protect < 0) return PIKV_ERR_INVALID;
+    if (desc->B == 0) return PIKV_OK;
+    PolicyParams p;
+    p.n_valid = n_valid;
+    p.birth = birth;
+    p.last_access = last_access;
+    p.freq = freq;
+    p.h2o = h2o;
+    p.out = out;
+    p.S = desc->S;
+    p.tiles = (desc->S + kPolicyThreads - 1) / kPolicyThreads;
+    p.policy = policy;
+    p.now = now;
+    p.window = window;
+    p.protect = protect;
+    p.lambda = lambda;
+    const int64_t blocks = (int64_t)desc->B * desc->E * p.tiles;
+    if (blocks > 0x7fffffff) return PIKV_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL(policy_utility, dim3((unsigned)blocks), dim3(kPolicyThreads), 0,
+                       as_stream(stream), p);
+    return launch_status();
+}

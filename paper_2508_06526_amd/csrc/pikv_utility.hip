@@ -6,6 +6,10 @@
 // This pass turns them into probabilities and sums them over the heads that read the
 // entry, in fixed head order (no atomics, bit-reproducible).  Grid: (sequence, expert,
 // slot tile); blocks of shards nobody selected exit at once and leave u untouched.
+//
+// The tracked form also keeps the per-entry bookkeeping of Table 3's LRU / LRU+ rows in the
+// same pass: an entry whose attention mass of this step exceeds a threshold has its
+// last-access stamp set to the step counter and its access count raised by one.
 #include "pikv_common.h"
 
 #include <math.h>
@@ -21,11 +25,18 @@ struct UtilParams {
     const float *slot_coef;
     const int32_t *n_valid;
     const int32_t *topk;
-    float *utility;
+    float *utility;      // may be null in the tracked form
     int Hq, E, S, k, rr, tiles;
     float decay;
+    // access bookkeeping (Table 3 rows LRU / LRU+): an entry whose attention mass of this
+    // step exceeds `threshold` is accessed at step `now`
+    int32_t *last_access;
+    int32_t *freq;
+    float threshold;
+    int now;
 };
 
+template <bool TRACK>
 __global__ __launch_bounds__(kUtilThreads) void utility_kernel(UtilParams p) {
     int bid = blockIdx.x;
     const int tile = bid % p.tiles;
@@ -95,8 +106,45 @@ __global__ __launch_bounds__(kUtilThreads) void utility_kernel(UtilParams p) {
             a = fmaf(head_coef[t], __expf(p.scores[(int64_t)head_off[t] * p.S + i] - head_shift[t]), a);
         part[g] = a;
     }
-    float *u = p.utility + ((int64_t)b * p.E + e) * p.S + i;
-    *u = fmaf(p.decay, *u, (part[0] + part[1]) + (part[2] + part[3]));
+    const float mass = (part[0] + part[1]) + (part[2] + part[3]);
+    const int64_t at = ((int64_t)b * p.E + e) * p.S + i;
+    if (!TRACK || p.utility) p.utility[at] = fmaf(p.decay, p.utility[at], mass);
+    if (TRACK && mass > p.threshold) {
+        p.last_access[at] = p.now;
+        p.freq[at] += 1;
+    }
+}
+
+int launch_utility(const pikv_desc *desc, const float *scores, const float *slot_coef,
+                   const int32_t *n_valid, const int32_t *topk_idx, int32_t k, float decay,
+                   float *utility, bool track, float threshold, int32_t now,
+                   int32_t *last_access, int32_t *freq, void *stream) {
+    UtilParams p;
+    p.scores = scores;
+    p.slot_coef = slot_coef;
+    p.n_valid = n_valid;
+    p.topk = topk_idx;
+    p.utility = utility;
+    p.Hq = desc->Hq;
+    p.E = desc->E;
+    p.S = desc->S;
+    p.k = k;
+    p.rr = desc->route_rows_per_seq;
+    p.tiles = (desc->S + kUtilTile - 1) / kUtilTile;
+    p.decay = decay;
+    p.last_access = last_access;
+    p.freq = freq;
+    p.threshold = threshold;
+    p.now = now;
+    const int64_t blocks = (int64_t)desc->B * desc->E * p.tiles;
+    if (blocks > 0x7fffffff) return PIKV_ERR_UNSUPPORTED;
+    if (track)
+        hipLaunchKernelGGL(utility_kernel<true>, dim3((unsigned)blocks), dim3(kUtilThreads), 0,
+                           as_stream(stream), p);
+    else
+        hipLaunchKernelGGL(utility_kernel<false>, dim3((unsigned)blocks), dim3(kUtilThreads), 0,
+                           as_stream(stream), p);
+    return launch_status();
 }
 
 }  // namespace
@@ -114,22 +162,23 @@ extern "C" int pikv_update_utility(const pikv_desc *desc, const float *scores,
     if (k < 1 || k > desc->E) return PIKV_ERR_INVALID;
     if (!(decay >= 0.0f) || decay > 3.0e38f) return PIKV_ERR_INVALID;
     if (desc->B == 0) return PIKV_OK;
-    UtilParams p;
-    p.scores = scores;
-    p.slot_coef = slot_coef;
-    p.n_valid = n_valid;
-    p.topk = topk_idx;
-    p.utility = utility;
-    p.Hq = desc->Hq;
-    p.E = desc->E;
-    p.S = desc->S;
-    p.k = k;
-    p.rr = desc->route_rows_per_seq;
-    p.tiles = (desc->S + kUtilTile - 1) / kUtilTile;
-    p.decay = decay;
-    const int64_t blocks = (int64_t)desc->B * desc->E * p.tiles;
-    if (blocks > 0x7fffffff) return PIKV_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL(utility_kernel, dim3((unsigned)blocks), dim3(kUtilThreads), 0,
-                       as_stream(stream), p);
-    return launch_status();
+    return launch_utility(desc, scores, slot_coef, n_valid, topk_idx, k, decay, utility, false, 0.0f,
+                          0, nullptr, nullptr, stream);
+}
+
+extern "C" int pikv_update_utility_tracked(const pikv_desc *desc, const float *scores,
+                                           const float *slot_coef, const int32_t *n_valid,
+                                           const int32_t *topk_idx, int32_t k, float decay,
+                                           float *utility, float threshold, int32_t now,
+                                           int32_t *last_access, int32_t *freq, void *stream) {
+    const int rc = check_desc(desc);
+    if (rc != PIKV_OK) return rc;
+    if (!scores || !slot_coef || !n_valid || !topk_idx || !last_access || !freq)
+        return PIKV_ERR_INVALID;
+    if (k < 1 || k > desc->E) return PIKV_ERR_INVALID;
+    if (utility && (!(decay >= 0.0f) || decay > 3.0e38f)) return PIKV_ERR_INVALID;
+    if (!(threshold >= 0.0f)) return PIKV_ERR_INVALID;
+    if (desc->B == 0) return PIKV_OK;
+    return launch_utility(desc, scores, slot_coef, n_valid, topk_idx, k, decay, utility, true,
+                          threshold, now, last_access, freq, stream);
 }
