@@ -594,7 +594,7 @@ __global__ __launch_bounds__(kWavesPerBlock *kWave, 3) void attn_partial_gqa128(
 
 template <typename T, int THREADS>
 __global__ __launch_bounds__(THREADS) void attn_combine(CombineParams p) {
-    __shared__ __attribute__((aligned(16))) unsigned char smem[combine_smem_bytes<THREADS>()];
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];   // combine_smem_bytes()
     combine_head<T, THREADS>(p, blockIdx.x, smem);
 }
 
@@ -792,12 +792,15 @@ int pikv_sharded_attn_merge(const pikv_desc *desc, const CombineParams *c, void 
     const dim3 cgrid(desc->B * desc->Hq);
     hipStream_t st = as_stream(stream);
     const bool f32 = desc->dtype == PIKV_F32;
-    if (combine_threads(c->k * c->nsplit) == 256) {
-        if (f32) hipLaunchKernelGGL((attn_combine<float, 256>), cgrid, dim3(256), 0, st, *c);
-        else hipLaunchKernelGGL((attn_combine<bf16, 256>), cgrid, dim3(256), 0, st, *c);
+    const int np = c->k * c->nsplit;
+    if (combine_threads(np) == 256) {
+        const size_t lds = combine_smem_bytes(256, np);
+        if (f32) hipLaunchKernelGGL((attn_combine<float, 256>), cgrid, dim3(256), lds, st, *c);
+        else hipLaunchKernelGGL((attn_combine<bf16, 256>), cgrid, dim3(256), lds, st, *c);
     } else {
-        if (f32) hipLaunchKernelGGL((attn_combine<float, 1024>), cgrid, dim3(1024), 0, st, *c);
-        else hipLaunchKernelGGL((attn_combine<bf16, 1024>), cgrid, dim3(1024), 0, st, *c);
+        const size_t lds = combine_smem_bytes(1024, np);
+        if (f32) hipLaunchKernelGGL((attn_combine<float, 1024>), cgrid, dim3(1024), lds, st, *c);
+        else hipLaunchKernelGGL((attn_combine<bf16, 1024>), cgrid, dim3(1024), lds, st, *c);
     }
     return launch_status();
 }

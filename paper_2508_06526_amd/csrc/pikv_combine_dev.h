@@ -95,10 +95,12 @@ __device__ __forceinline__ void head_weights(int k, const float *Mj, const float
 //   phase 2: one thread forms the k gate-weighted shard weights in either combine mode.
 //   phase 3: weighted sum of the accumulators, slices reduced through LDS in fixed order,
 //            then (rank > 0) the value decoder y = ycode U_V[h'].
-// Bytes of LDS combine_head<., THREADS> carves from the buffer it is given.
-template <int THREADS>
-constexpr int combine_smem_bytes() {
-    return (2 * kMaxPartialsPerHead + 6 * 64 + 128) * 4 + THREADS * 16;
+// Bytes of LDS combine_head<., threads> carves from the buffer it is given (np = k * nsplit
+// partials per head).  Sized by the real np, not by its maximum: the blocks are short and
+// many, and the LDS they reserve decides how many of them a CU holds at once.
+inline __host__ __device__ int combine_np_pad(int np) { return (np + 3) & ~3; }
+inline size_t combine_smem_bytes(int threads, int np) {
+    return (size_t)(2 * combine_np_pad(np) + 6 * 64 + 128) * 4 + (size_t)threads * 16;
 }
 
 // Block size of the merge: one query head rarely has more than a few dozen partials; a small
@@ -115,8 +117,8 @@ __device__ __forceinline__ void combine_head(const CombineParams &p, int bh, uns
 
     float4 *red = reinterpret_cast<float4 *>(smem);                  // [THREADS]
     float *wt = reinterpret_cast<float *>(smem + THREADS * 16);     // max of every partial, later its weight
-    float *ls = wt + kMaxPartialsPerHead;
-    float *Mj = ls + kMaxPartialsPerHead, *Zj = Mj + 64, *shard_w = Zj + 64;
+    float *ls = wt + combine_np_pad(np);
+    float *Mj = ls + combine_np_pad(np), *Zj = Mj + 64, *shard_w = Zj + 64;
     float *sh_shift = shard_w + 64, *sh_coef = sh_shift + 64, *g_s = sh_coef + 64;
     float *ycode = g_s + 64;                                         // [128]
 

@@ -143,6 +143,7 @@ __global__ __launch_bounds__(kRouteThreads) void step_pre(PreParams p) {
 // score loads are already in flight.
 constexpr int kPostMaxShards = 2048;   // Hq * k
 constexpr int kPostPrefetchHeads = 8;  // score loads each thread issues before the statistics
+constexpr int kPostMaxTiles = 8;       // slot tiles one utility block walks through
 
 struct PostParams {
     CombineParams c;
@@ -150,23 +151,30 @@ struct PostParams {
     const int32_t *n_valid;
     const int32_t *topk;
     float *utility;
-    int B, E, S, tiles;
+    int B, E, S;
+    int tiles;            // utility blocks per selected shard
+    int tiles_per_block;  // consecutive slot tiles each of them covers
     float decay;
 };
 
-template <int THREADS>
-constexpr int post_smem_bytes() {
-    constexpr int util = (4 * kPostMaxShards + 64 + THREADS) * 4;
-    return util > combine_smem_bytes<THREADS>() ? util : combine_smem_bytes<THREADS>();
+// LDS of a utility block: statistics of the Hq * k (head, shard) pairs, the gates, and two
+// buffers of per-(head group, slot) sums used in turn.
+inline __host__ __device__ int post_pairs_pad(int pairs) { return (pairs + 3) & ~3; }
+inline size_t post_smem_bytes(int threads, int np, int pairs) {
+    const size_t util = (size_t)(4 * post_pairs_pad(pairs) + 64 + 2 * threads) * 4;
+    const size_t comb = combine_smem_bytes(threads, np);
+    return util > comb ? util : comb;
 }
 
-// Blocks [0, B*Hq) merge one query head each; the others update the utilities of THREADS/4
-// slots of the j-th selected shard of a sequence.  THREADS is the merge's block size
-// (combine_threads), so that the merge is bit-identical to the stand-alone kernel.
-template <typename T, int THREADS>
+// Blocks [0, B*Hq) merge one query head each; the others update the utilities of
+// tiles_per_block tiles of THREADS/4 slots of the j-th selected shard of a sequence.  THREADS
+// is the merge's block size (combine_threads), so that the merge is bit-identical to the
+// stand-alone kernel.
+template <typename T, int THREADS, bool MULTI>
 __global__ __launch_bounds__(THREADS) void step_post(PostParams p) {
     constexpr int kSlots = THREADS / 4;
-    __shared__ __attribute__((aligned(16))) unsigned char smem[post_smem_bytes<THREADS>()];
+    const int ntiles = MULTI ? p.tiles_per_block : 1;   // MULTI = false: straight-line code
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];   // post_smem_bytes()
     const int ncomb = p.B * p.c.Hq;
     if ((int)blockIdx.x < ncomb) {
         combine_head<T, THREADS>(p.c, blockIdx.x, smem);
@@ -182,13 +190,14 @@ __global__ __launch_bounds__(THREADS) void step_post(PostParams p) {
     const int tid = threadIdx.x;
     const int e = p.topk[(int64_t)b * k + j];
     const int n = p.n_valid[(int64_t)b * p.E + e];
-    const int i0 = tile * kSlots;
+    const int i0 = tile * kSlots * ntiles;
     if (i0 >= n) return;
 
-    float *Mj_s = reinterpret_cast<float *>(smem), *Zj_s = Mj_s + kPostMaxShards;
-    float *shift_s = Zj_s + kPostMaxShards, *coef_s = shift_s + kPostMaxShards;
-    float *g_s = coef_s + kPostMaxShards;      // [64]
-    float *part_s = g_s + 64;                  // [4][kSlots]
+    const int pairs = post_pairs_pad(Hq * k);
+    float *Mj_s = reinterpret_cast<float *>(smem), *Zj_s = Mj_s + pairs;
+    float *shift_s = Zj_s + pairs, *coef_s = shift_s + pairs;
+    float *g_s = coef_s + pairs;               // [64]
+    float *part_s = g_s + 64;                  // [2][4][kSlots]
 
     // thread = (slot, head group); the heads are cut into 4 consecutive groups, each summed in
     // ascending order, the groups joined as (g0 + g1) + (g2 + g3) - the order the stand-alone
@@ -196,16 +205,18 @@ __global__ __launch_bounds__(THREADS) void step_post(PostParams p) {
     const int slot = tid & (kSlots - 1), hg = tid / kSlots;
     const int gsize = (Hq + 3) / 4;
     const int h_lo = hg * gsize, h_hi = min(Hq, h_lo + gsize);
-    const int i = i0 + slot;
-    const bool live = i < n;
     float sc[kPostPrefetchHeads];
+    auto fetch = [&](int i) {
 #pragma unroll
-    for (int t = 0; t < kPostPrefetchHeads; ++t) {
-        const int h = h_lo + t;
-        sc[t] = (h < h_hi && live) ? p.scores[(((int64_t)b * Hq + h) * k + j) * p.S + i] : 0.0f;
-    }
-    float *uptr = p.utility + ((int64_t)b * p.E + e) * p.S + i;
-    const float u_old = (live && hg == 0) ? *uptr : 0.0f;
+        for (int t = 0; t < kPostPrefetchHeads; ++t) {
+            const int h = h_lo + t;
+            sc[t] = (h < h_hi && i < n) ? p.scores[(((int64_t)b * Hq + h) * k + j) * p.S + i] : 0.0f;
+        }
+    };
+    float *urow = p.utility + ((int64_t)b * p.E + e) * p.S;
+    int i = i0 + slot;
+    fetch(i);
+    float u_old = (i < n && hg == 0) ? urow[i] : 0.0f;
     if (p.c.gates != nullptr && tid < k) g_s[tid] = p.c.gates[(int64_t)b * k + tid];
 
     // softmax statistics of every (head, selected shard): 8 lanes each, pairs read from L2
@@ -229,23 +240,35 @@ __global__ __launch_bounds__(THREADS) void step_post(PostParams p) {
                      shift_s + h * k, coef_s + h * k, &M, &norm);
     }
     __syncthreads();
-    float a = 0.0f;
-    if (live) {
+    for (int it = 0; it < ntiles; ++it) {
+        const bool live = i < n;
+        float a = 0.0f;
+        if (live) {
 #pragma unroll
-        for (int t = 0; t < kPostPrefetchHeads; ++t) {
-            const int h = h_lo + t;
-            if (h < h_hi) a = fmaf(coef_s[h * k + j], __expf(sc[t] - shift_s[h * k + j]), a);
+            for (int t = 0; t < kPostPrefetchHeads; ++t) {
+                const int h = h_lo + t;
+                if (h < h_hi) a = fmaf(coef_s[h * k + j], __expf(sc[t] - shift_s[h * k + j]), a);
+            }
+            for (int h = h_lo + kPostPrefetchHeads; h < h_hi; ++h)
+                a = fmaf(coef_s[h * k + j],
+                         __expf(p.scores[(((int64_t)b * Hq + h) * k + j) * p.S + i] - shift_s[h * k + j]), a);
         }
-        for (int h = h_lo + kPostPrefetchHeads; h < h_hi; ++h)
-            a = fmaf(coef_s[h * k + j],
-                     __expf(p.scores[(((int64_t)b * Hq + h) * k + j) * p.S + i] - shift_s[h * k + j]), a);
-    }
-    part_s[hg * kSlots + slot] = a;
-    __syncthreads();
-    if (hg == 0 && live) {
-        const float total = (part_s[slot] + part_s[kSlots + slot]) +
-                            (part_s[2 * kSlots + slot] + part_s[3 * kSlots + slot]);
-        *uptr = fmaf(p.decay, u_old, total);
+        // the next tile's loads go out before this tile's sums meet in LDS
+        const int i_next = i + kSlots;
+        const float u_cur = u_old;
+        if (it + 1 < ntiles) {
+            fetch(i_next);
+            u_old = (i_next < n && hg == 0) ? urow[i_next] : 0.0f;
+        }
+        float *part = part_s + (it & 1) * 4 * kSlots;    // rewritten two tiles later, after a barrier
+        part[hg * kSlots + slot] = a;
+        __syncthreads();
+        if (hg == 0 && live) {
+            const float total = (part[slot] + part[kSlots + slot]) +
+                                (part[2 * kSlots + slot] + part[3 * kSlots + slot]);
+            urow[i] = fmaf(p.decay, u_cur, total);
+        }
+        i = i_next;
     }
 }
 
@@ -333,19 +356,37 @@ extern "C" int pikv_decode_step(const pikv_desc *desc, const void *q, const void
     pp.B = desc->B;
     pp.E = desc->E;
     pp.S = desc->S;
-    const int threads = combine_threads(k * plan.nsplit);
-    pp.tiles = (desc->S + threads / 4 - 1) / (threads / 4);
+    const int np = k * plan.nsplit;
+    const int threads = combine_threads(np);
+    // Utility blocks: enough of them to fill the GPU once (256 CUs x the blocks a CU holds),
+    // each walking through several slot tiles rather than a new block per tile - the
+    // statistics of the sequence's (head, shard) pairs are then computed once per block.
+    const int64_t slot_tiles = (desc->S + threads / 4 - 1) / (threads / 4);
+    const int64_t want_blocks = threads == 256 ? 1024 : 256;
+    int64_t tpb = ((int64_t)desc->B * k * slot_tiles + want_blocks - 1) / want_blocks;
+    if (tpb < 1) tpb = 1;
+    if (tpb > kPostMaxTiles) tpb = kPostMaxTiles;
+    pp.tiles_per_block = (int)tpb;
+    pp.tiles = (int)((slot_tiles + tpb - 1) / tpb);
     pp.decay = decay;
     const int64_t blocks = (int64_t)desc->B * desc->Hq + (int64_t)desc->B * k * pp.tiles;
     if (blocks > 0x7fffffff) return PIKV_ERR_UNSUPPORTED;
     const dim3 grid((unsigned)blocks);
     const bool f32 = desc->dtype == PIKV_F32;
+    const size_t lds = post_smem_bytes(threads, np, desc->Hq * k);
+    const bool multi = tpb > 1;
+#define PIKV_LAUNCH_POST(T, TH)                                                                  \
+    do {                                                                                         \
+        if (multi) hipLaunchKernelGGL((step_post<T, TH, true>), grid, dim3(TH), lds, st, pp);    \
+        else hipLaunchKernelGGL((step_post<T, TH, false>), grid, dim3(TH), lds, st, pp);         \
+    } while (0)
     if (threads == 256) {
-        if (f32) hipLaunchKernelGGL((step_post<float, 256>), grid, dim3(256), 0, st, pp);
-        else hipLaunchKernelGGL((step_post<bf16, 256>), grid, dim3(256), 0, st, pp);
+        if (f32) PIKV_LAUNCH_POST(float, 256);
+        else PIKV_LAUNCH_POST(bf16, 256);
     } else {
-        if (f32) hipLaunchKernelGGL((step_post<float, 1024>), grid, dim3(1024), 0, st, pp);
-        else hipLaunchKernelGGL((step_post<bf16, 1024>), grid, dim3(1024), 0, st, pp);
+        if (f32) PIKV_LAUNCH_POST(float, 1024);
+        else PIKV_LAUNCH_POST(bf16, 1024);
     }
+#undef PIKV_LAUNCH_POST
     return launch_status();
 }
