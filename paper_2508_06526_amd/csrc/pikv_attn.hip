@@ -39,8 +39,13 @@ struct AttnParams {
     int B, Hq, G, D, E, S, k, rr, rank;
     int64_t stride_h, stride_s;
     int nsplit, chunk;
+    int stage_scores;   // plain-ALU kernel: keep the block's scores in LDS, write them at the end
+    int stream_scores;  // ... with non-temporal stores
     float scale;
 };
+
+// Raw scores of at most this many bytes per block are staged in LDS (plain-ALU kernel).
+constexpr int kScoreStageBytes = 16384;
 
 // Resolve the j-th selected shard of a routing row with ONE round trip to memory: the
 // expert id is fetched while lanes 0..E-1 fetch the entry count and the K/V base address of
@@ -105,6 +110,10 @@ __global__ __launch_bounds__(kWavesPerBlock *kWave) void attn_partial(AttnParams
     __shared__ float sm_acc[kWavesPerBlock][GB][W];
     __shared__ float sm_m[kWavesPerBlock][GB];
     __shared__ float sm_l[kWavesPerBlock][GB];
+    // Raw scores of the block's rows, [GB][chunk], when p.stage_scores: scattered 128-byte
+    // score writes in the middle of the K/V stream cost far more HBM time than their bytes
+    // (each one turns a channel around); one contiguous burst per block at the end does not.
+    extern __shared__ __attribute__((aligned(16))) float score_stage[];
 
     const int64_t part_base = (((int64_t)b * p.Hq + h0) * p.k + j) * p.nsplit + split;
     const int64_t part_head_stride = (int64_t)p.k * p.nsplit;
@@ -221,7 +230,10 @@ __global__ __launch_bounds__(kWavesPerBlock *kWave) void attn_partial(AttnParams
 #pragma unroll
                     for (int t = 1; t < LPR && u + t < NL; ++t) v = (c == t) ? s[u + t][g] : v;
                     const int row = t0 + (u + c) * RPL + r;
-                    if (u + c < NL && row < r1) dst[row] = v;
+                    if (u + c < NL && row < r1) {
+                        if (p.stage_scores) score_stage[g * p.chunk + row - r0] = v;
+                        else dst[row] = v;
+                    }
                 }
             }
         }
@@ -284,6 +296,32 @@ __global__ __launch_bounds__(kWavesPerBlock *kWave) void attn_partial(AttnParams
         }
     }
     __syncthreads();
+
+    if (p.scores != nullptr && p.stage_scores) {   // the block's scores, one contiguous burst
+        const int rows = r1 - r0;
+#pragma unroll
+        for (int g = 0; g < GB; ++g) {
+            float *dst = p.scores + (((int64_t)b * p.Hq + h0 + g) * p.k + j) * p.S + r0;
+            const float *src = score_stage + g * p.chunk;
+            if ((p.S & 3) == 0 && (reinterpret_cast<uintptr_t>(p.scores) & 15) == 0) {   // r0, chunk: multiples of the tile
+                const int rows4 = rows & ~3;
+                // Bursts that land while later blocks still stream K/V (more than one round
+                // of blocks) go out non-temporally: a dirty line parked in L2 is evicted on
+                // its own later and interrupts a read stream each time.  With a single round
+                // all bursts come at the very end and ordinary stores are cheaper.
+                if (p.stream_scores) {
+                    for (int i = tid * 4; i < rows4; i += blockDim.x * 4)
+                        store16_stream(dst + i, *reinterpret_cast<const uint4 *>(src + i));
+                } else {
+                    for (int i = tid * 4; i < rows4; i += blockDim.x * 4)
+                        *reinterpret_cast<float4 *>(dst + i) = *reinterpret_cast<const float4 *>(src + i);
+                }
+                if (tid < rows - rows4) dst[rows4 + tid] = src[rows4 + tid];
+            } else {
+                for (int i = tid; i < rows; i += blockDim.x) dst[i] = src[i];
+            }
+        }
+    }
 
     // ... then the waves of the block, and write the block's partial.
     for (int idx = tid; idx < GB * W; idx += blockDim.x) {
@@ -601,11 +639,12 @@ __global__ __launch_bounds__(THREADS) void attn_combine(CombineParams p) {
 template <typename T, int W>
 int launch_partial_w(int gb, const AttnParams &p, int blocks, hipStream_t st) {
     const dim3 grid(blocks), block(kWavesPerBlock * kWave);
+    const size_t lds = p.stage_scores ? (size_t)gb * p.chunk * sizeof(float) : 0;
     switch (gb) {
-        case 1: hipLaunchKernelGGL((attn_partial<T, W, 1>), grid, block, 0, st, p); break;
-        case 2: hipLaunchKernelGGL((attn_partial<T, W, 2>), grid, block, 0, st, p); break;
-        case 4: hipLaunchKernelGGL((attn_partial<T, W, 4>), grid, block, 0, st, p); break;
-        case 8: hipLaunchKernelGGL((attn_partial<T, W, 8>), grid, block, 0, st, p); break;
+        case 1: hipLaunchKernelGGL((attn_partial<T, W, 1>), grid, block, lds, st, p); break;
+        case 2: hipLaunchKernelGGL((attn_partial<T, W, 2>), grid, block, lds, st, p); break;
+        case 4: hipLaunchKernelGGL((attn_partial<T, W, 4>), grid, block, lds, st, p); break;
+        case 8: hipLaunchKernelGGL((attn_partial<T, W, 8>), grid, block, lds, st, p); break;
         default: return PIKV_ERR_UNSUPPORTED;
     }
     return launch_status();
@@ -664,6 +703,7 @@ int make_attn_plan(const pikv_desc *d, int k, AttnPlan *plan) {
     plan->tile_rows = tile;
     plan->chunk = chunk;
     plan->nsplit = (int)nsplit;
+    plan->resident_blocks = (int)target_blocks;
     plan->acc_floats = (size_t)d->B * d->Hq * k * nsplit * W;
     plan->ml_floats = (size_t)d->B * d->Hq * k * nsplit * 2;
     return PIKV_OK;
@@ -744,10 +784,13 @@ int launch_attn_partial(const pikv_desc *desc, const void *q, const void *const 
     p.stride_s = desc->stride_s;
     p.nsplit = plan.nsplit;
     p.chunk = plan.chunk;
+    p.stage_scores = scores != nullptr && !plan.gqa_mfma &&
+                     (size_t)plan.heads_per_block * plan.chunk * sizeof(float) <= kScoreStageBytes;
     p.scale = scale > 0.0f ? scale : 1.0f / sqrtf((float)desc->D);
 
     const int64_t blocks64 = (int64_t)desc->B * plan.head_blocks * k * plan.nsplit;
     if (blocks64 > 0x7fffffff) return PIKV_ERR_UNSUPPORTED;
+    p.stream_scores = blocks64 > plan.resident_blocks;
     hipStream_t st = as_stream(stream);
     int lrc;
     if (g_prof_start) (void)hipEventRecord(g_prof_start, st);

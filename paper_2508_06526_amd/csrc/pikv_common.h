@@ -112,6 +112,13 @@ __device__ __forceinline__ uint4 load16_stream(const void *p) {
     const u32x4_t v = __builtin_nontemporal_load((global_u32x4_ptr)(uintptr_t)p);
     return make_uint4(v.x, v.y, v.z, v.w);
 }
+// 16-byte store of data nobody reads back soon (written once, consumed by a later kernel):
+// the non-temporal hint sends it on its way instead of parking a dirty line in L2.
+typedef u32x4_t __attribute__((address_space(1))) *global_u32x4_wptr;
+__device__ __forceinline__ void store16_stream(void *p, uint4 v) {
+    const u32x4_t x = {v.x, v.y, v.z, v.w};
+    __builtin_nontemporal_store(x, (global_u32x4_wptr)(uintptr_t)p);
+}
 
 // fp32 -> uint32 whose unsigned order is the float order (-0 folded onto +0).
 __device__ __forceinline__ uint32_t order_key(float u) {
@@ -146,6 +153,7 @@ struct AttnPlan {
     int tile_rows;        // rows one wave consumes per iteration
     int chunk;            // rows per split (multiple of tile_rows)
     int nsplit;
+    int resident_blocks;  // blocks of the split pass the GPU holds at once
     size_t acc_floats;    // B*Hq*k*nsplit*width
     size_t ml_floats;     // B*Hq*k*nsplit*2
 };
