@@ -2,6 +2,8 @@
 // step kernel (PiKV Section 3.2, Table 1 "TopK softmax").
 #pragma once
 
+#include <type_traits>
+
 #include "pikv_common.h"
 
 #include <math.h>
@@ -65,15 +67,29 @@ __device__ __forceinline__ void route_logits_vec(const T *xr, const T *W_r, cons
     float acc[EPL];
 #pragma unroll
     for (int i = 0; i < EPL; ++i) acc[i] = 0.0f;
-#pragma unroll 4
-    for (int c = tid; c < total; c += kRouteThreads) {
-        const uint4 w = load16(W_r + (int64_t)c * EPL);
-        const float xj = load_scalar<T>(xr, c >> cshift);
-        float wf[EPL];
-        Pack16<T>::widen(w, wf);
+    // batches of 8, then 4, then single chunks: all loads of a batch are in flight together,
+    // the multiply-adds stay in ascending chunk order whatever the batching
+    auto batch = [&](int c, auto nload) {
+        constexpr int NB = decltype(nload)::value;
+        uint4 w[NB];
+        float xj[NB];
 #pragma unroll
-        for (int i = 0; i < EPL; ++i) acc[i] = fmaf(xj, wf[i], acc[i]);
-    }
+        for (int u = 0; u < NB; ++u) {
+            w[u] = load16(W_r + (int64_t)(c + u * kRouteThreads) * EPL);
+            xj[u] = load_scalar<T>(xr, (c + u * kRouteThreads) >> cshift);
+        }
+#pragma unroll
+        for (int u = 0; u < NB; ++u) {
+            float wf[EPL];
+            Pack16<T>::widen(w[u], wf);
+#pragma unroll
+            for (int i = 0; i < EPL; ++i) acc[i] = fmaf(xj[u], wf[i], acc[i]);
+        }
+    };
+    int c = tid;
+    for (; c + 7 * kRouteThreads < total; c += 8 * kRouteThreads) batch(c, std::integral_constant<int, 8>{});
+    for (; c + 3 * kRouteThreads < total; c += 4 * kRouteThreads) batch(c, std::integral_constant<int, 4>{});
+    for (; c < total; c += kRouteThreads) batch(c, std::integral_constant<int, 1>{});
     for (int off = cpr; off < kWave; off <<= 1) {
 #pragma unroll
         for (int i = 0; i < EPL; ++i) acc[i] += __shfl_xor(acc[i], off, kWave);
