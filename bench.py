@@ -33,6 +33,8 @@ HBM_PEAK_GBS = 8000.0
 MEASURED_TRAFFIC = {
     "c3_long_context": {"bytes_per_launch": int((128.21 + 5.59) * 2 ** 20),
                         "source": "profiles/c3_long_context_hbm_traffic_pmc.txt"},
+    "c2_bf16_decode": {"bytes_per_launch": int((1024.39 + 8.53) * 2 ** 20),
+                       "source": "profiles/c2_bf16_decode_hbm_traffic_pmc.txt"},
 }
 
 
