@@ -107,6 +107,67 @@ def test_host_side_argument_errors(lib):
     assert ap(C.byref(d), fake, fake, fake, 2, fake, None, 1, fake, fake, fake, fake, None) == INVALID
 
 
+def test_host_side_argument_errors_of_the_widened_entry_points(lib):
+    vp = C.c_void_p
+    fake = vp(0x1000)        # never dereferenced
+    INVALID, UNSUPPORTED, WORKSPACE = -1, -2, -3
+    d = pk.make_desc(2, 4, 4, 64, 8, 256, dtype=1)
+
+    def step(desc=d, q=fake, K_new=fake, V_new=fake, eidx=fake, k=2, decay=1.0, combine=0, ws=fake,
+             ws_bytes=1 << 30, scores=fake):
+        return lib.pikv_decode_step(C.byref(desc), q, fake, None, K_new, V_new, fake, fake, None, None, fake,
+                                    fake, k, combine, 0.0, decay, fake, fake, eidx, fake, fake, None, None,
+                                    scores, fake, ws, ws_bytes, None)
+    assert step(q=None) == INVALID
+    assert step(V_new=None) == INVALID                     # K_new without V_new
+    assert step(eidx=None) == INVALID                      # insert without the eviction outputs
+    assert step(k=0) == INVALID and step(k=9) == INVALID
+    assert step(decay=-1.0) == INVALID and step(combine=2) == INVALID
+    assert step(scores=None) == INVALID
+    assert step(ws_bytes=8) == WORKSPACE
+    assert step(desc=pk.make_desc(2, 4, 4, 64, 8, 256, dtype=1, route_rows_per_seq=4)) == UNSUPPORTED
+    assert step(desc=pk.make_desc(2, 4, 4, 64, 4, 256, dtype=1)) == UNSUPPORTED   # W_r rows of 8 bytes
+    assert step(desc=pk.make_desc(0, 4, 4, 64, 8, 256, dtype=1)) == 0
+
+    rp = lib.pikv_router_penalty
+    assert rp(7, fake, 1, 2, 8, fake, None, 0.1, fake, None) == INVALID
+    assert rp(0, fake, 1, 2, 8, None, None, 0.1, fake, None) == INVALID
+    assert rp(0, fake, 1, 2, 65, fake, None, 0.1, fake, None) == INVALID
+    assert rp(1, fake, 1, 2, 8, fake, None, 0.1, fake, None) == INVALID           # cache-aware needs miss
+    assert rp(0, fake, 1, 2, 8, fake, None, float("nan"), fake, None) == INVALID
+
+    cp = lib.pikv_compress
+    dr = pk.make_desc(2, 4, 4, 64, 8, 256, rank=32, dtype=1)
+    assert cp(C.byref(d), fake, fake, fake, None, None, None, None) == INVALID    # rank == 0
+    assert cp(C.byref(dr), None, fake, fake, None, None, None, None) == INVALID
+    assert cp(C.byref(dr), fake, fake, fake, fake, None, None, None) == INVALID   # partly given V
+
+    st = lib.pikv_policy_stamp
+    assert st(C.byref(d), None, 2, None, None, 0, fake, 5, fake, fake, fake, None) == INVALID
+    assert st(C.byref(d), fake, 9, None, None, 0, fake, 5, fake, fake, fake, None) == INVALID
+    assert st(C.byref(d), fake, 2, fake, None, 1, fake, 5, fake, fake, fake, None) == INVALID
+    assert st(C.byref(d), fake, 2, fake, fake, 0, fake, 5, fake, fake, fake, None) == INVALID
+    assert st(C.byref(pk.make_desc(2, 4, 4, 64, 8, 256, dtype=1, route_rows_per_seq=4)), fake, 2, None, None, 0,
+              fake, 5, fake, fake, fake, None) == UNSUPPORTED
+
+    tr = lib.pikv_update_utility_tracked
+    assert tr(C.byref(d), fake, fake, fake, fake, 2, 1.0, None, 0.1, 5, None, fake, None) == INVALID
+    assert tr(C.byref(d), fake, fake, fake, fake, 2, 1.0, None, -0.1, 5, fake, fake, None) == INVALID
+    assert tr(C.byref(d), fake, fake, fake, fake, 2, -1.0, fake, 0.1, 5, fake, fake, None) == INVALID
+    assert tr(C.byref(pk.make_desc(0, 4, 4, 64, 8, 256, dtype=1)), fake, fake, fake, fake, 2, 1.0, None, 0.1, 5,
+              fake, fake, None) == 0
+
+    pu = lib.pikv_policy_utility
+    assert pu(C.byref(d), 4, fake, 5, 0.0, 0, 0, fake, fake, fake, fake, fake, None) == INVALID
+    assert pu(C.byref(d), 0, fake, 5, 0.0, 0, 0, fake, fake, fake, None, fake, None) == INVALID   # H2O needs h2o
+    assert pu(C.byref(d), 1, fake, 5, 0.0, 3, 0, None, fake, fake, None, fake, None) == INVALID   # SL needs birth
+    assert pu(C.byref(d), 2, fake, 5, 0.0, 0, 0, fake, None, fake, None, fake, None) == INVALID   # LRU needs last
+    assert pu(C.byref(d), 3, fake, 5, float("nan"), 0, 0, fake, fake, fake, None, fake, None) == INVALID
+    assert pu(C.byref(d), 2, fake, 5, 0.0, -1, 0, fake, fake, fake, None, fake, None) == INVALID
+    assert pu(C.byref(d), 2, fake, 5, 0.0, 0, 2, None, fake, fake, None, fake, None) == INVALID   # protect needs birth
+    assert pu(C.byref(d), 2, fake, 5, 0.0, 0, 0, None, fake, None, None, None, None) == INVALID   # out
+
+
 def test_missing_library_fails_loudly(monkeypatch, tmp_path):
     monkeypatch.setattr(binding, "_lib", None)
     monkeypatch.setattr(binding, "_LIB_PATH", str(tmp_path / "nope.so"))
