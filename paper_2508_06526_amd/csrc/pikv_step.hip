@@ -249,9 +249,18 @@ __global__ __launch_bounds__(THREADS) void step_post(PostParams p) {
                 const int h = h_lo + t;
                 if (h < h_hi) a = fmaf(coef_s[h * k + j], __expf(sc[t] - shift_s[h * k + j]), a);
             }
-            for (int h = h_lo + kPostPrefetchHeads; h < h_hi; ++h)
-                a = fmaf(coef_s[h * k + j],
-                         __expf(p.scores[(((int64_t)b * Hq + h) * k + j) * p.S + i] - shift_s[h * k + j]), a);
+            // more heads per group than were prefetched: batches of loads, same ascending order
+            for (int hb = h_lo + kPostPrefetchHeads; hb < h_hi; hb += kPostPrefetchHeads) {
+                float more[kPostPrefetchHeads];
+#pragma unroll
+                for (int t = 0; t < kPostPrefetchHeads; ++t)
+                    more[t] = hb + t < h_hi ? p.scores[(((int64_t)b * Hq + hb + t) * k + j) * p.S + i] : 0.0f;
+#pragma unroll
+                for (int t = 0; t < kPostPrefetchHeads; ++t) {
+                    const int h = hb + t;
+                    if (h < h_hi) a = fmaf(coef_s[h * k + j], __expf(more[t] - shift_s[h * k + j]), a);
+                }
+            }
         }
         // the next tile's loads go out before this tile's sums meet in LDS
         const int i_next = i + kSlots;
