@@ -391,7 +391,12 @@ __global__ __launch_bounds__(kWavesPerBlock *kWave, 3) void attn_partial_gqa128(
     const int r = lane >> 4;
     const int gb = p.G;                       // heads per block = the whole query group
 
+    // Workgroups go to the 8 XCDs round-robin by id.  Giving each XCD a contiguous range of
+    // work items - whole (kv head, shard) units, whose splits share score rows and partial
+    // lines - measures 1.3 % faster here than spreading neighbours over all XCDs; the
+    // plain-ALU kernel above measures 2.6 % slower with it and keeps the round-robin order.
     int bid = blockIdx.x;
+    if (gridDim.x % 8 == 0) bid = (bid % 8) * (gridDim.x / 8) + bid / 8;
     const int split = bid % p.nsplit;
     bid /= p.nsplit;
     const int j = bid % p.k;
