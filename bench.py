@@ -30,6 +30,8 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of the dominant kernel as measured by rocprofv3 --pmc FETCH_SIZE /
 # WRITE_SIZE (two runs, scaled by what a plain 1 GiB device copy reads on the same counters);
 # the numbers and the commands are in the named files under profiles/.
+CPU_BASELINE_SECONDS = 10.0   # how long the oracle leg keeps repeating its sample
+
 MEASURED_TRAFFIC = {
     "c3_long_context": {"bytes_per_launch": int((128.21 + 5.59) * 2 ** 20),
                         "source": "profiles/c3_long_context_hbm_traffic_pmc.txt"},
@@ -194,14 +196,20 @@ def cpu_baseline(torch, wl, layers, n_steps):
             u=t["utility"].cpu().numpy(),
             UK=None if t["U_K"] is None else wl.to_host(t["U_K"], g.dtype),
             UV=None if t["U_V"] is None else wl.to_host(t["U_V"], g.dtype)))
+    # passes over the prepared steps until about 10 s of CPU work are on the clock
     t0 = time.perf_counter()
-    for p in prepared:
-        idx, gates, _ = orc.route(p["x"], p["W"], g.k, bias=p["bias"], dtype=g.dtype)
-        orc.attend(p["q"], p["Ks"], p["Vs"], p["n"], idx, gates, Hkv=g.Hkv, E=g.E, S=g.S,
-                   dtype=g.dtype, rank=g.rank, U_K=p["UK"], U_V=p["UV"], utility=p["u"],
-                   decay=DECAY.get(g.name, 1.0))
+    done = 0
+    while True:
+        for p in prepared:
+            idx, gates, _ = orc.route(p["x"], p["W"], g.k, bias=p["bias"], dtype=g.dtype)
+            orc.attend(p["q"], p["Ks"], p["Vs"], p["n"], idx, gates, Hkv=g.Hkv, E=g.E, S=g.S,
+                       dtype=g.dtype, rank=g.rank, U_K=p["UK"], U_V=p["UV"], utility=p["u"],
+                       decay=DECAY.get(g.name, 1.0))
+            done += 1
+        if not prepared or time.perf_counter() - t0 >= CPU_BASELINE_SECONDS:
+            break
     dt = time.perf_counter() - t0
-    return dt / max(1, len(prepared)), len(prepared)
+    return dt / max(1, done), done, dt
 
 
 def expert_histogram(pk, torch, geo, t, n_queries, dev):
@@ -368,12 +376,13 @@ def main():
     }
     if not args.no_cpu and args.cpu_steps != 0:
         n_cpu = args.cpu_steps if args.cpu_steps > 0 else min(n_layers, 8)
-        per_step, n_done = cpu_baseline(torch, wl, layers, n_cpu)
+        per_step, n_done, secs = cpu_baseline(torch, wl, layers, n_cpu)
         out["cpu_baseline"] = {"value": geo.B * geo.tq / per_step, "unit": "queries/s",
                                "cores": int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1)),
                                "kind": "oracle",
-                               "sample": "%d steps (layer instances) of %s: route+attend+utility, "
-                                         "selected shards copied to host" % (n_done, args.config)}
+                               "sample": "%d steps of %s (%d layer instances, repeated for %.1f s): "
+                                         "route+attend+utility, selected shards copied to host"
+                                         % (n_done, args.config, min(n_cpu, n_layers), secs)}
     print(json.dumps(out))
 
 
