@@ -149,6 +149,52 @@ def test_attention_and_utility_match_oracle(name, combine, use_gates):
                 np.testing.assert_allclose(p, ref["prob"][b, h, j, :n], rtol=1e-4, atol=1e-10)
 
 
+def random_geometry(rng):
+    D = int(rng.choice([16, 32, 64, 128]))
+    dtype = str(rng.choice(["bf16", "bf16", "f32"]))
+    rank = int(rng.choice([0, 0, 16, 32, 64]))
+    if rank >= D:
+        rank = 0
+    Hkv = int(rng.choice([1, 2, 3, 4]))
+    G = int(rng.choice([1, 1, 2, 3, 4, 5, 8, 16]))
+    E = int(rng.integers(1, 10))
+    k = int(rng.integers(1, E + 1))
+    per_head = bool(rng.random() < 0.25)
+    return dict(B=int(rng.integers(1, 4)), Hq=Hkv * G, Hkv=Hkv, D=D, E=E, S=int(rng.integers(1, 700)), k=k,
+                dtype=dtype, rank=rank, per_head_routing=per_head)
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_attention_on_random_geometries(seed):
+    """Seeded sweep over shapes nobody hand-picked: head grouping, widths, code ranks, shard counts,
+    ragged fills, both combine modes, gates or mask, split counts forced or chosen."""
+    rng = np.random.default_rng(1000 + seed)
+    g = wl.Geometry(**random_geometry(rng))
+    case = wl.make_host_case(g, seed=seed, kv="lognormal_token", n_valid=str(rng.choice(["ragged", "full"])),
+                             utility0="exp")
+    idx, gates = random_selection(g, 50 + seed)
+    if rng.random() < 0.3:
+        gates = None
+    combine = int(rng.choice([orc.COMBINE_LSE, orc.COMBINE_LOCAL]))
+    u_ref = case.utility.copy()
+    ref = oracle_step(case, idx, gates, combine, utility=u_ref, decay=0.7)
+    forced = int(rng.choice([0, 0, 1, 3, 7]))
+    pk.pikv_set_attn_split(forced)
+    try:
+        dc = DeviceCase(case)
+        d_idx = torch.from_numpy(idx).to(DEV)
+        d_gates = None if gates is None else torch.from_numpy(gates).to(DEV)
+        dc.attend(topk=d_idx, gates=d_gates, combine=combine)
+        dc.update_utility(0.7, topk=d_idx)
+        y, u = t2n(dc.y), t2n(dc.utility)
+    finally:
+        pk.pikv_set_attn_split(0)
+    ok, emax, l2 = y_tolerance_ok(y, ref["y"], g.dtype)
+    assert ok, "geometry %s: max abs %.3e, rel L2 %.3e" % (g, emax, l2)
+    np.testing.assert_allclose(t2n(dc.row_max), ref["row_max"], rtol=1e-4, atol=1e-5)
+    assert_utility_close(u, u_ref)
+
+
 def test_attention_is_bitwise_repeatable():
     spec, nv = ATTN_CASES["c3_scaled"]
     g = wl.Geometry(**spec)
