@@ -492,6 +492,52 @@ def test_fused_decode_step_equals_separate_calls_and_oracle(spec):
         np.testing.assert_array_equal(t2n(dA.n_valid), ref.n_valid)
 
 
+@pytest.mark.parametrize("seed", range(12))
+def test_fused_step_is_bit_identical_to_separate_calls_on_random_geometries(seed):
+    """The fused step is defined as the sequence of the separate calls: same bits in every piece of
+    state after several steps, on shapes nobody hand-picked (both combine modes, decay, fills)."""
+    from gpu_harness import dev_storage
+    rng = np.random.default_rng(2000 + seed)
+    dtype = str(rng.choice(["bf16", "bf16", "f32"]))
+    E = int(rng.choice([8, 16, 32] if dtype == "bf16" else [4, 8, 16]))
+    D = int(rng.choice([32, 64, 128]))
+    rank = int(rng.choice([0, 0, 16, 32]))
+    if rank >= D:
+        rank = 0
+    Hkv = int(rng.choice([1, 2, 4]))
+    G = int(rng.choice([1, 2, 3, 4, 8]))
+    g = wl.Geometry(B=int(rng.integers(1, 4)), Hq=Hkv * G, Hkv=Hkv, D=D, E=E, S=int(rng.integers(2, 300)),
+                    k=int(rng.integers(1, min(E, 6) + 1)), dtype=dtype, rank=rank)
+    case = wl.make_host_case(g, seed=seed, utility0="exp", zipf_s=1.1, n_valid=str(rng.choice(["ragged", "full"])))
+    combine = int(rng.choice([pk.COMBINE_LSE, pk.COMBINE_LOCAL]))
+    decay = float(rng.choice([1.0, 0.9, 0.5]))
+    dA, dB = DeviceCase(case), DeviceCase(case)
+    eiA = torch.full((g.B, g.E, 1), -1, device=DEV, dtype=torch.int32)
+    ecA = torch.full((g.B, g.E), -5, device=DEV, dtype=torch.int32)
+    eiB, ecB = eiA.clone(), ecA.clone()
+    for step in range(4):
+        qn = wl.draw_queries(g, 3000 + 10 * seed + step)
+        kn, vn = wl.draw_new_kv(g, 4000 + 10 * seed + step)
+        dkn, dvn = dev_storage(kn, g.dtype), dev_storage(vn, g.dtype)
+        for d in (dA, dB):
+            d.q.copy_(dev_storage(qn, g.dtype))
+        pk.pikv_decode_step(dA.desc, dA.q, dA.W_r, dA.bias, dkn, dvn, dA.K_tab, dA.V_tab, dA.U_K, dA.U_V,
+                            dA.n_valid, dA.utility, g.k, combine, 0.0, decay, dA.topk, dA.gates,
+                            eiA, ecA, dA.y, dA.row_max, dA.row_norm, dA.scores, dA.slot_coef, dA.workspace)
+        dB.route()
+        pk.pikv_evict(dB.desc, dB.utility, dB.n_valid, g.S - 1, dB.topk, g.k, eiB, ecB, 1, False, None, None)
+        pk.pikv_append(dB.desc, dkn, dvn, dB.topk, g.k, eiB, ecB, 1, dB.K_tab, dB.V_tab, dB.utility, dB.n_valid)
+        dB.attend(combine=combine)
+        dB.update_utility(decay)
+        for name in ("topk", "gates", "n_valid", "utility", "y", "row_max", "row_norm", "K", "V"):
+            a, b2 = getattr(dA, name), getattr(dB, name)
+            if a.dtype == torch.bfloat16:
+                a, b2 = a.view(torch.int16), b2.view(torch.int16)
+            np.testing.assert_array_equal(t2n(a), t2n(b2), err_msg="%s differs at step %d for %s" % (name, step, g))
+        np.testing.assert_array_equal(t2n(ecA), t2n(ecB))
+        np.testing.assert_array_equal(t2n(eiA)[t2n(ecA) == 1], t2n(eiB)[t2n(ecB) == 1])
+
+
 def test_fused_decode_step_without_insert_and_unsupported_shapes():
     g = wl.Geometry(B=2, Hq=4, Hkv=4, D=64, E=8, S=80, k=2, dtype="bf16")
     case = wl.make_host_case(g, seed=42, utility0="exp")
