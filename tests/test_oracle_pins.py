@@ -824,3 +824,25 @@ def test_policy_stamp_marks_the_slot_the_append_writes():
     full = np.full((g.B, g.E), g.S, np.int32)
     with pytest.raises(ValueError):                                     # no room: an error, as for the append
         orc.policy_stamp(topk, full, 78, birth, last, freq)
+
+
+def test_rank_r_compressor_at_the_svd_optimum_leaves_the_tail_singular_values():
+    """Table 2, rows LoRA / truncated SVD: with the encoder = decoder^T = the top-r right singular
+    vectors, the squared reconstruction error of a set of rows is the sum of the squared singular
+    values beyond r; the crop compressor's error is the energy of the dropped coordinates."""
+    rng = np.random.default_rng(3)
+    n, D, r = 12, 16, 5
+    K = (rng.standard_normal((n, D)) * np.linspace(3.0, 0.2, D)).astype(np.float32)
+    _, sig, Vt = np.linalg.svd(K.astype(np.float64), full_matrices=False)
+    U = np.ascontiguousarray(Vt[:r][None].astype(np.float32))               # [1, r, D]
+    codes = orc.compress(np.ascontiguousarray(K[:, None, :]), U)            # rows as a batch of 1-head tokens
+    recon = codes[:, 0, :].astype(np.float64) @ U[0].astype(np.float64)
+    err = ((K.astype(np.float64) - recon) ** 2).sum()
+    np.testing.assert_allclose(err, (sig[r:] ** 2).sum(), rtol=1e-4)
+    crop = np.zeros((1, r, D), np.float32)
+    crop[0, np.arange(r), np.arange(r)] = 1
+    kept = orc.compress(np.ascontiguousarray(K[:, None, :]), crop)[:, 0, :]
+    err_crop = ((K[:, :r] - kept) ** 2).sum() + (K[:, r:].astype(np.float64) ** 2).sum()
+    np.testing.assert_allclose(err_crop, (K[:, r:].astype(np.float64) ** 2).sum(), rtol=1e-12)
+    assert err <= err_crop            # the SVD basis is the optimal rank-r choice
+
