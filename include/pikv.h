@@ -223,7 +223,9 @@ int pikv_compress(const pikv_desc *desc, const void *K_full, const void *Wenc_K,
  * `now` is the caller's step counter.  An entry is accessed in a step when the attention
  * mass it received in that step, a_i = sum over the query heads that read it of its
  * probability, exceeds `threshold` (>= 0).  Slots are stable under pikv_evict with
- * compact == 0, which is the mode these arrays are meant for (compaction does not move them).
+ * compact == 0; after a pikv_evict with compact != 0 call pikv_policy_compact with that call's
+ * evicted_idx / evicted_cnt / max_evict and the n_valid it left, and the three arrays' kept
+ * entries move down the same way (shards with evicted_cnt <= 0 are left alone).
  *
  * pikv_policy_stamp: bookkeeping of the entry the next pikv_append writes (Algorithm 1
  * Insert) - call it BEFORE that pikv_append, with the same topk_idx / reuse_idx / reuse_cnt /
@@ -258,6 +260,9 @@ int pikv_policy_utility(const pikv_desc *desc, int32_t policy, const int32_t *n_
                         float lambda, int32_t window, int32_t protect, const int32_t *birth,
                         const int32_t *last_access, const int32_t *freq, const float *h2o,
                         float *out, void *stream);
+int pikv_policy_compact(const pikv_desc *desc, const int32_t *evicted_idx, const int32_t *evicted_cnt,
+                        int32_t max_evict, const int32_t *n_valid, int32_t *birth,
+                        int32_t *last_access, int32_t *freq, void *stream);
 
 /* Tuning hook: force the number of row-range splits per (head group, selected shard) used
  * by pikv_sharded_attn and pikv_attn_workspace_bytes (process-wide; 0 restores the built-in

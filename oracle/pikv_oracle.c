@@ -521,3 +521,30 @@ int pikv_oracle_policy_utility(int policy, int B, int E, int S, const int32_t *n
     return 0;
 }
 
+/* Compaction of the bookkeeping arrays after an eviction that compacted the shard
+ * (pikv_oracle_evict with compact != 0): the kept entries' stamps and counts move down
+ * with them, in ascending original-slot order.  evicted lists the removed slots
+ * (ascending) per shard, n_valid is the entry count AFTER the eviction.                */
+int pikv_oracle_policy_compact(int B, int E, int S, const int32_t *evicted_idx,
+                               const int32_t *evicted_cnt, int max_evict, const int32_t *n_valid,
+                               int32_t *birth, int32_t *last_access, int32_t *freq) {
+    if (B < 0 || E < 1 || S < 1 || max_evict < 1) return -1;
+    for (int64_t be = 0; be < (int64_t)B * E; ++be) {
+        const int cnt = evicted_cnt[be];
+        if (cnt <= 0) continue;
+        const int n_old = n_valid[be] + cnt;
+        if (n_old > S || cnt > max_evict) return -1;
+        const int32_t *gone = evicted_idx + be * max_evict;
+        int out = 0, g = 0;
+        for (int i = 0; i < n_old; ++i) {
+            if (g < cnt && gone[g] == i) { ++g; continue; }
+            birth[be * S + out] = birth[be * S + i];
+            last_access[be * S + out] = last_access[be * S + i];
+            freq[be * S + out] = freq[be * S + i];
+            ++out;
+        }
+        if (out != n_valid[be]) return -1;
+    }
+    return 0;
+}
+

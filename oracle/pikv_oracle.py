@@ -42,7 +42,7 @@ def lib():
         for name in ("pikv_oracle_route", "pikv_oracle_attend", "pikv_oracle_evict",
                      "pikv_oracle_append", "pikv_oracle_router_penalty", "pikv_oracle_compress",
                      "pikv_oracle_policy_stamp", "pikv_oracle_policy_access",
-                     "pikv_oracle_policy_utility"):
+                     "pikv_oracle_policy_utility", "pikv_oracle_policy_compact"):
             getattr(_lib, name).restype = C.c_int
     return _lib
 
@@ -284,4 +284,19 @@ def policy_utility(policy, n_valid, now, birth, last_access, freq, *, lam=0.0, w
     if rc:
         raise ValueError("pikv_oracle_policy_utility failed: %d" % rc)
     return out
+
+
+def policy_compact(evicted_idx, evicted_cnt, n_valid, birth, last_access, freq):
+    """In place on birth/last_access/freq: follow an eviction that compacted the shards
+    (n_valid as it is after that eviction)."""
+    evicted_idx = _chk(evicted_idx, np.int32, "evicted_idx")
+    evicted_cnt = _chk(evicted_cnt, np.int32, "evicted_cnt")
+    n_valid = _chk(n_valid, np.int32, "n_valid")
+    for a, nm in ((birth, "birth"), (last_access, "last_access"), (freq, "freq")):
+        _chk(a, np.int32, nm)
+    B, E, S = birth.shape
+    rc = lib().pikv_oracle_policy_compact(B, E, S, _ptr(evicted_idx), _ptr(evicted_cnt), evicted_idx.shape[2],
+                                          _ptr(n_valid), _ptr(birth), _ptr(last_access), _ptr(freq))
+    if rc:
+        raise ValueError("pikv_oracle_policy_compact failed: %d" % rc)
 

@@ -20,7 +20,7 @@ POLICY_H2O, POLICY_SL, POLICY_LRU, POLICY_LRU_PLUS = 0, 1, 2, 3
 EXPORTS = ("pikv_route", "pikv_attn_workspace_bytes", "pikv_sharded_attn", "pikv_update_utility",
            "pikv_evict", "pikv_append", "pikv_strerror", "pikv_version", "pikv_set_attn_split", "pikv_decode_step",
            "pikv_set_profile_events", "pikv_router_penalty", "pikv_compress", "pikv_policy_stamp",
-           "pikv_update_utility_tracked", "pikv_policy_utility")
+           "pikv_update_utility_tracked", "pikv_policy_utility", "pikv_policy_compact")
 
 
 class PikvError(RuntimeError):
@@ -73,6 +73,8 @@ def load_library():
     lib.pikv_update_utility_tracked.restype = C.c_int
     lib.pikv_policy_utility.argtypes = [dp, i32, vp, i32, f32, i32, i32, vp, vp, vp, vp, vp, vp]
     lib.pikv_policy_utility.restype = C.c_int
+    lib.pikv_policy_compact.argtypes = [dp, vp, vp, i32, vp, vp, vp, vp, vp]
+    lib.pikv_policy_compact.restype = C.c_int
     lib.pikv_evict.argtypes = [dp, vp, vp, i32, vp, i32, vp, vp, i32, i32, vp, vp, vp]
     lib.pikv_evict.restype = C.c_int
     lib.pikv_append.argtypes = [dp, vp, vp, vp, i32, vp, vp, i32, vp, vp, vp, vp, vp]
@@ -265,4 +267,11 @@ def pikv_policy_utility(desc, policy, n_valid, now, lam, window, protect, birth,
                                             int(window), int(protect), _p(birth), _p(last_access),
                                             _p(freq), _p(h2o), _p(out), _stream(stream))
     _check(st, "pikv_policy_utility")
+
+
+def pikv_policy_compact(desc, evicted_idx, evicted_cnt, max_evict, n_valid, birth, last_access, freq,
+                        stream=None):
+    st = load_library().pikv_policy_compact(C.byref(desc), _p(evicted_idx), _p(evicted_cnt), max_evict,
+                                            _p(n_valid), _p(birth), _p(last_access), _p(freq), _stream(stream))
+    _check(st, "pikv_policy_compact")
 

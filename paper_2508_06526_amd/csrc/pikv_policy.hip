@@ -7,6 +7,10 @@
 //                    birth = last access = now, access count 0.  One block per (sequence,
 //                    selected position), same slot rule as append_rows.
 //   policy_utility : one thread per live entry; reads three ints, writes one float.
+//   policy_compact : after an eviction that compacted a shard, one block per shard slides the
+//                    three arrays' kept entries down the same way (a pass of 256 slots at a
+//                    time, read before written; a slot's shift is the number of evicted
+//                    slots below it, found in the ascending list by binary search).
 #include "pikv_common.h"
 
 #include <math.h>
@@ -72,10 +76,73 @@ __global__ __launch_bounds__(kPolicyThreads) void policy_utility(PolicyParams p)
     p.out[at] = u;
 }
 
+struct CompactParams {
+    const int32_t *evicted_idx;
+    const int32_t *evicted_cnt;
+    const int32_t *n_valid;     // after the eviction
+    int32_t *arrays[3];
+    int S, max_evict;
+};
+
+__global__ __launch_bounds__(kPolicyThreads) void policy_compact(CompactParams p) {
+    const int be = blockIdx.x, tid = threadIdx.x;
+    const int cnt = p.evicted_cnt[be];
+    if (cnt <= 0) return;
+    const int n_old = p.n_valid[be] + cnt;
+    const int32_t *gone = p.evicted_idx + (int64_t)be * p.max_evict;
+    for (int base = gone[0]; base < n_old; base += kPolicyThreads) {   // slots below the first hole stay
+        const int i = base + tid;
+        int before = 0;
+        bool kept = false;
+        int32_t v[3] = {0, 0, 0};
+        if (i < n_old) {
+            int lo = 0, hi = cnt;            // number of evicted slots < i
+            while (lo < hi) {
+                const int mid = (lo + hi) >> 1;
+                if (gone[mid] < i) lo = mid + 1; else hi = mid;
+            }
+            before = lo;
+            kept = !(lo < cnt && gone[lo] == i);
+            if (kept)
+#pragma unroll
+                for (int a = 0; a < 3; ++a) v[a] = p.arrays[a][(int64_t)be * p.S + i];
+        }
+        __syncthreads();                     // the pass is in registers before anything moves
+        if (kept && before > 0)
+#pragma unroll
+            for (int a = 0; a < 3; ++a) p.arrays[a][(int64_t)be * p.S + i - before] = v[a];
+        __syncthreads();
+    }
+}
+
 }  // namespace
 }  // namespace pikv
 
 using namespace pikv;
+
+extern "C" int pikv_policy_compact(const pikv_desc *desc, const int32_t *evicted_idx,
+                                   const int32_t *evicted_cnt, int32_t max_evict,
+                                   const int32_t *n_valid, int32_t *birth, int32_t *last_access,
+                                   int32_t *freq, void *stream) {
+    const int rc = check_desc(desc);
+    if (rc != PIKV_OK) return rc;
+    if (!evicted_idx || !evicted_cnt || !n_valid || !birth || !last_access || !freq)
+        return PIKV_ERR_INVALID;
+    if (max_evict < 1) return PIKV_ERR_INVALID;
+    if (desc->B == 0) return PIKV_OK;
+    CompactParams p;
+    p.evicted_idx = evicted_idx;
+    p.evicted_cnt = evicted_cnt;
+    p.n_valid = n_valid;
+    p.arrays[0] = birth;
+    p.arrays[1] = last_access;
+    p.arrays[2] = freq;
+    p.S = desc->S;
+    p.max_evict = max_evict;
+    hipLaunchKernelGGL(policy_compact, dim3(desc->B * desc->E), dim3(kPolicyThreads), 0,
+                       as_stream(stream), p);
+    return launch_status();
+}
 
 extern "C" int pikv_policy_stamp(const pikv_desc *desc, const int32_t *topk_idx, int32_t k,
                                  const int32_t *reuse_idx, const int32_t *reuse_cnt,

@@ -220,3 +220,34 @@ def test_streaming_with_a_bookkeeping_policy(name):
     assert evicted_any > 10
     for s in range(g.B * g.E):
         np.testing.assert_array_equal(dc.shard_host("K", s), ref.K_shards[s])
+
+
+@pytest.mark.parametrize("S,cap", [(300, 200), (1000, 3), (64, 63), (700, 699)])
+def test_policy_arrays_follow_a_compacting_eviction(S, cap):
+    g = wl.Geometry(B=2, Hq=2, Hkv=2, D=16, E=3, S=S, k=2, dtype="bf16")
+    case = wl.make_host_case(g, seed=81, n_valid="ragged", utility0="exp")
+    case.n_valid[0, 0] = g.S
+    case.n_valid[1, 2] = min(cap, g.S)                   # nothing to evict there
+    rng = np.random.default_rng(15)
+    birth, last, freq = random_state(rng, g.B, g.E, g.S, 900)
+    dc = DeviceCase(case)
+    d = [to_dev(a) for a in (birth, last, freq)]
+    max_evict = g.S
+    eidx = torch.full((g.B, g.E, max_evict), -1, device=DEV, dtype=torch.int32)
+    ecnt = torch.zeros((g.B, g.E), device=DEV, dtype=torch.int32)
+    pk.pikv_evict(dc.desc, dc.utility, dc.n_valid, cap, None, 0, eidx, ecnt, max_evict, True, dc.K_tab, dc.V_tab)
+    pk.pikv_policy_compact(dc.desc, eidx, ecnt, max_evict, dc.n_valid, d[0], d[1], d[2])
+    ref = case.clone()
+    ridx, rcnt = orc.evict(ref.utility, ref.n_valid, cap, compact=True, K_shards=ref.K_shards, V_shards=ref.V_shards,
+                           Hkv=g.Hkv, width=g.width, dtype=g.dtype, max_evict=max_evict)
+    orc.policy_compact(ridx, rcnt, ref.n_valid, birth, last, freq)
+    np.testing.assert_array_equal(t2n(ecnt), rcnt)
+    n_after = t2n(dc.n_valid)
+    np.testing.assert_array_equal(n_after, ref.n_valid)
+    for got, want in zip(d, (birth, last, freq)):
+        got = t2n(got)
+        for b in range(g.B):
+            for e in range(g.E):
+                np.testing.assert_array_equal(got[b, e, :n_after[b, e]], want[b, e, :n_after[b, e]])
+    assert rcnt.sum() > 0
+

@@ -60,6 +60,7 @@ MUTANTS = {
     "stamp_ignores_freed_slot": ("if (reuse_cnt && reuse_cnt[be] > 0) slot = reuse_idx[be * max_evict];\n            if (slot < 0 || slot >= S || n_valid[be] >= S) return -3;\n            birth",
                                  "if (slot < 0 || slot >= S || n_valid[be] >= S) return -3;\n            birth"),
     "stamp_keeps_old_frequency": ("freq[be * S + slot] = 0;", ""),
+    "policy_compact_skips_hole_test": ("if (g < cnt && gone[g] == i) { ++g; continue; }", "if (g < cnt && gone[g] == i) { ++g; }"),
     "empty_shard_counted_in_local_norm": ("if (Z[j] > 0.0) norm += gsel ? (double)gsel[j] : 1.0;",
                                           "norm += gsel ? (double)gsel[j] : 1.0;"),
 }

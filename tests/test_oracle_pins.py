@@ -846,3 +846,27 @@ def test_rank_r_compressor_at_the_svd_optimum_leaves_the_tail_singular_values():
     np.testing.assert_allclose(err_crop, (K[:, r:].astype(np.float64) ** 2).sum(), rtol=1e-12)
     assert err <= err_crop            # the SVD basis is the optimal rank-r choice
 
+
+def test_policy_arrays_follow_a_compacting_eviction():
+    """After evict(compact) + policy_compact, slot i of every array describes the same entry as the
+    compacted utility at slot i: tag each entry with a unique id in all arrays and compare."""
+    rng = np.random.default_rng(21)
+    B, E, S, cap = 2, 3, 30, 17
+    n = np.array([[30, 20, 17], [5, 30, 0]], np.int32)
+    ids = np.arange(B * E * S, dtype=np.int32).reshape(B, E, S)
+    u = ids.astype(np.float32) % 7 + rng.random((B, E, S)).astype(np.float32)   # distinct utilities
+    tag_of = {float(u[b, e, i]): int(ids[b, e, i]) for b in range(B) for e in range(E) for i in range(S)}
+    birth, last, freq = ids.copy(), ids.copy() + 1000, ids.copy() + 2000
+    dummyK = [np.zeros((1, S, 4), np.float32) for _ in range(B * E)]
+    dummyV = [np.zeros((1, S, 4), np.float32) for _ in range(B * E)]
+    n_after = n.copy()
+    eidx, ecnt = orc.evict(u, n_after, cap, compact=True, K_shards=dummyK, V_shards=dummyV, Hkv=1, width=4,
+                           dtype="f32")
+    orc.policy_compact(eidx, ecnt, n_after, birth, last, freq)
+    for b in range(B):
+        for e in range(E):
+            for i in range(n_after[b, e]):
+                tag = tag_of[float(u[b, e, i])]
+                assert (birth[b, e, i], last[b, e, i], freq[b, e, i]) == (tag, tag + 1000, tag + 2000)
+    assert (ecnt == np.maximum(n - cap, 0)).all()
+
