@@ -66,6 +66,9 @@ def parse_args():
     ap.add_argument("--histogram", type=int, default=0, metavar="N",
                     help="route N random queries through layer 0's router and print the empirical "
                          "expert popularity to stderr")
+    ap.add_argument("--policy", choices=["none", "lru", "lru_plus", "sl"], default="none",
+                    help="widened row: evict by a Table 3 bookkeeping policy inside the fused step "
+                         "(pikv_decode_step_policy) and keep the access stamps and counts up to date")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run a plain 1 GiB device copy 8 times and exit (reference for the "
                          "rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")
@@ -112,6 +115,17 @@ class Layer:
 
     def _step(self):
         pk, g, t, s = self.pk, self.geo, self.t, self.sh
+        if self.fused and s.get("policy"):
+            # the step counter is baked into the captured launch: replays re-stamp with the same
+            # value, which costs the same as a running counter
+            args = pk.make_policy_args(s["policy"], 1000, lam=0.5, window=g.S // 2, threshold=1.0 / g.S,
+                                       birth=t["birth"], last_access=t["last_access"], freq=t["freq"])
+            pk.pikv_decode_step_policy(self.desc, t["q"], t["W_r"], t["bias"], s["K_new"], s["V_new"],
+                                       self.K_tab, self.V_tab, t["U_K"], t["U_V"], t["n_valid"], t["utility"],
+                                       g.k, pk.COMBINE_LSE, 0.0, self.decay, s["topk"], s["gates"], s["eidx"],
+                                       s["ecnt"], s["y"], s["row_max"], s["row_norm"], s["scores"],
+                                       s["slot_coef"], s["workspace"], args)
+            return
         if self.fused:
             pk.pikv_decode_step(self.desc, t["q"], t["W_r"], t["bias"], s["K_new"], s["V_new"],
                                 self.K_tab, self.V_tab, t["U_K"], t["U_V"], t["n_valid"], t["utility"],
@@ -272,6 +286,12 @@ def main():
         for t in raw:
             t["load"] = torch.zeros(geo.E, device=dev, dtype=torch.int32)
             t["bias"] = torch.zeros(geo.E, device=dev)
+    if args.policy != "none":
+        shared["policy"] = {"lru": pk.POLICY_LRU, "lru_plus": pk.POLICY_LRU_PLUS, "sl": pk.POLICY_SL}[args.policy]
+        for t in raw:
+            t["birth"] = torch.randint(0, 1000, (geo.B, geo.E, geo.S), device=dev, dtype=torch.int32)
+            t["last_access"] = torch.randint(0, 1000, (geo.B, geo.E, geo.S), device=dev, dtype=torch.int32)
+            t["freq"] = torch.randint(0, 50, (geo.B, geo.E, geo.S), device=dev, dtype=torch.int32)
     if args.compress and geo.rank:
         tdt = torch.bfloat16 if geo.dtype == "bf16" else torch.float32
         gen = torch.Generator(device=dev)
@@ -359,7 +379,7 @@ def main():
                    "overrides": {"k": args.k or None, "rank": args.rank if args.rank >= 0 else None}, "queries_per_sequence": geo.tq,
                    "layers_cycled": n_layers,
                    "launch": args.mode, "api": args.api, "balance": bool(args.balance),
-                   "compress_on_insert": bool(args.compress and geo.rank),
+                   "compress_on_insert": bool(args.compress and geo.rank), "policy": args.policy,
                    "step": "route+evict1+append+attend+utility"},
         "step_effective_GBps": kv_bytes / (ms_per_step * 1e-3) / 1e9,
         "step_frac_of_hbm_peak": kv_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,

@@ -260,6 +260,37 @@ int pikv_policy_utility(const pikv_desc *desc, int32_t policy, const int32_t *n_
                         float lambda, int32_t window, int32_t protect, const int32_t *birth,
                         const int32_t *last_access, const int32_t *freq, const float *h2o,
                         float *out, void *stream);
+/* pikv_decode_step with a scheduling policy (same arguments, plus `policy`; NULL = exactly
+ * pikv_decode_step).  It is the sequence
+ *   pikv_route; pikv_policy_utility(policy, ...) into a scratch utility;
+ *   pikv_evict(scratch, capacity = S-1, sel_idx = topk_idx, max_evict = 1, compact = 0);
+ *   pikv_policy_stamp; pikv_append; pikv_sharded_attn;
+ *   pikv_update_utility_tracked(decay, utility, threshold, now, last_access, freq)
+ * in the same three launches as pikv_decode_step, with no scratch utility: the entry to evict
+ * is chosen on the policy's value computed on the fly (bit-identical to the separate calls).
+ * Arrays the policy does not read may be NULL; the new entry is stamped in those given; access
+ * bookkeeping runs when last_access and freq are both given (threshold >= 0).  `utility` keeps
+ * accumulating the attention (H2O) whatever the policy.
+ * Errors: as pikv_decode_step and pikv_policy_utility.                                       */
+typedef struct {
+    int32_t policy;        /* pikv_policy */
+    int32_t now;           /* the caller's step counter */
+    float lambda;          /* PIKV_POLICY_LRU_PLUS */
+    int32_t window;        /* PIKV_POLICY_SL */
+    int32_t protect;       /* > 0: entries younger than this many steps are never evicted */
+    float threshold;       /* attention mass above which an entry counts as accessed */
+    int32_t *birth;        /* [B,E,S] device arrays */
+    int32_t *last_access;
+    int32_t *freq;
+} pikv_policy_args;
+int pikv_decode_step_policy(const pikv_desc *desc, const void *q, const void *W_r, const float *bias,
+                            const void *K_new, const void *V_new, void *const *K_shards,
+                            void *const *V_shards, const void *U_K, const void *U_V, int32_t *n_valid,
+                            float *utility, int32_t k, int32_t combine, float scale, float decay,
+                            int32_t *topk_idx, float *gates, int32_t *evicted_idx, int32_t *evicted_cnt,
+                            float *y, float *row_max, float *row_norm, float *scores, float *slot_coef,
+                            void *workspace, size_t workspace_bytes, void *stream,
+                            const pikv_policy_args *policy);
 int pikv_policy_compact(const pikv_desc *desc, const int32_t *evicted_idx, const int32_t *evicted_cnt,
                         int32_t max_evict, const int32_t *n_valid, int32_t *birth,
                         int32_t *last_access, int32_t *freq, void *stream);

@@ -20,7 +20,7 @@ POLICY_H2O, POLICY_SL, POLICY_LRU, POLICY_LRU_PLUS = 0, 1, 2, 3
 EXPORTS = ("pikv_route", "pikv_attn_workspace_bytes", "pikv_sharded_attn", "pikv_update_utility",
            "pikv_evict", "pikv_append", "pikv_strerror", "pikv_version", "pikv_set_attn_split", "pikv_decode_step",
            "pikv_set_profile_events", "pikv_router_penalty", "pikv_compress", "pikv_policy_stamp",
-           "pikv_update_utility_tracked", "pikv_policy_utility", "pikv_policy_compact")
+           "pikv_update_utility_tracked", "pikv_policy_utility", "pikv_policy_compact", "pikv_decode_step_policy")
 
 
 class PikvError(RuntimeError):
@@ -84,6 +84,8 @@ def load_library():
     lib.pikv_decode_step.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, f32, f32,
                                      vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
     lib.pikv_decode_step.restype = C.c_int
+    lib.pikv_decode_step_policy.argtypes = list(lib.pikv_decode_step.argtypes) + [vp]
+    lib.pikv_decode_step_policy.restype = C.c_int
     lib.pikv_router_penalty.argtypes = [i32, vp, i32, i32, i32, vp, vp, f32, vp, vp]
     lib.pikv_router_penalty.restype = C.c_int
     lib.pikv_compress.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp]
@@ -274,4 +276,33 @@ def pikv_policy_compact(desc, evicted_idx, evicted_cnt, max_evict, n_valid, birt
     st = load_library().pikv_policy_compact(C.byref(desc), _p(evicted_idx), _p(evicted_cnt), max_evict,
                                             _p(n_valid), _p(birth), _p(last_access), _p(freq), _stream(stream))
     _check(st, "pikv_policy_compact")
+
+
+class PikvPolicyArgs(C.Structure):
+    _fields_ = [("policy", C.c_int32), ("now", C.c_int32), ("lam", C.c_float), ("window", C.c_int32),
+                ("protect", C.c_int32), ("threshold", C.c_float), ("birth", C.c_void_p),
+                ("last_access", C.c_void_p), ("freq", C.c_void_p)]
+
+
+def make_policy_args(policy, now, lam=0.0, window=0, protect=0, threshold=0.0, birth=None, last_access=None,
+                     freq=None):
+    a = PikvPolicyArgs()
+    a.policy, a.now, a.lam, a.window, a.protect, a.threshold = int(policy), int(now), float(lam), int(window), \
+        int(protect), float(threshold)
+    for name, t in (("birth", birth), ("last_access", last_access), ("freq", freq)):
+        ptr = _p(t)
+        setattr(a, name, None if ptr is None else ptr.value)
+    return a
+
+
+def pikv_decode_step_policy(desc, q, W_r, bias, K_new, V_new, K_shards, V_shards, U_K, U_V, n_valid, utility, k,
+                            combine, scale, decay, topk_idx, gates, evicted_idx, evicted_cnt, y, row_max,
+                            row_norm, scores, slot_coef, workspace, policy_args, stream=None):
+    st = load_library().pikv_decode_step_policy(
+        C.byref(desc), _p(q), _p(W_r), _p(bias), _p(K_new), _p(V_new), _p(K_shards), _p(V_shards), _p(U_K),
+        _p(U_V), _p(n_valid), _p(utility), k, combine, float(scale), float(decay), _p(topk_idx), _p(gates),
+        _p(evicted_idx), _p(evicted_cnt), _p(y), _p(row_max), _p(row_norm), _p(scores), _p(slot_coef),
+        _p(workspace), workspace.numel() * workspace.element_size(), _stream(stream),
+        None if policy_args is None else C.cast(C.pointer(policy_args), C.c_void_p))
+    _check(st, "pikv_decode_step_policy")
 

@@ -12,6 +12,7 @@
 //                    time, read before written; a slot's shift is the number of evicted
 //                    slots below it, found in the ascending list by binary search).
 #include "pikv_common.h"
+#include "pikv_policy_dev.h"
 
 #include <math.h>
 
@@ -49,13 +50,10 @@ __global__ __launch_bounds__(kWave) void policy_stamp(StampParams p) {
 
 struct PolicyParams {
     const int32_t *n_valid;
-    const int32_t *birth;
-    const int32_t *last_access;
-    const int32_t *freq;
     const float *h2o;
     float *out;
-    int S, tiles, policy, now, window, protect;
-    float lambda;
+    int S, tiles;
+    PolicyView v;
 };
 
 __global__ __launch_bounds__(kPolicyThreads) void policy_utility(PolicyParams p) {
@@ -63,17 +61,7 @@ __global__ __launch_bounds__(kPolicyThreads) void policy_utility(PolicyParams p)
     const int i = tile * kPolicyThreads + threadIdx.x;
     if (i >= p.n_valid[be]) return;
     const int64_t at = (int64_t)be * p.S + i;
-    float u;
-    if (p.policy == PIKV_POLICY_H2O) {
-        u = p.h2o[at];
-    } else if (p.policy == PIKV_POLICY_SL) {
-        u = (p.now - p.birth[at] < p.window) ? 1.0f : 0.0f;
-    } else {
-        const float r = (float)(p.now - p.last_access[at]);
-        u = (p.policy == PIKV_POLICY_LRU) ? -r : fmaf(p.lambda, (float)p.freq[at], -r);
-    }
-    if (p.protect > 0 && p.now - p.birth[at] < p.protect) u = INFINITY;
-    p.out[at] = u;
+    p.out[at] = policy_value(p.v, at, p.h2o);
 }
 
 struct CompactParams {
@@ -184,27 +172,24 @@ extern "C" int pikv_policy_utility(const pikv_desc *desc, int32_t policy, const 
     const int rc = check_desc(desc);
     if (rc != PIKV_OK) return rc;
     if (!n_valid || !out) return PIKV_ERR_INVALID;
-    if (policy < PIKV_POLICY_H2O || policy > PIKV_POLICY_LRU_PLUS) return PIKV_ERR_INVALID;
-    if (policy == PIKV_POLICY_H2O && !h2o) return PIKV_ERR_INVALID;
-    if ((policy == PIKV_POLICY_SL || protect > 0) && !birth) return PIKV_ERR_INVALID;
-    if (policy >= PIKV_POLICY_LRU && !last_access) return PIKV_ERR_INVALID;
-    if (policy == PIKV_POLICY_LRU_PLUS && (!freq || !(lambda == lambda))) return PIKV_ERR_INVALID;
-    if (window < 0 || protect < 0) return PIKV_ERR_INVALID;
+    const int prc = check_policy(policy, window, protect, lambda, birth, last_access, freq, h2o);
+    if (prc != PIKV_OK) return prc;
     if (desc->B == 0) return PIKV_OK;
     PolicyParams p;
     p.n_valid = n_valid;
-    p.birth = birth;
-    p.last_access = last_access;
-    p.freq = freq;
     p.h2o = h2o;
     p.out = out;
     p.S = desc->S;
     p.tiles = (desc->S + kPolicyThreads - 1) / kPolicyThreads;
-    p.policy = policy;
-    p.now = now;
-    p.window = window;
-    p.protect = protect;
-    p.lambda = lambda;
+    p.v.policy = policy;
+    p.v.now = now;
+    p.v.window = window;
+    p.v.protect = protect;
+    p.v.lambda = lambda;
+    p.v.threshold = 0.0f;
+    p.v.birth = const_cast<int32_t *>(birth);
+    p.v.last_access = const_cast<int32_t *>(last_access);
+    p.v.freq = const_cast<int32_t *>(freq);
     const int64_t blocks = (int64_t)desc->B * desc->E * p.tiles;
     if (blocks > 0x7fffffff) return PIKV_ERR_UNSUPPORTED;
     hipLaunchKernelGGL(policy_utility, dim3((unsigned)blocks), dim3(kPolicyThreads), 0,

@@ -18,6 +18,7 @@
 #include "pikv_common.h"
 #include "pikv_combine_dev.h"
 #include "pikv_route_dev.h"
+#include "pikv_policy_dev.h"
 
 namespace pikv {
 namespace {
@@ -38,6 +39,8 @@ struct PreParams {
     int32_t *evicted_cnt;
     int64_t stride_h_bytes, stride_s_bytes;
     int d_r, E, cpr, k, S, Hkv, row_chunks, do_insert;
+    int use_policy;      // the entry to evict is chosen by pol (Table 3) instead of the utility
+    PolicyView pol;      // its arrays, when given, are also stamped for the new entry
 };
 
 // Grid: (sequence b, selected position j).  Every block of a sequence recomputes the routing
@@ -79,7 +82,24 @@ __global__ __launch_bounds__(kRouteThreads) void step_pre(PreParams p) {
     char *Vd = static_cast<char *>(p.V[be]);
     const float *u = p.utility + be * p.S;
     uint64_t best = ~0ull;
-    if ((p.S & 3) == 0) {
+    if (p.use_policy) {
+        if (policy_vec_ok(p.pol, p.utility, p.S)) {
+            for (int i = tid * 4; i < p.S; i += kRouteThreads * 4) {
+                float v[4];
+                policy_value4(p.pol, be * p.S + i, p.utility, v);
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    const uint64_t c0 = evict_composite(v[t], i + t);
+                    best = c0 < best ? c0 : best;
+                }
+            }
+        } else {
+            for (int i = tid; i < p.S; i += kRouteThreads) {
+                const uint64_t c0 = evict_composite(policy_value(p.pol, be * p.S + i, p.utility), i);
+                best = c0 < best ? c0 : best;
+            }
+        }
+    } else if ((p.S & 3) == 0) {
         for (int i = tid * 4; i < p.S; i += kRouteThreads * 4) {
             const float4 v = *reinterpret_cast<const float4 *>(u + i);
             uint64_t c0 = evict_composite(v.x, i), c1 = evict_composite(v.y, i + 1);
@@ -126,6 +146,10 @@ __global__ __launch_bounds__(kRouteThreads) void step_pre(PreParams p) {
         p.evicted_cnt[be] = full ? 1 : 0;
         p.utility[be * p.S + slot] = 0.0f;
         p.n_valid[be] = full ? p.S : n + 1;
+        // the new entry's bookkeeping (Algorithm 1 Insert)
+        if (p.pol.birth) p.pol.birth[be * p.S + slot] = p.pol.now;
+        if (p.pol.last_access) p.pol.last_access[be * p.S + slot] = p.pol.now;
+        if (p.pol.freq) p.pol.freq[be * p.S + slot] = 0;
     }
     // experts nobody selected report "nothing evicted" (block 0 of the sequence)
     if (j == 0 && tid < p.E) {
@@ -155,6 +179,8 @@ struct PostParams {
     int tiles;            // utility blocks per selected shard
     int tiles_per_block;  // consecutive slot tiles each of them covers
     float decay;
+    int track;            // access bookkeeping: mass above pol.threshold stamps and counts the entry
+    PolicyView pol;
 };
 
 // LDS of a utility block: statistics of the Hq * k (head, shard) pairs, the gates, and two
@@ -276,6 +302,11 @@ __global__ __launch_bounds__(THREADS) void step_post(PostParams p) {
             const float total = (part[slot] + part[kSlots + slot]) +
                                 (part[2 * kSlots + slot] + part[3 * kSlots + slot]);
             urow[i] = fmaf(p.decay, u_cur, total);
+            if (p.track && total > p.pol.threshold) {
+                const int64_t at = ((int64_t)b * p.E + e) * p.S + i;
+                p.pol.last_access[at] = p.pol.now;
+                p.pol.freq[at] += 1;
+            }
         }
         i = i_next;
     }
@@ -286,16 +317,35 @@ __global__ __launch_bounds__(THREADS) void step_post(PostParams p) {
 
 using namespace pikv;
 
-extern "C" int pikv_decode_step(const pikv_desc *desc, const void *q, const void *W_r,
-                                const float *bias, const void *K_new, const void *V_new,
-                                void *const *K_shards, void *const *V_shards, const void *U_K,
-                                const void *U_V, int32_t *n_valid, float *utility, int32_t k,
-                                int32_t combine, float scale, float decay, int32_t *topk_idx,
-                                float *gates, int32_t *evicted_idx, int32_t *evicted_cnt, float *y,
-                                float *row_max, float *row_norm, float *scores, float *slot_coef,
-                                void *workspace, size_t workspace_bytes, void *stream) {
+static int decode_step(const pikv_desc *desc, const void *q, const void *W_r, const float *bias,
+                       const void *K_new, const void *V_new, void *const *K_shards,
+                       void *const *V_shards, const void *U_K, const void *U_V, int32_t *n_valid,
+                       float *utility, int32_t k, int32_t combine, float scale, float decay,
+                       int32_t *topk_idx, float *gates, int32_t *evicted_idx, int32_t *evicted_cnt,
+                       float *y, float *row_max, float *row_norm, float *scores, float *slot_coef,
+                       void *workspace, size_t workspace_bytes, void *stream,
+                       const pikv_policy_args *pa) {
     const int rc = check_desc(desc);
     if (rc != PIKV_OK) return rc;
+    PolicyView pol = {};
+    bool use_policy = false, track = false;
+    if (pa != nullptr) {
+        const int prc = check_policy(pa->policy, pa->window, pa->protect, pa->lambda, pa->birth,
+                                     pa->last_access, pa->freq, utility);
+        if (prc != PIKV_OK) return prc;
+        track = pa->last_access != nullptr && pa->freq != nullptr;
+        if (track && !(pa->threshold >= 0.0f)) return PIKV_ERR_INVALID;
+        pol.policy = pa->policy;
+        pol.now = pa->now;
+        pol.window = pa->window;
+        pol.protect = pa->protect;
+        pol.lambda = pa->lambda;
+        pol.threshold = pa->threshold;
+        pol.birth = pa->birth;
+        pol.last_access = pa->last_access;
+        pol.freq = pa->freq;
+        use_policy = pa->policy != PIKV_POLICY_H2O || pa->protect > 0;
+    }
     if (!q || !W_r || !K_shards || !V_shards || !n_valid || !utility || !topk_idx || !gates || !y ||
         !scores || !slot_coef)
         return PIKV_ERR_INVALID;
@@ -336,6 +386,8 @@ extern "C" int pikv_decode_step(const pikv_desc *desc, const void *q, const void
     p.Hkv = desc->Hkv;
     p.row_chunks = desc_width(desc) * eb / 16;
     p.do_insert = K_new != nullptr;
+    p.use_policy = use_policy;
+    p.pol = pol;
     hipStream_t st = as_stream(stream);
     if (desc->dtype == PIKV_F32)
         hipLaunchKernelGGL(step_pre<float>, dim3(desc->B * k), dim3(kRouteThreads), 0, st, p);
@@ -353,6 +405,10 @@ extern "C" int pikv_decode_step(const pikv_desc *desc, const void *q, const void
         // too many partials to restage per utility block: separate merge and utility launches
         lrc = pikv_sharded_attn_merge(desc, &c, stream);
         if (lrc != PIKV_OK) return lrc;
+        if (track)
+            return pikv_update_utility_tracked(desc, scores, slot_coef, n_valid, topk_idx, k, decay,
+                                               utility, pol.threshold, pol.now, pol.last_access,
+                                               pol.freq, stream);
         return pikv_update_utility(desc, scores, slot_coef, n_valid, topk_idx, k, decay, utility,
                                    stream);
     }
@@ -362,6 +418,8 @@ extern "C" int pikv_decode_step(const pikv_desc *desc, const void *q, const void
     pp.n_valid = n_valid;
     pp.topk = topk_idx;
     pp.utility = utility;
+    pp.track = track;
+    pp.pol = pol;
     pp.B = desc->B;
     pp.E = desc->E;
     pp.S = desc->S;
@@ -399,3 +457,31 @@ extern "C" int pikv_decode_step(const pikv_desc *desc, const void *q, const void
 #undef PIKV_LAUNCH_POST
     return launch_status();
 }
+
+extern "C" int pikv_decode_step(const pikv_desc *desc, const void *q, const void *W_r,
+                                const float *bias, const void *K_new, const void *V_new,
+                                void *const *K_shards, void *const *V_shards, const void *U_K,
+                                const void *U_V, int32_t *n_valid, float *utility, int32_t k,
+                                int32_t combine, float scale, float decay, int32_t *topk_idx,
+                                float *gates, int32_t *evicted_idx, int32_t *evicted_cnt, float *y,
+                                float *row_max, float *row_norm, float *scores, float *slot_coef,
+                                void *workspace, size_t workspace_bytes, void *stream) {
+    return decode_step(desc, q, W_r, bias, K_new, V_new, K_shards, V_shards, U_K, U_V, n_valid, utility,
+                       k, combine, scale, decay, topk_idx, gates, evicted_idx, evicted_cnt, y, row_max,
+                       row_norm, scores, slot_coef, workspace, workspace_bytes, stream, nullptr);
+}
+
+extern "C" int pikv_decode_step_policy(const pikv_desc *desc, const void *q, const void *W_r,
+                                       const float *bias, const void *K_new, const void *V_new,
+                                       void *const *K_shards, void *const *V_shards, const void *U_K,
+                                       const void *U_V, int32_t *n_valid, float *utility, int32_t k,
+                                       int32_t combine, float scale, float decay, int32_t *topk_idx,
+                                       float *gates, int32_t *evicted_idx, int32_t *evicted_cnt,
+                                       float *y, float *row_max, float *row_norm, float *scores,
+                                       float *slot_coef, void *workspace, size_t workspace_bytes,
+                                       void *stream, const pikv_policy_args *policy) {
+    return decode_step(desc, q, W_r, bias, K_new, V_new, K_shards, V_shards, U_K, U_V, n_valid, utility,
+                       k, combine, scale, decay, topk_idx, gates, evicted_idx, evicted_cnt, y, row_max,
+                       row_norm, scores, slot_coef, workspace, workspace_bytes, stream, policy);
+}
+

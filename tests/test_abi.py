@@ -157,6 +157,27 @@ def test_host_side_argument_errors_of_the_widened_entry_points(lib):
     assert tr(C.byref(pk.make_desc(0, 4, 4, 64, 8, 256, dtype=1)), fake, fake, fake, fake, 2, 1.0, None, 0.1, 5,
               fake, fake, None) == 0
 
+    lib.pikv_decode_step_policy.argtypes = list(lib.pikv_decode_step.argtypes) + [vp]
+    lib.pikv_decode_step_policy.restype = C.c_int
+
+    def pstep(args):
+        return lib.pikv_decode_step_policy(C.byref(d), fake, fake, None, fake, fake, fake, fake, None, None, fake,
+                                           fake, 2, 0, 0.0, 1.0, fake, fake, fake, fake, fake, None, None, fake,
+                                           fake, fake, 1 << 30, None, C.cast(C.pointer(args), vp))
+    fakeptr = 0x1000
+    bad = pk.PikvPolicyArgs(policy=9, now=1)
+    assert pstep(bad) == INVALID
+    assert pstep(pk.PikvPolicyArgs(policy=pk.POLICY_LRU, now=1)) == INVALID                     # needs last_access
+    assert pstep(pk.PikvPolicyArgs(policy=pk.POLICY_SL, now=1, window=4)) == INVALID             # needs birth
+    assert pstep(pk.PikvPolicyArgs(policy=pk.POLICY_LRU, now=1, last_access=fakeptr, freq=fakeptr,
+                                   threshold=-1.0)) == INVALID                                   # tracking threshold
+    assert pstep(pk.PikvPolicyArgs(policy=pk.POLICY_LRU_PLUS, now=1, lam=float("nan"), last_access=fakeptr,
+                                   freq=fakeptr)) == INVALID
+    pc = lib.pikv_policy_compact
+    assert pc(C.byref(d), None, fake, 4, fake, fake, fake, fake, None) == INVALID
+    assert pc(C.byref(d), fake, fake, 0, fake, fake, fake, fake, None) == INVALID
+    assert pc(C.byref(pk.make_desc(0, 4, 4, 64, 8, 256, dtype=1)), fake, fake, 4, fake, fake, fake, fake, None) == 0
+
     pu = lib.pikv_policy_utility
     assert pu(C.byref(d), 4, fake, 5, 0.0, 0, 0, fake, fake, fake, fake, fake, None) == INVALID
     assert pu(C.byref(d), 0, fake, 5, 0.0, 0, 0, fake, fake, fake, None, fake, None) == INVALID   # H2O needs h2o

@@ -251,3 +251,64 @@ def test_policy_arrays_follow_a_compacting_eviction(S, cap):
                 np.testing.assert_array_equal(got[b, e, :n_after[b, e]], want[b, e, :n_after[b, e]])
     assert rcnt.sum() > 0
 
+
+
+@pytest.mark.parametrize("name", ["h2o_protect", "sl", "lru", "lru_plus"])
+@pytest.mark.parametrize("spec", [
+    dict(B=3, Hq=4, Hkv=2, D=64, E=8, S=48, k=2, dtype="bf16"),
+    dict(B=2, Hq=8, Hkv=2, D=128, E=16, S=70, k=3, dtype="bf16"),          # matrix-core attention kernel
+    dict(B=2, Hq=4, Hkv=4, D=128, E=8, S=40, k=2, dtype="bf16", rank=32),
+], ids=["d64", "gqa4_d128", "rank32"])
+def test_fused_step_with_a_policy_is_bit_identical_to_the_separate_calls(name, spec):
+    """pikv_decode_step_policy against the sequence it is defined as: route, policy utility, evict,
+    stamp, append, attend, tracked update - all state equal bit for bit over several steps."""
+    g = wl.Geometry(**spec)
+    case = wl.make_host_case(g, seed=91, utility0="exp", zipf_s=1.1)
+    case.n_valid[:, 1] = g.S - 2
+    policy = {"h2o_protect": pk.POLICY_H2O, "sl": pk.POLICY_SL, "lru": pk.POLICY_LRU, "lru_plus": pk.POLICY_LRU_PLUS}[name]
+    protect = 6 if name == "h2o_protect" else 0
+    lam, window, thr = 1.5, 12, 0.02
+    rng = np.random.default_rng(16)
+    birth, last, freq = random_state(rng, g.B, g.E, g.S, 20)
+    dA, dB = DeviceCase(case), DeviceCase(case)
+    sA = [to_dev(a) for a in (birth, last, freq)]
+    sB = [to_dev(a) for a in (birth, last, freq)]
+    u_pol = torch.zeros((g.B, g.E, g.S), device=DEV)
+    eiA = torch.full((g.B, g.E, 1), -1, device=DEV, dtype=torch.int32)
+    ecA = torch.full((g.B, g.E), -5, device=DEV, dtype=torch.int32)
+    eiB, ecB = eiA.clone(), ecA.clone()
+    evictions = 0
+    for step in range(6):
+        now = 21 + step
+        qn = wl.draw_queries(g, 7000 + step)
+        kn, vn = wl.draw_new_kv(g, 7100 + step)
+        dkn, dvn = dev_storage(kn, g.dtype), dev_storage(vn, g.dtype)
+        for d in (dA, dB):
+            d.q.copy_(dev_storage(qn, g.dtype))
+        args = pk.make_policy_args(policy, now, lam=lam, window=window, protect=protect, threshold=thr,
+                                   birth=sA[0], last_access=sA[1], freq=sA[2])
+        pk.pikv_decode_step_policy(dA.desc, dA.q, dA.W_r, dA.bias, dkn, dvn, dA.K_tab, dA.V_tab, dA.U_K, dA.U_V,
+                                   dA.n_valid, dA.utility, g.k, pk.COMBINE_LSE, 0.0, 0.9, dA.topk, dA.gates,
+                                   eiA, ecA, dA.y, dA.row_max, dA.row_norm, dA.scores, dA.slot_coef,
+                                   dA.workspace, args)
+        dB.route()
+        pk.pikv_policy_utility(dB.desc, policy, dB.n_valid, now, lam, window, protect, sB[0], sB[1], sB[2],
+                               dB.utility, u_pol)
+        pk.pikv_evict(dB.desc, u_pol, dB.n_valid, g.S - 1, dB.topk, g.k, eiB, ecB, 1, False, None, None)
+        pk.pikv_policy_stamp(dB.desc, dB.topk, g.k, eiB, ecB, 1, dB.n_valid, now, sB[0], sB[1], sB[2])
+        pk.pikv_append(dB.desc, dkn, dvn, dB.topk, g.k, eiB, ecB, 1, dB.K_tab, dB.V_tab, dB.utility, dB.n_valid)
+        dB.attend(combine=pk.COMBINE_LSE)
+        pk.pikv_update_utility_tracked(dB.desc, dB.scores, dB.slot_coef, dB.n_valid, dB.topk, g.k, 0.9,
+                                       dB.utility, thr, now, sB[1], sB[2])
+        for nm in ("topk", "gates", "n_valid", "utility", "y", "K", "V"):
+            a, b2 = getattr(dA, nm), getattr(dB, nm)
+            if a.dtype == torch.bfloat16:
+                a, b2 = a.view(torch.int16), b2.view(torch.int16)
+            np.testing.assert_array_equal(t2n(a), t2n(b2), err_msg="%s differs at step %d" % (nm, step))
+        for a, b2, nm in zip(sA, sB, ("birth", "last_access", "freq")):
+            np.testing.assert_array_equal(t2n(a), t2n(b2), err_msg="%s differs at step %d" % (nm, step))
+        np.testing.assert_array_equal(t2n(ecA), t2n(ecB))
+        np.testing.assert_array_equal(t2n(eiA)[t2n(ecA) == 1], t2n(eiB)[t2n(ecB) == 1])
+        evictions += int((t2n(ecA) == 1).sum())
+    assert evictions > 0
+    assert (t2n(sA[2]) != freq).any()            # accesses were counted
