@@ -722,3 +722,58 @@ def test_fused_step_with_many_heads_times_shards_uses_the_separate_merge():
     ok, emax, l2 = y_tolerance_ok(t2n(dA.y), ref["y"], g.dtype)
     assert ok, (emax, l2)
     assert_utility_close(t2n(dA.utility), u_ref)
+
+
+# ------------------------------------------------------------------- HIP graph replay
+@pytest.mark.parametrize("spec", [
+    dict(B=2, Hq=8, Hkv=2, D=128, E=8, S=96, k=2, dtype="bf16"),            # matrix-core kernel
+    dict(B=3, Hq=4, Hkv=4, D=64, E=8, S=80, k=3, dtype="bf16", rank=16),   # plain-ALU kernel, codes
+], ids=["gqa4_d128", "rank16"])
+def test_graph_replays_of_the_fused_step_equal_eager_steps(spec):
+    """The benchmark times a captured graph of fused steps.  Every replay must leave exactly the
+    state the same number of eager steps leaves (the step carries state: utilities, entry counts,
+    evicted rows), with eager work and synchronisations of the program's own between replays."""
+    from gpu_harness import dev_storage
+    g = wl.Geometry(**spec)
+    case = wl.make_host_case(g, seed=101, utility0="exp", zipf_s=1.1)
+    kn, vn = wl.draw_new_kv(g, 102)
+    per_graph, replays = 3, 4
+
+    def run(dc, ei, ec, dkn, dvn):
+        pk.pikv_decode_step(dc.desc, dc.q, dc.W_r, dc.bias, dkn, dvn, dc.K_tab, dc.V_tab, dc.U_K, dc.U_V,
+                            dc.n_valid, dc.utility, g.k, pk.COMBINE_LSE, 0.0, 0.9, dc.topk, dc.gates, ei, ec,
+                            dc.y, dc.row_max, dc.row_norm, dc.scores, dc.slot_coef, dc.workspace)
+
+    def fresh():
+        dc = DeviceCase(case)
+        ei = torch.full((g.B, g.E, 1), -1, device=DEV, dtype=torch.int32)
+        ec = torch.zeros((g.B, g.E), device=DEV, dtype=torch.int32)
+        return dc, ei, ec, dev_storage(kn, g.dtype), dev_storage(vn, g.dtype)
+
+    # eager reference trajectory, a snapshot after every per_graph steps
+    dE = fresh()
+    snaps = []
+    for r in range(replays + 1):                  # +1: the capture pass itself executes nothing, warm-up does
+        for _ in range(per_graph):
+            run(*dE)
+        snaps.append([t2n(x).copy() for x in (dE[0].utility, dE[0].n_valid, dE[0].y, dE[0].topk, dE[2])])
+
+    dG = fresh()
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        for _ in range(per_graph):                # warm-up = the first per_graph steps of the trajectory
+            run(*dG)
+        stream.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=stream):
+            for _ in range(per_graph):
+                run(*dG)
+        for r in range(replays):
+            graph.replay()
+            stream.synchronize()
+            got = [t2n(x) for x in (dG[0].utility, dG[0].n_valid, dG[0].y, dG[0].topk, dG[2])]
+            for a, b2, nm in zip(got, snaps[r + 1], ("utility", "n_valid", "y", "topk", "evicted_cnt")):
+                np.testing.assert_array_equal(a, b2, err_msg="%s differs after replay %d" % (nm, r))
+            # eager work of the program's own between replays (must not disturb the captured launches)
+            scratch = torch.rand(1 << 16, device=DEV)
+            assert float((scratch * 2).sum().item()) > 0
