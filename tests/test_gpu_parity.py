@@ -102,6 +102,11 @@ ATTN_CASES = {
     "d16_bf16_perhead": (dict(B=2, Hq=4, Hkv=2, D=16, E=4, S=1030, k=2, dtype="bf16", per_head_routing=True), "ragged"),
     "k_equals_E": (dict(B=1, Hq=4, Hkv=4, D=64, E=4, S=129, k=4, dtype="bf16"), "ragged"),
     "one_slot": (dict(B=1, Hq=2, Hkv=2, D=64, E=2, S=1, k=2, dtype="bf16"), "full"),
+    # the limits: longest shards, most query heads, most experts
+    "long_shard_70k": (dict(B=1, Hq=4, Hkv=2, D=128, E=2, S=70000, k=2, dtype="bf16"), "ragged"),
+    "long_shard_g1_40k": (dict(B=1, Hq=2, Hkv=2, D=64, E=2, S=40000, k=1, dtype="bf16"), "full"),
+    "hq256": (dict(B=1, Hq=256, Hkv=32, D=64, E=2, S=64, k=2, dtype="bf16"), "ragged"),
+    "e64_k64": (dict(B=1, Hq=2, Hkv=2, D=32, E=64, S=40, k=64, dtype="bf16"), "ragged"),
 }
 
 
