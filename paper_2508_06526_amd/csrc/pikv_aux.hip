@@ -21,8 +21,14 @@ __global__ __launch_bounds__(kWave) void router_penalty(int mode, const int32_t 
                                                         int32_t *load, const int32_t *miss, float coef,
                                                         float *bias) {
     const int e = threadIdx.x;
+    // lane e counts the selections equal to e: 64 ids per load, each then passed to every lane
+    // through the scalar unit (one round trip per 64 selections instead of one per selection)
     int cnt = 0;
-    for (int i = 0; i < n_sel; ++i) cnt += (topk[i] == e);
+    for (int base = 0; base < n_sel; base += kWave) {
+        const int mine_sel = base + e < n_sel ? topk[base + e] : -1;
+#pragma unroll
+        for (int s = 0; s < kWave; ++s) cnt += (__builtin_amdgcn_readlane(mine_sel, s) == e);
+    }
     int mine = 0;
     if (e < E) {
         mine = load[e] + cnt;
