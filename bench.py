@@ -33,7 +33,7 @@ HBM_PEAK_GBS = 8000.0
 CPU_BASELINE_SECONDS = 10.0   # how long the oracle leg keeps repeating its sample
 
 MEASURED_TRAFFIC = {
-    "c3_long_context": {"bytes_per_launch": int((128.21 + 5.59) * 2 ** 20),
+    "c3_long_context": {"bytes_per_launch": int((128.15 + 5.52) * 2 ** 20),
                         "source": "profiles/c3_long_context_hbm_traffic_pmc.txt"},
     "c2_bf16_decode": {"bytes_per_launch": int((1024.39 + 8.53) * 2 ** 20),
                        "source": "profiles/c2_bf16_decode_hbm_traffic_pmc.txt"},
