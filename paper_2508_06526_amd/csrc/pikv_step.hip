@@ -11,6 +11,10 @@
 //   step_post  : merge of the split partials with the router gates and the utility update
 //                u <- decay * u + attention mass (Section 3.4, Table 3 H2O), in one launch.
 //
+// With a scheduling policy (Table 3 rows SL, LRU, LRU+) step_pre takes its minimum over the
+// policy's value, computed on the fly from the per-entry stamps and counts, and stamps the
+// new entry; step_post marks the entries whose attention mass exceeds the access threshold.
+//
 // On MI355X even an empty kernel occupies the queue for ~1.5 us and each small kernel is a
 // chain of dependent memory round trips; six launches cost more in dispatch and latency than
 // in work next to a ~20 us attention pass.  The step is defined as exactly the sequence of
