@@ -35,4 +35,4 @@ extern "C" const char *pikv_strerror(int status) {
     }
 }
 
-extern "C" int pikv_version(void) { return 110; }
+extern "C" int pikv_version(void) { return 200; }
