@@ -190,6 +190,14 @@ int pikv_decode_step(const pikv_desc *desc, const void *q, const void *W_r, cons
                      float *y, float *row_max, float *row_norm, float *scores, float *slot_coef,
                      void *workspace, size_t workspace_bytes, void *stream);
 
+/* Section 3.2, Table 1 row B: the base round-robin router (no scores, O(1)).  The k selections
+ * of routed row r at step `step` are the experts ((step + r) * k + j) mod E, j = 0..k-1, gate
+ * 1/k each: consecutive (step, row) pairs take consecutive groups of k experts, so every
+ * expert is chosen equally often.  Outputs as pikv_route (topk_idx [rows,k], gates [rows,k]).
+ * Errors: INVALID for rows < 0, E not in 1..64, k not in 1..E, step < 0, null outputs.       */
+int pikv_route_round_robin(int32_t rows, int32_t E, int32_t k, int64_t step, int32_t *topk_idx,
+                           float *gates, void *stream);
+
 /* Section 3.2, Table 1, column "Penalty Term": the additive per-expert term of the penalised
  * routers, kept on the device so that routing feeds back into itself without the host:
  *   PIKV_PENALTY_LOAD_BALANCE (row LB):  bias_e = -coef * (load_e - mean_e' load_e')

@@ -548,3 +548,19 @@ int pikv_oracle_policy_compact(int B, int E, int S, const int32_t *evicted_idx,
     return 0;
 }
 
+/* Section 3.2, Table 1 row B (base round-robin router, no scores): the k selections of
+ * routed row r at step t are the experts ((t + r) * k + j) mod E, j = 0..k-1, each with
+ * gate 1/k - consecutive (step, row) pairs take consecutive groups of k experts, so over
+ * any E consecutive pairs every expert is chosen exactly k times.                        */
+int pikv_oracle_route_round_robin(int rows, int E, int k, int64_t step, int32_t *topk_idx,
+                                  float *gates) {
+    if (rows < 0 || E < 1 || k < 1 || k > E || step < 0) return -1;
+    for (int r = 0; r < rows; ++r) {
+        for (int j = 0; j < k; ++j) {
+            topk_idx[(int64_t)r * k + j] = (int32_t)(((step + r) * k + j) % E);
+            gates[(int64_t)r * k + j] = (float)(1.0 / (double)k);
+        }
+    }
+    return 0;
+}
+

@@ -42,7 +42,7 @@ def lib():
         for name in ("pikv_oracle_route", "pikv_oracle_attend", "pikv_oracle_evict",
                      "pikv_oracle_append", "pikv_oracle_router_penalty", "pikv_oracle_compress",
                      "pikv_oracle_policy_stamp", "pikv_oracle_policy_access",
-                     "pikv_oracle_policy_utility", "pikv_oracle_policy_compact"):
+                     "pikv_oracle_policy_utility", "pikv_oracle_policy_compact", "pikv_oracle_route_round_robin"):
             getattr(_lib, name).restype = C.c_int
     return _lib
 
@@ -299,4 +299,14 @@ def policy_compact(evicted_idx, evicted_cnt, n_valid, birth, last_access, freq):
                                           _ptr(n_valid), _ptr(birth), _ptr(last_access), _ptr(freq))
     if rc:
         raise ValueError("pikv_oracle_policy_compact failed: %d" % rc)
+
+
+def route_round_robin(rows, E, k, step):
+    """Table 1 row B: idx int32 [rows,k], gates f32 [rows,k] of the score-free round-robin router."""
+    idx = np.zeros((rows, k), np.int32)
+    gates = np.zeros((rows, k), np.float32)
+    rc = lib().pikv_oracle_route_round_robin(rows, E, k, C.c_int64(step), _ptr(idx), _ptr(gates))
+    if rc:
+        raise ValueError("pikv_oracle_route_round_robin failed: %d" % rc)
+    return idx, gates
 

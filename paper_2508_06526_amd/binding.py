@@ -20,7 +20,7 @@ POLICY_H2O, POLICY_SL, POLICY_LRU, POLICY_LRU_PLUS = 0, 1, 2, 3
 EXPORTS = ("pikv_route", "pikv_attn_workspace_bytes", "pikv_sharded_attn", "pikv_update_utility",
            "pikv_evict", "pikv_append", "pikv_strerror", "pikv_version", "pikv_set_attn_split", "pikv_decode_step",
            "pikv_set_profile_events", "pikv_router_penalty", "pikv_compress", "pikv_policy_stamp",
-           "pikv_update_utility_tracked", "pikv_policy_utility", "pikv_policy_compact", "pikv_decode_step_policy")
+           "pikv_update_utility_tracked", "pikv_policy_utility", "pikv_policy_compact", "pikv_decode_step_policy", "pikv_route_round_robin")
 
 
 class PikvError(RuntimeError):
@@ -75,6 +75,8 @@ def load_library():
     lib.pikv_policy_utility.restype = C.c_int
     lib.pikv_policy_compact.argtypes = [dp, vp, vp, i32, vp, vp, vp, vp, vp]
     lib.pikv_policy_compact.restype = C.c_int
+    lib.pikv_route_round_robin.argtypes = [i32, i32, i32, C.c_int64, vp, vp, vp]
+    lib.pikv_route_round_robin.restype = C.c_int
     lib.pikv_evict.argtypes = [dp, vp, vp, i32, vp, i32, vp, vp, i32, i32, vp, vp, vp]
     lib.pikv_evict.restype = C.c_int
     lib.pikv_append.argtypes = [dp, vp, vp, vp, i32, vp, vp, i32, vp, vp, vp, vp, vp]
@@ -305,4 +307,9 @@ def pikv_decode_step_policy(desc, q, W_r, bias, K_new, V_new, K_shards, V_shards
         _p(workspace), workspace.numel() * workspace.element_size(), _stream(stream),
         None if policy_args is None else C.cast(C.pointer(policy_args), C.c_void_p))
     _check(st, "pikv_decode_step_policy")
+
+
+def pikv_route_round_robin(rows, E, k, step, topk_idx, gates, stream=None):
+    st = load_library().pikv_route_round_robin(rows, E, k, int(step), _p(topk_idx), _p(gates), _stream(stream))
+    _check(st, "pikv_route_round_robin")
 

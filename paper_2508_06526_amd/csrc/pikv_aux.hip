@@ -46,6 +46,16 @@ __global__ __launch_bounds__(kWave) void router_penalty(int mode, const int32_t 
     }
 }
 
+// Table 1 row B: the score-free round-robin router.  One thread per (routed row, position).
+__global__ __launch_bounds__(256) void route_round_robin(int n, int E, int k, long long step, int32_t *topk,
+                                                         float *gates) {
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= n) return;
+    const int r = i / k, j = i - r * k;
+    topk[i] = (int32_t)(((step + r) * k + j) % E);
+    gates[i] = 1.0f / (float)k;
+}
+
 typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 typedef float f32x2_t __attribute__((ext_vector_type(2)));
 
@@ -137,3 +147,16 @@ extern "C" int pikv_compress(const pikv_desc *desc, const void *K_full, const vo
                            static_cast<bf16 *>(V_codes), desc->Hkv, desc->D, desc->rank);
     return launch_status();
 }
+
+extern "C" int pikv_route_round_robin(int32_t rows, int32_t E, int32_t k, int64_t step,
+                                      int32_t *topk_idx, float *gates, void *stream) {
+    if (rows < 0 || E < 1 || E > 64 || k < 1 || k > E || step < 0) return PIKV_ERR_INVALID;
+    if (!topk_idx || !gates) return PIKV_ERR_INVALID;
+    if ((int64_t)rows * k > 0x7fffffff) return PIKV_ERR_UNSUPPORTED;
+    if (rows == 0) return PIKV_OK;
+    const int n = rows * k;
+    hipLaunchKernelGGL(route_round_robin, dim3((n + 255) / 256), dim3(256), 0, as_stream(stream), n, E, k,
+                       (long long)step, topk_idx, gates);
+    return launch_status();
+}
+

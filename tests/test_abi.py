@@ -129,6 +129,14 @@ def test_host_side_argument_errors_of_the_widened_entry_points(lib):
     assert step(desc=pk.make_desc(2, 4, 4, 64, 4, 256, dtype=1)) == UNSUPPORTED   # W_r rows of 8 bytes
     assert step(desc=pk.make_desc(0, 4, 4, 64, 8, 256, dtype=1)) == 0
 
+    rr = lib.pikv_route_round_robin
+    rr.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_int64, vp, vp, vp]
+    assert rr(2, 8, 9, 0, fake, fake, None) == INVALID
+    assert rr(2, 65, 2, 0, fake, fake, None) == INVALID
+    assert rr(2, 8, 2, -1, fake, fake, None) == INVALID
+    assert rr(2, 8, 2, 0, None, fake, None) == INVALID
+    assert rr(0, 8, 2, 0, fake, fake, None) == 0
+
     rp = lib.pikv_router_penalty
     assert rp(7, fake, 1, 2, 8, fake, None, 0.1, fake, None) == INVALID
     assert rp(0, fake, 1, 2, 8, None, None, 0.1, fake, None) == INVALID

@@ -77,6 +77,23 @@ def test_route_exact_ties_lower_index_first():
             np.testing.assert_allclose(t2n(tg), gates, rtol=2e-5)
 
 
+def test_round_robin_router_matches_oracle_and_feeds_attention():
+    g = wl.Geometry(B=5, Hq=4, Hkv=2, D=64, E=7, S=90, k=3, dtype="bf16")
+    case = wl.make_host_case(g, seed=17, n_valid="ragged")
+    dc = DeviceCase(case)
+    for step in (0, 4, 123456789):
+        pk.pikv_route_round_robin(g.B, g.E, g.k, step, dc.topk, dc.gates)
+        idx, gates = orc.route_round_robin(g.B, g.E, g.k, step)
+        np.testing.assert_array_equal(t2n(dc.topk), idx)
+        np.testing.assert_array_equal(t2n(dc.gates), gates)
+    ref = oracle_step(case, idx, gates, orc.COMBINE_LOCAL)
+    dc.attend(combine=pk.COMBINE_LOCAL)
+    ok, emax, l2 = y_tolerance_ok(t2n(dc.y), ref["y"], g.dtype)
+    assert ok, (emax, l2)
+    with pytest.raises(pk.PikvError):
+        pk.pikv_route_round_robin(g.B, g.E, g.E + 1, 0, dc.topk, dc.gates)
+
+
 # ------------------------------------------------------------------ attention
 ATTN_CASES = {
     # config 1 itself: per-head routing, fp32

@@ -61,6 +61,7 @@ MUTANTS = {
                                  "if (slot < 0 || slot >= S || n_valid[be] >= S) return -3;\n            birth"),
     "stamp_keeps_old_frequency": ("freq[be * S + slot] = 0;", ""),
     "policy_compact_skips_hole_test": ("if (g < cnt && gone[g] == i) { ++g; continue; }", "if (g < cnt && gone[g] == i) { ++g; }"),
+    "round_robin_ignores_k_stride": ("(int32_t)(((step + r) * k + j) % E);", "(int32_t)(((step + r) + j) % E);"),
     "empty_shard_counted_in_local_norm": ("if (Z[j] > 0.0) norm += gsel ? (double)gsel[j] : 1.0;",
                                           "norm += gsel ? (double)gsel[j] : 1.0;"),
 }

@@ -870,3 +870,21 @@ def test_policy_arrays_follow_a_compacting_eviction():
                 assert (birth[b, e, i], last[b, e, i], freq[b, e, i]) == (tag, tag + 1000, tag + 2000)
     assert (ecnt == np.maximum(n - cap, 0)).all()
 
+
+def test_round_robin_router_is_exactly_balanced_and_selects_distinct_experts():
+    """Table 1 row B: over any E consecutive (step, row) pairs every expert is taken k times; the k
+    selections of one row are distinct; gates are uniform; routed attention accepts the result."""
+    E, k, rows = 7, 3, 2
+    counts = np.zeros(E, int)
+    for step in range(100, 100 + E):
+        idx, gates = orc.route_round_robin(rows, E, k, step)
+        assert idx.shape == (rows, k) and (gates == np.float32(1.0 / k)).all()
+        for r in range(rows):
+            assert len(set(idx[r])) == k and idx[r].min() >= 0 and idx[r].max() < E
+        counts += np.bincount(idx[0], minlength=E)
+    assert (counts == k).all()
+    a, _ = orc.route_round_robin(3, E, k, 5)
+    b, _ = orc.route_round_robin(3, E, k, 6)
+    np.testing.assert_array_equal(a[1:], b[:2])          # row r at step t = row r-1 at step t+1
+    assert list(a[0]) == [(5 * k + j) % E for j in range(k)]
+
