@@ -63,9 +63,10 @@ def parse_args():
                     help="sanity ratio: override the configuration's k (k = E is dense attention)")
     ap.add_argument("--rank", type=int, default=-1,
                     help="sanity ratio: override the configuration's code rank (0 = full-width K/V)")
-    ap.add_argument("--histogram", type=int, default=0, metavar="N",
+    ap.add_argument("--histogram", type=int, default=-1, metavar="N",
                     help="route N random queries through layer 0's router and print the empirical "
-                         "expert popularity to stderr")
+                         "expert popularity to stderr (default: 4096 for the workloads with a Zipf "
+                         "popularity law, 0 = off)")
     ap.add_argument("--policy", choices=["none", "lru", "lru_plus", "sl"], default="none",
                     help="widened row: evict by a Table 3 bookkeeping policy inside the fused step "
                          "(pikv_decode_step_policy) and keep the access stamps and counts up to date")
@@ -303,8 +304,9 @@ def main():
                       Wenc_V=(rn(geo.Hkv, geo.rank, geo.D) / geo.D ** 0.5).to(tdt))
     layers = [Layer(pk, torch, geo, t, shared) for t in raw]
     torch.cuda.synchronize()
-    if args.histogram > 0:
-        expert_histogram(pk, torch, geo, raw[0], args.histogram, dev)
+    n_hist = args.histogram if args.histogram >= 0 else (4096 if "zipf_s" in RECIPE[args.config] else 0)
+    if n_hist > 0:
+        expert_histogram(pk, torch, geo, raw[0], n_hist, dev)
 
     stream = torch.cuda.Stream()          # default priority; all library calls go here
     K, W = args.steps, args.warmup
