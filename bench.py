@@ -12,7 +12,10 @@ heads over 8 KV heads, D=128, E=16 shards x 8192 tokens, top-k=4, bf16).  One st
 128 MiB of K/V, which would fit the 256 MB Infinity Cache, so the steps cycle round-robin
 over 32 independent layer instances (16 GiB), as a 32-layer model does for every token.
 
-Prints ONE JSON line (see README for the fields).
+Prints ONE JSON line: `value` = queries/s over the timed steps (B x steps / elapsed), `roofline` =
+the split attention pass against the 8 TB/s HBM peak (algorithmic K/V bytes per launch over its
+average duration, taken with a HIP event pair around that kernel), `cpu_baseline` = the CPU
+oracle on a bounded sample of the same workload.
 """
 from __future__ import annotations
 
