@@ -13,15 +13,18 @@ heads over 8 KV heads, D=128, E=16 shards x 8192 tokens, top-k=4, bf16).  One st
 over 32 independent layer instances (16 GiB), as a 32-layer model does for every token.
 
 Prints ONE JSON line: `value` = queries/s over the timed steps (B x steps / elapsed), `roofline` =
-the split attention pass against the 8 TB/s HBM peak (algorithmic K/V bytes per launch over its
-average duration, taken with a HIP event pair around that kernel), `cpu_baseline` = the CPU
-oracle on a bounded sample of the same workload.
+the attention pass against the 8 TB/s HBM peak: `frac` uses the kernel's average duration from
+the committed rocprofv3 kernel trace of this same command (profiles/), the live HIP-event
+figures of this run are printed beside it; `cpu_baseline` = the CPU oracle on a bounded sample
+of the same workload; `other_workloads` = one short line per remaining workload.
 """
 from __future__ import annotations
 
 import argparse
+import gc
 import json
 import os
+import re
 import sys
 import time
 
@@ -29,17 +32,15 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+CPU_BASELINE_SECONDS = 10.0   # how long the oracle leg keeps repeating its sample
+MIN_PROBE_STEPS = 256         # eager steps with the event pair around the attention pass
 
 # HBM bytes per launch of the dominant kernel as measured by rocprofv3 --pmc FETCH_SIZE /
 # WRITE_SIZE (two runs, scaled by what a plain 1 GiB device copy reads on the same counters);
 # the numbers and the commands are in the named files under profiles/.
-CPU_BASELINE_SECONDS = 10.0   # how long the oracle leg keeps repeating its sample
-
-MEASURED_TRAFFIC = {
-    "c3_long_context": {"bytes_per_launch": int((128.15 + 5.52) * 2 ** 20),
-                        "source": "profiles/c3_long_context_hbm_traffic_pmc.txt"},
-    "c2_bf16_decode": {"bytes_per_launch": int((1024.39 + 8.53) * 2 ** 20),
-                       "source": "profiles/c2_bf16_decode_hbm_traffic_pmc.txt"},
+TRAFFIC_FILES = {
+    "c3_long_context": "profiles/c3_long_context_hbm_traffic_pmc.txt",
+    "c2_bf16_decode": "profiles/c2_bf16_decode_hbm_traffic_pmc.txt",
 }
 
 
@@ -52,9 +53,11 @@ def parse_args():
     ap.add_argument("--layers", type=int, default=0, help="layer instances cycled (0: per config)")
     ap.add_argument("--mode", choices=["graph", "eager"], default="graph")
     ap.add_argument("--api", choices=["fused", "separate"], default="fused",
-                    help="fused: pikv_decode_step (3 launches); separate: the five calls (6 launches)")
+                    help="fused: pikv_decode_step (3 launches); separate: the five calls (7 launches)")
     ap.add_argument("--cpu-steps", type=int, default=-1, help="oracle steps timed (0: skip, -1: auto)")
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--no-others", action="store_true",
+                    help="skip the short runs of the other workloads (key other_workloads)")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--balance", action="store_true",
                     help="widened row: keep the load-balance router penalty on the device and feed "
@@ -91,6 +94,7 @@ RECIPE = {  # how each configuration's inputs are drawn (workloads.make_device_l
     "c3_long_context_tq4": dict(zipf_s=1.1, w_sigma=0.01),
 }
 DECAY = {"c4_streaming": 0.9}
+OTHER_WORKLOADS = ("c2_bf16_decode", "c4_streaming", "c5_compressed")
 
 
 class Layer:
@@ -144,15 +148,11 @@ class Layer:
                           s["ecnt"], 1, False, None, None)
             pk.pikv_append(self.desc, s["K_new"], s["V_new"], s["topk"], g.k, s["eidx"], s["ecnt"], 1,
                            self.K_tab, self.V_tab, t["utility"], t["n_valid"])
-        self.attend()
-        pk.pikv_update_utility(self.desc, s["scores"], s["slot_coef"], t["n_valid"], s["topk"], g.k,
-                               self.decay, t["utility"])
-
-    def attend(self):
-        pk, g, t, s = self.pk, self.geo, self.t, self.sh
         pk.pikv_sharded_attn(self.desc, t["q"], self.K_tab, self.V_tab, t["U_K"], t["U_V"],
                              t["n_valid"], s["topk"], s["gates"], g.k, pk.COMBINE_LSE, 0.0, s["y"],
                              s["row_max"], s["row_norm"], s["scores"], s["slot_coef"], s["workspace"])
+        pk.pikv_update_utility(self.desc, s["scores"], s["slot_coef"], t["n_valid"], s["topk"], g.k,
+                               self.decay, t["utility"])
 
 
 def make_shared(pk, torch, geo, dev):
@@ -184,7 +184,33 @@ def attn_kernel_name(geo):
     if geo.dtype == "bf16" and geo.rank == 0 and geo.D == 128 and not geo.per_head_routing and 2 <= g <= 16:
         return "attn_partial_gqa128"
     gb = g if (not geo.per_head_routing and g in (2, 4, 8)) else 1
-    return "attn_partial<%s, %d, %d>" % ("float" if geo.dtype == "f32" else "bf16", geo.width, gb)
+    return "attn_partial<%s, %d, %d>" % ("pikv::bf16" if geo.dtype == "bf16" else "float", geo.width, gb)
+
+
+def profile_summary(config, kernel):
+    """Average duration (ns) of `kernel` in the committed rocprofv3 kernel-trace summary of this
+    workload (profiles/<config>_kernel_stats.txt: a table `name calls avg_ns min_ns max_ns pct`)."""
+    path = os.path.join(ROOT, "profiles", "%s_kernel_stats.txt" % config)
+    if not os.path.exists(path):
+        return None, None
+    key = re.sub(r"[^A-Za-z0-9_]", "", kernel)
+    for line in open(path):
+        m = re.match(r"^(.*\S)\s+(\d+)\s+(\d+)\s+(\d+)\s+(\d+)\s+[\d.]+\s*$", line)
+        if m and key in re.sub(r"[^A-Za-z0-9_]", "", m.group(1)):
+            return float(m.group(3)), os.path.relpath(path, ROOT)
+    return None, os.path.relpath(path, ROOT)
+
+
+def measured_traffic(config):
+    """(bytes per launch, file) from the committed FETCH_SIZE / WRITE_SIZE summary, if any."""
+    rel = TRAFFIC_FILES.get(config)
+    if not rel or not os.path.exists(os.path.join(ROOT, rel)):
+        return None, None
+    for line in open(os.path.join(ROOT, rel)):
+        m = re.match(r"^\s*traffic_bytes_per_launch\s*[:=]\s*(\d+)", line)
+        if m:
+            return int(m.group(1)), rel
+    return None, rel
 
 
 def cpu_baseline(torch, wl, layers, n_steps):
@@ -250,6 +276,189 @@ def expert_histogram(pk, torch, geo, t, n_queries, dev):
               (r + 1, e, counts[e] / total, top1[e] / float(n_queries)), file=sys.stderr)
 
 
+class StepRunner:
+    """Enqueues steps round-robin over the layer instances on one stream of default priority;
+    the same code runs eagerly and under graph capture."""
+
+    def __init__(self, torch, layers):
+        self.torch, self.layers = torch, layers
+        self.main = torch.cuda.Stream()
+
+    def run(self, i):
+        with self.torch.cuda.stream(self.main):
+            self.layers[i % len(self.layers)].step()
+
+    def synchronize(self):
+        self.main.synchronize()
+
+
+def measure(args, config, steps, warmup, with_cpu, probe_steps, quiet=False):
+    """Build the workload, time `steps` steps, time the attention pass; returns the result dict."""
+    import torch
+    import paper_2508_06526_amd as pk
+    import workloads as wl
+
+    dev = torch.device("cuda:0")
+    geo = wl.CONFIGS[config]
+    if args.k > 0 or args.rank >= 0:
+        import dataclasses
+        geo = dataclasses.replace(geo, k=args.k if args.k > 0 else geo.k,
+                                  rank=args.rank if args.rank >= 0 else geo.rank)
+    n_layers = args.layers or DEFAULT_LAYERS[config]
+    raw = wl.make_device_layers(geo, n_layers, args.seed, dev, **RECIPE[config])
+    shared = [make_shared(pk, torch, geo, dev)]
+    for s in shared:
+        s["fused"] = args.api == "fused"
+    if args.balance:
+        for s in shared:
+            s["balance"] = True
+        for t in raw:
+            t["load"] = torch.zeros(geo.E, device=dev, dtype=torch.int32)
+            t["bias"] = torch.zeros(geo.E, device=dev)
+    if args.policy != "none":
+        for s in shared:
+            s["policy"] = {"lru": pk.POLICY_LRU, "lru_plus": pk.POLICY_LRU_PLUS, "sl": pk.POLICY_SL}[args.policy]
+        for t in raw:
+            t["birth"] = torch.randint(0, 1000, (geo.B, geo.E, geo.S), device=dev, dtype=torch.int32)
+            t["last_access"] = torch.randint(0, 1000, (geo.B, geo.E, geo.S), device=dev, dtype=torch.int32)
+            t["freq"] = torch.randint(0, 50, (geo.B, geo.E, geo.S), device=dev, dtype=torch.int32)
+    if args.compress and geo.rank:
+        tdt = torch.bfloat16 if geo.dtype == "bf16" else torch.float32
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(777)
+        rn = lambda *sh: torch.randn(*sh, device=dev, generator=gen)
+        extra = dict(compress=True,
+                     K_full=rn(geo.B, geo.Hkv, geo.D).to(tdt), V_full=rn(geo.B, geo.Hkv, geo.D).to(tdt),
+                     Wenc_K=(rn(geo.Hkv, geo.rank, geo.D) / geo.D ** 0.5).to(tdt),
+                     Wenc_V=(rn(geo.Hkv, geo.rank, geo.D) / geo.D ** 0.5).to(tdt))
+        for s in shared:
+            s.update(extra)
+    layers = [Layer(pk, torch, geo, t, shared[0]) for t in raw]
+    torch.cuda.synchronize()
+    n_hist = args.histogram if args.histogram >= 0 else (4096 if "zipf_s" in RECIPE[config] else 0)
+    if n_hist > 0 and not quiet:
+        expert_histogram(pk, torch, geo, raw[0], n_hist, dev)
+
+    run = StepRunner(torch, layers)
+    K, W = steps, warmup
+    for i in range(W):
+        run.run(i)
+    run.synchronize()
+    # The graph holds one round over the layer instances, or fewer steps if fewer are asked for;
+    # steps that do not fill a whole replay are launched one by one (both counts are reported).
+    graph, per_replay = None, 0
+    if args.mode == "graph":
+        per_replay = min(n_layers, K)
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=run.main):
+            for i in range(per_replay):
+                run.run(i)
+        graph.replay()                 # one untimed replay
+        run.main.synchronize()
+
+    # ---- timed region: exactly K steps
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    replays = K // per_replay if graph is not None else 0
+    with torch.cuda.stream(run.main):
+        for _ in range(replays):
+            graph.replay()
+    for i in range(replays * per_replay, K):
+        run.run(i)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    eager_steps = K - replays * per_replay
+
+    # ---- dominant kernel (the attention pass that streams the K/V bytes): the library records
+    # a HIP event pair on the launch stream right around that kernel's launch
+    # (pikv_set_profile_events), inside the same steps as above, launched eagerly; the GPU work
+    # per step is longer than the launch work, so the queue stays ahead of the GPU
+    n_probe = probe_steps
+    ev, ev_empty = [], []
+    with torch.cuda.stream(run.main):
+        for _ in range(n_probe):
+            quad = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+            for x in quad:
+                x.record(run.main)
+            ev.append((quad[0], quad[1]))
+            ev_empty.append((quad[2], quad[3]))
+    for i in range(64):                      # refill the queue after the event creation
+        run.run(i)
+    for i in range(n_probe):
+        pk.pikv_set_profile_events(ev[i][0], ev[i][1])
+        run.run(i)
+        # an event pair with nothing in between, in the same stream position: what the two
+        # marker packets themselves cost
+        ev_empty[i][0].record(run.main)
+        ev_empty[i][1].record(run.main)
+    pk.pikv_set_profile_events(None, None)
+    run.synchronize()
+    raw_ms = sorted(a.elapsed_time(b2) for a, b2 in ev)
+    empty_ms = sorted(a.elapsed_time(b2) for a, b2 in ev_empty)
+    raw_avg_ms = sum(raw_ms) / len(raw_ms)
+    empty_avg_ms = sum(empty_ms) / len(empty_ms)
+    net_avg_ms = raw_avg_ms - empty_avg_ms
+
+    ms_per_step = elapsed * 1e3 / K
+    qps = geo.B * geo.tq * K / elapsed
+    n_mean = float(torch.stack([L.t["n_valid"].float().mean() for L in layers]).mean().item())
+    kv_bytes = geo.kv_bytes_per_step(n_mean)
+    gbps = lambda ms: kv_bytes / (ms * 1e-3) / 1e9
+    kernel = attn_kernel_name(geo)
+    prof_ns, prof_file = profile_summary(config, kernel) if not (args.k > 0 or args.rank >= 0) else (None, None)
+    if prof_ns is not None:
+        avg_ms, basis = prof_ns * 1e-6, "rocprofv3 kernel trace of this command, " + prof_file
+    else:
+        avg_ms, basis = raw_avg_ms, "uncorrected HIP event pair of this run (no kernel-trace summary for this workload)"
+    traffic, traffic_file = measured_traffic(config)
+    out = {
+        "metric": "routed sharded-KV decode queries/sec", "value": qps, "unit": "queries/s",
+        "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if geo.dtype == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": config, "B": geo.B, "Hq": geo.Hq, "Hkv": geo.Hkv, "D": geo.D,
+                   "E": geo.E, "S": geo.S, "k": geo.k, "rank": geo.rank,
+                   "overrides": {"k": args.k or None, "rank": args.rank if args.rank >= 0 else None},
+                   "queries_per_sequence": geo.tq, "layers_cycled": n_layers,
+                   "launch": {"mode": args.mode, "graph_replays": replays, "steps_per_replay": per_replay,
+                              "steps_in_replays": replays * per_replay, "steps_launched_eagerly": eager_steps},
+                   "timed_region_s": elapsed,
+                   "api": args.api, "balance": bool(args.balance),
+                   "compress_on_insert": bool(args.compress and geo.rank), "policy": args.policy,
+                   "step": "route+evict1+append+attend+utility"},
+        "step_effective_GBps": gbps(ms_per_step),
+        "step_frac_of_hbm_peak": gbps(ms_per_step) / HBM_PEAK_GBS,
+        "roofline": {"bound": "hbm", "kernel": kernel,
+                     "achieved": gbps(avg_ms), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": gbps(avg_ms) / HBM_PEAK_GBS,
+                     "traffic": traffic, "traffic_source": traffic_file,
+                     "bytes_per_launch": kv_bytes, "avg_ms": avg_ms, "avg_ms_basis": basis,
+                     "profile_avg_ms": None if prof_ns is None else prof_ns * 1e-6,
+                     "frac_profile": None if prof_ns is None else gbps(prof_ns * 1e-6) / HBM_PEAK_GBS,
+                     "live": {"event_pair_raw_avg_ms": raw_avg_ms,
+                              "frac_event_pair_raw": gbps(raw_avg_ms) / HBM_PEAK_GBS,
+                              "empty_event_pair_avg_ms": empty_avg_ms,
+                              "event_pair_minus_empty_avg_ms": net_avg_ms,
+                              "frac_event_pair_minus_empty": gbps(net_avg_ms) / HBM_PEAK_GBS,
+                              "median_raw_ms": raw_ms[len(raw_ms) // 2], "probe_steps": n_probe,
+                              "timed_with": "HIP event pair recorded by the library on the launch stream "
+                                            "around the kernel, in eager steps of this run"}},
+    }
+    if with_cpu:
+        n_cpu = args.cpu_steps if args.cpu_steps > 0 else min(n_layers, 8)
+        per_step, n_done, secs = cpu_baseline(torch, wl, layers, n_cpu)
+        out["cpu_baseline"] = {"value": geo.B * geo.tq / per_step, "unit": "queries/s",
+                               "cores": int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1)),
+                               "kind": "oracle",
+                               "sample": "%d steps of %s (%d layer instances, repeated for %.1f s): "
+                                         "route+attend+utility, selected shards copied to host"
+                                         % (n_done, config, min(n_cpu, n_layers), secs)}
+    del layers, raw, shared, run, graph
+    gc.collect()
+    torch.cuda.empty_cache()
+    return out
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -258,7 +467,6 @@ def main():
         sys.exit(2)
     import torch
     import paper_2508_06526_amd as pk
-    import workloads as wl
 
     if not torch.cuda.is_available():
         print("bench.py needs a GPU (no CPU fallback exists)", file=sys.stderr)
@@ -276,138 +484,22 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"calibrate_copy_bytes_read": n, "calibrate_copy_bytes_written": n, "launches": 8}))
         return
-    geo = wl.CONFIGS[args.config]
-    if args.k > 0 or args.rank >= 0:
-        import dataclasses
-        geo = dataclasses.replace(geo, k=args.k if args.k > 0 else geo.k,
-                                  rank=args.rank if args.rank >= 0 else geo.rank)
-    n_layers = args.layers or DEFAULT_LAYERS[args.config]
-    raw = wl.make_device_layers(geo, n_layers, args.seed, dev, **RECIPE[args.config])
-    shared = make_shared(pk, torch, geo, dev)
-    shared["fused"] = args.api == "fused"
-    if args.balance:
-        shared["balance"] = True
-        for t in raw:
-            t["load"] = torch.zeros(geo.E, device=dev, dtype=torch.int32)
-            t["bias"] = torch.zeros(geo.E, device=dev)
-    if args.policy != "none":
-        shared["policy"] = {"lru": pk.POLICY_LRU, "lru_plus": pk.POLICY_LRU_PLUS, "sl": pk.POLICY_SL}[args.policy]
-        for t in raw:
-            t["birth"] = torch.randint(0, 1000, (geo.B, geo.E, geo.S), device=dev, dtype=torch.int32)
-            t["last_access"] = torch.randint(0, 1000, (geo.B, geo.E, geo.S), device=dev, dtype=torch.int32)
-            t["freq"] = torch.randint(0, 50, (geo.B, geo.E, geo.S), device=dev, dtype=torch.int32)
-    if args.compress and geo.rank:
-        tdt = torch.bfloat16 if geo.dtype == "bf16" else torch.float32
-        gen = torch.Generator(device=dev)
-        gen.manual_seed(777)
-        rn = lambda *sh: torch.randn(*sh, device=dev, generator=gen)
-        shared.update(compress=True,
-                      K_full=rn(geo.B, geo.Hkv, geo.D).to(tdt), V_full=rn(geo.B, geo.Hkv, geo.D).to(tdt),
-                      Wenc_K=(rn(geo.Hkv, geo.rank, geo.D) / geo.D ** 0.5).to(tdt),
-                      Wenc_V=(rn(geo.Hkv, geo.rank, geo.D) / geo.D ** 0.5).to(tdt))
-    layers = [Layer(pk, torch, geo, t, shared) for t in raw]
-    torch.cuda.synchronize()
-    n_hist = args.histogram if args.histogram >= 0 else (4096 if "zipf_s" in RECIPE[args.config] else 0)
-    if n_hist > 0:
-        expert_histogram(pk, torch, geo, raw[0], n_hist, dev)
-
-    stream = torch.cuda.Stream()          # default priority; all library calls go here
-    K, W = args.steps, args.warmup
-    with torch.cuda.stream(stream):
-        for i in range(W):
-            layers[i % n_layers].step()
-        stream.synchronize()
-        graph = None
-        if args.mode == "graph":
-            graph = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(graph, stream=stream):
-                for L in layers:
-                    L.step()
-            graph.replay()                 # one untimed replay
-            stream.synchronize()
-
-        # ---- timed region: exactly K steps
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        done = 0
-        if graph is not None:
-            for _ in range(K // n_layers):
-                graph.replay()
-            done = (K // n_layers) * n_layers
-        for i in range(done, K):
-            layers[i % n_layers].step()
-        torch.cuda.synchronize()
-        elapsed = time.perf_counter() - t0
-
-        # ---- dominant kernel (the split attention pass that streams the K/V bytes): the
-        # library records a HIP event pair on this stream right around that kernel's launch
-        # (pikv_set_profile_events), inside the same steps as above, launched eagerly; the GPU
-        # work per step is longer than the launch work, so the queue stays ahead of the GPU
-        n_probe = min(K, 512)
-        ev, ev_empty = [], []
-        for _ in range(n_probe):
-            quad = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
-            for x in quad:
-                x.record(stream)
-            ev.append((quad[0], quad[1]))
-            ev_empty.append((quad[2], quad[3]))
-        for i in range(64):                      # refill the queue after the event creation
-            layers[i % n_layers].step()
-        for i in range(n_probe):
-            pk.pikv_set_profile_events(ev[i][0], ev[i][1])
-            layers[i % n_layers].step()
-            # an event pair with nothing in between, in the same stream position: what the two
-            # marker packets themselves cost
-            ev_empty[i][0].record(stream)
-            ev_empty[i][1].record(stream)
-        pk.pikv_set_profile_events(None, None)
-        stream.synchronize()
-        raw_ms = sorted(a.elapsed_time(b2) for a, b2 in ev)
-        empty_ms = sorted(a.elapsed_time(b2) for a, b2 in ev_empty)
-        raw_avg_ms = sum(raw_ms) / len(raw_ms)
-        empty_avg_ms = sum(empty_ms) / len(empty_ms)
-        attn_avg_ms = raw_avg_ms - empty_avg_ms
-        attn_ms = [x - empty_avg_ms for x in raw_ms]
-
-    ms_per_step = elapsed * 1e3 / K
-    qps = geo.B * geo.tq * K / elapsed
-    n_mean = float(torch.stack([L.t["n_valid"].float().mean() for L in layers]).mean().item())
-    kv_bytes = geo.kv_bytes_per_step(n_mean)
-    achieved = kv_bytes / (attn_avg_ms * 1e-3) / 1e9
-    out = {
-        "metric": "routed sharded-KV decode queries/sec", "value": qps, "unit": "queries/s",
-        "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": ms_per_step,
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16" if geo.dtype == "bf16" else "f32", "data": "synthetic",
-        "config": {"workload": args.config, "B": geo.B, "Hq": geo.Hq, "Hkv": geo.Hkv, "D": geo.D,
-                   "E": geo.E, "S": geo.S, "k": geo.k, "rank": geo.rank,
-                   "overrides": {"k": args.k or None, "rank": args.rank if args.rank >= 0 else None}, "queries_per_sequence": geo.tq,
-                   "layers_cycled": n_layers,
-                   "launch": args.mode, "api": args.api, "balance": bool(args.balance),
-                   "compress_on_insert": bool(args.compress and geo.rank), "policy": args.policy,
-                   "step": "route+evict1+append+attend+utility"},
-        "step_effective_GBps": kv_bytes / (ms_per_step * 1e-3) / 1e9,
-        "step_frac_of_hbm_peak": kv_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
-        "roofline": {"bound": "hbm", "kernel": attn_kernel_name(geo),
-                     "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": MEASURED_TRAFFIC.get(args.config, {}).get("bytes_per_launch"),
-                     "traffic_source": MEASURED_TRAFFIC.get(args.config, {}).get("source"),
-                     "bytes_per_launch": kv_bytes, "avg_ms": attn_avg_ms,
-                     "median_ms": attn_ms[len(attn_ms) // 2],
-                     "event_pair_raw_avg_ms": raw_avg_ms, "empty_event_pair_avg_ms": empty_avg_ms,
-                     "timed_with": "HIP event pair recorded by the library around the kernel launch in "
-                                   "%d eager steps, minus the same run's empty event pair" % n_probe},
-    }
-    if not args.no_cpu and args.cpu_steps != 0:
-        n_cpu = args.cpu_steps if args.cpu_steps > 0 else min(n_layers, 8)
-        per_step, n_done, secs = cpu_baseline(torch, wl, layers, n_cpu)
-        out["cpu_baseline"] = {"value": geo.B * geo.tq / per_step, "unit": "queries/s",
-                               "cores": int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1)),
-                               "kind": "oracle",
-                               "sample": "%d steps of %s (%d layer instances, repeated for %.1f s): "
-                                         "route+attend+utility, selected shards copied to host"
-                                         % (n_done, args.config, min(n_cpu, n_layers), secs)}
+    with_cpu = not args.no_cpu and args.cpu_steps != 0
+    out = measure(args, args.config, args.steps, args.warmup, with_cpu,
+                  max(MIN_PROBE_STEPS, min(args.steps, 512)))
+    plain = not (args.balance or args.compress or args.policy != "none" or args.k > 0 or args.rank >= 0)
+    if not args.no_others and plain and args.config == "c3_long_context":
+        # the other workloads, briefly, in the same launch structure (their own lines, not `value`)
+        others = {}
+        for name in OTHER_WORKLOADS:
+            r = measure(args, name, 256, 32, False, 64, quiet=True)
+            rf = r["roofline"]
+            others[name] = {"step_us": r["ms_per_step"] * 1e3, "queries_per_s": r["value"],
+                            "step_frac_of_hbm_peak": r["step_frac_of_hbm_peak"],
+                            "kernel": rf["kernel"], "kernel_frac": rf["frac"], "kernel_avg_ms": rf["avg_ms"],
+                            "kernel_frac_basis": rf["avg_ms_basis"],
+                            "kernel_frac_event_pair_raw": rf["live"]["frac_event_pair_raw"], "steps": r["steps"]}
+        out["other_workloads"] = others
     print(json.dumps(out))
 
 

@@ -7,7 +7,9 @@
  *   - Every pointer argument is a DEVICE pointer unless the comment says "host".  The
  *     descriptor (pikv_desc) is a host struct passed by const pointer.
  *   - The caller owns every buffer.  The library allocates nothing, frees nothing and
- *     keeps no state between calls; scratch space is passed in as `workspace`.
+ *     keeps no state between calls; scratch space is passed in as `workspace`.  The only
+ *     exceptions are the two process-wide measurement hooks at the end of this file
+ *     (pikv_set_attn_split, pikv_set_profile_events), both off by default.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only
  *     enqueue work and return; they never synchronise.
  *   - Return value: a pikv_status.  Argument errors are detected on the host before
@@ -179,9 +181,11 @@ int pikv_append(const pikv_desc *desc, const void *K_new, const void *V_new,
  *   pikv_sharded_attn(...); pikv_update_utility(...);
  * with the same argument meanings.  K_new == V_new == NULL skips the evict/insert stage
  * (evicted_* may then be NULL).  evicted_idx is [B,E,1], evicted_cnt [B,E]; scores and
- * slot_coef are required.  Errors: as for the separate calls; UNSUPPORTED when
- * route_rows_per_seq != 1 or a row of W_r is not a power-of-two number of aligned 16-byte
- * chunks (E * sizeof(element) in {16,32,64,128,256}).                                      */
+ * slot_coef are required.  Errors: as for the separate calls, every one of them detected
+ * before the first launch (a rejected call leaves the cache untouched); INVALID while a
+ * profiling event pair is installed (pikv_set_profile_events) and `stream` is being captured
+ * into a graph; UNSUPPORTED when route_rows_per_seq != 1 or a row of W_r is not a power-of-two
+ * number of aligned 16-byte chunks (E * sizeof(element) in {16,32,64,128,256}).            */
 int pikv_decode_step(const pikv_desc *desc, const void *q, const void *W_r, const float *bias,
                      const void *K_new, const void *V_new, void *const *K_shards,
                      void *const *V_shards, const void *U_K, const void *U_V, int32_t *n_valid,
@@ -313,8 +317,9 @@ void pikv_set_attn_split(int32_t nsplit);
  * later pikv_sharded_attn / pikv_decode_step call records on its stream immediately before and
  * after launching the split attention pass - the kernel that streams the K/V bytes - so that a
  * caller can time exactly that kernel in its real context with hipEventElapsedTime.  NULL, NULL
- * switches it off (the default).  Process-wide, not thread-safe; do not leave it set while a
- * stream is being captured into a graph.                                                   */
+ * switches it off (the default).  Process-wide, not thread-safe.  While a pair is installed
+ * pikv_decode_step refuses (INVALID) a stream that is being captured into a graph: the records
+ * would replay with the graph.                                                             */
 void pikv_set_profile_events(void *start_event, void *stop_event);
 
 /* Static description of a status code (host string, never NULL).                          */

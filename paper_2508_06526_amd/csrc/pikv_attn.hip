@@ -741,14 +741,12 @@ extern "C" size_t pikv_attn_workspace_bytes(const pikv_desc *desc, int32_t k) {
 
 namespace pikv {
 
-// Validate, plan and launch the split pass only; fills the parameters of the merge pass.
-int launch_attn_partial(const pikv_desc *desc, const void *q, const void *const *K_shards,
-                        const void *const *V_shards, const void *U_K, const void *U_V,
-                        const int32_t *n_valid, const int32_t *topk_idx, const float *gates,
-                        int32_t k, int32_t combine, float scale, float *y, float *row_max,
-                        float *row_norm, float *scores, float *slot_coef, void *workspace,
-                        size_t workspace_bytes, void *stream, AttnPlan *plan_out,
-                        CombineParams *c_out) {
+// Every host-side check of the attention call and its split plan; launches nothing.
+int check_attn_args(const pikv_desc *desc, const void *q, const void *const *K_shards,
+                    const void *const *V_shards, const void *U_K, const void *U_V,
+                    const int32_t *n_valid, const int32_t *topk_idx, int32_t k, int32_t combine,
+                    float scale, const float *y, const void *workspace, size_t workspace_bytes,
+                    AttnPlan *plan_out) {
     AttnPlan plan;
     const int rc = make_attn_plan(desc, k, &plan);
     if (rc != PIKV_OK) return rc;
@@ -761,6 +759,26 @@ int launch_attn_partial(const pikv_desc *desc, const void *q, const void *const 
     const size_t need = pikv_attn_workspace_bytes(desc, k);
     if (!workspace || workspace_bytes < need) return PIKV_ERR_WORKSPACE;
     if (reinterpret_cast<uintptr_t>(workspace) % 256 != 0) return PIKV_ERR_INVALID;
+    if ((int64_t)desc->B * plan.head_blocks * k * plan.nsplit > 0x7fffffff) return PIKV_ERR_UNSUPPORTED;
+    return PIKV_OK;
+}
+
+bool profile_events_set() { return g_prof_start != nullptr || g_prof_stop != nullptr; }
+
+// Validate, plan and launch the split pass only; fills the parameters of the merge pass.
+int launch_attn_partial(const pikv_desc *desc, const void *q, const void *const *K_shards,
+                        const void *const *V_shards, const void *U_K, const void *U_V,
+                        const int32_t *n_valid, const int32_t *topk_idx, const float *gates,
+                        int32_t k, int32_t combine, float scale, float *y, float *row_max,
+                        float *row_norm, float *scores, float *slot_coef, void *workspace,
+                        size_t workspace_bytes, void *stream, AttnPlan *plan_out,
+                        CombineParams *c_out) {
+    AttnPlan plan;
+    const int rc = check_attn_args(desc, q, K_shards, V_shards, U_K, U_V, n_valid, topk_idx, k, combine,
+                                   scale, y, workspace, workspace_bytes, &plan);
+    if (rc != PIKV_OK) return rc;
+    *plan_out = plan;
+    if (desc->B == 0) return PIKV_OK;
 
     const int W = desc_width(desc);
     float *part_acc = static_cast<float *>(workspace);
@@ -794,7 +812,6 @@ int launch_attn_partial(const pikv_desc *desc, const void *q, const void *const 
     p.scale = scale > 0.0f ? scale : 1.0f / sqrtf((float)desc->D);
 
     const int64_t blocks64 = (int64_t)desc->B * plan.head_blocks * k * plan.nsplit;
-    if (blocks64 > 0x7fffffff) return PIKV_ERR_UNSUPPORTED;
     p.stream_scores = blocks64 > plan.resident_blocks;
     hipStream_t st = as_stream(stream);
     int lrc;

@@ -232,8 +232,19 @@ __device__ __forceinline__ void combine_head(const CombineParams &p, int bh, uns
     }
 }
 
-// Host side (pikv_attn.hip): validate, plan and launch the split pass only, and fill the
-// parameters of the merge pass.
+// Host side (pikv_attn.hip).  check_attn_args: every host-side check of the attention call and
+// its split plan, nothing launched - a caller with earlier launches of its own (the step's
+// routing / insert kernel) rejects bad arguments before anything is enqueued.
+int check_attn_args(const pikv_desc *desc, const void *q, const void *const *K_shards,
+                    const void *const *V_shards, const void *U_K, const void *U_V,
+                    const int32_t *n_valid, const int32_t *topk_idx, int32_t k, int32_t combine,
+                    float scale, const float *y, const void *workspace, size_t workspace_bytes,
+                    AttnPlan *plan_out);
+// True while a profiling event pair is installed (pikv_set_profile_events).
+bool profile_events_set();
+
+// launch_attn_partial: validate, plan and launch the split pass only, and fill the parameters
+// of the merge pass.
 int launch_attn_partial(const pikv_desc *desc, const void *q, const void *const *K_shards,
                         const void *const *V_shards, const void *U_K, const void *U_V,
                         const int32_t *n_valid, const int32_t *topk_idx, const float *gates,

@@ -361,8 +361,19 @@ static int decode_step(const pikv_desc *desc, const void *q, const void *W_r, co
     if (desc->route_rows_per_seq != 1) return PIKV_ERR_UNSUPPORTED;
     int cpr = 0;
     if (!route_vec_ok(W_r, desc->E, desc->dtype, &cpr)) return PIKV_ERR_UNSUPPORTED;
-    const size_t need = pikv_attn_workspace_bytes(desc, k);
-    if (!workspace || workspace_bytes < need) return PIKV_ERR_WORKSPACE;
+    // the attention pass's own checks come before the first launch as well: a rejected call
+    // leaves the cache (rows, utilities, entry counts, policy arrays) exactly as it was
+    AttnPlan checked;
+    const int arc = check_attn_args(desc, q, K_shards, V_shards, U_K, U_V, n_valid, topk_idx, k, combine,
+                                    scale, y, workspace, workspace_bytes, &checked);
+    if (arc != PIKV_OK) return arc;
+    hipStream_t st = as_stream(stream);
+    if (profile_events_set()) {
+        // an event record inside a captured graph would replay with every launch of the graph
+        hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+        if (hipStreamIsCapturing(st, &cs) != hipSuccess) return PIKV_ERR_HIP;
+        if (cs != hipStreamCaptureStatusNone) return PIKV_ERR_INVALID;
+    }
     if (desc->B == 0) return PIKV_OK;
 
     PreParams p;
@@ -392,7 +403,6 @@ static int decode_step(const pikv_desc *desc, const void *q, const void *W_r, co
     p.do_insert = K_new != nullptr;
     p.use_policy = use_policy;
     p.pol = pol;
-    hipStream_t st = as_stream(stream);
     if (desc->dtype == PIKV_F32)
         hipLaunchKernelGGL(step_pre<float>, dim3(desc->B * k), dim3(kRouteThreads), 0, st, p);
     else

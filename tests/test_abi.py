@@ -114,9 +114,9 @@ def test_host_side_argument_errors_of_the_widened_entry_points(lib):
     d = pk.make_desc(2, 4, 4, 64, 8, 256, dtype=1)
 
     def step(desc=d, q=fake, K_new=fake, V_new=fake, eidx=fake, k=2, decay=1.0, combine=0, ws=fake,
-             ws_bytes=1 << 30, scores=fake):
-        return lib.pikv_decode_step(C.byref(desc), q, fake, None, K_new, V_new, fake, fake, None, None, fake,
-                                    fake, k, combine, 0.0, decay, fake, fake, eidx, fake, fake, None, None,
+             ws_bytes=1 << 30, scores=fake, scale=0.0, U=None):
+        return lib.pikv_decode_step(C.byref(desc), q, fake, None, K_new, V_new, fake, fake, U, U, fake,
+                                    fake, k, combine, scale, decay, fake, fake, eidx, fake, fake, None, None,
                                     scores, fake, ws, ws_bytes, None)
     assert step(q=None) == INVALID
     assert step(V_new=None) == INVALID                     # K_new without V_new
@@ -125,6 +125,10 @@ def test_host_side_argument_errors_of_the_widened_entry_points(lib):
     assert step(decay=-1.0) == INVALID and step(combine=2) == INVALID
     assert step(scores=None) == INVALID
     assert step(ws_bytes=8) == WORKSPACE
+    # the checks of the attention pass are made before the step's first launch as well
+    assert step(ws=vp(0x1010)) == INVALID                  # workspace not 256-byte aligned
+    assert step(scale=float("nan")) == INVALID
+    assert step(desc=pk.make_desc(2, 4, 4, 64, 8, 256, rank=32, dtype=1)) == INVALID   # codes without decoders
     assert step(desc=pk.make_desc(2, 4, 4, 64, 8, 256, dtype=1, route_rows_per_seq=4)) == UNSUPPORTED
     assert step(desc=pk.make_desc(2, 4, 4, 64, 4, 256, dtype=1)) == UNSUPPORTED   # W_r rows of 8 bytes
     assert step(desc=pk.make_desc(0, 4, 4, 64, 8, 256, dtype=1)) == 0

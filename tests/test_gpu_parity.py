@@ -514,6 +514,46 @@ def test_fused_decode_step_equals_separate_calls_and_oracle(spec):
         np.testing.assert_array_equal(t2n(dA.n_valid), ref.n_valid)
 
 
+@pytest.mark.parametrize("bad", ["workspace_alignment", "workspace_size", "nan_scale", "missing_decoder"])
+def test_rejected_fused_step_leaves_the_cache_untouched(bad):
+    """Argument errors of the attention pass are found before the step's first launch: after a
+    rejected call no row, utility, entry count or routing output has changed."""
+    from gpu_harness import dev_storage
+    spec = dict(B=2, Hq=4, Hkv=4, D=128, E=8, S=64, k=2, dtype="bf16")
+    if bad == "missing_decoder":
+        spec["rank"] = 32
+    g = wl.Geometry(**spec)
+    case = wl.make_host_case(g, seed=5, utility0="exp")
+    d = DeviceCase(case)
+    kn, vn = wl.draw_new_kv(g, 6)
+    dkn, dvn = dev_storage(kn, g.dtype), dev_storage(vn, g.dtype)
+    ei = torch.full((g.B, g.E, 1), -1, device=DEV, dtype=torch.int32)
+    ec = torch.full((g.B, g.E), -5, device=DEV, dtype=torch.int32)
+    d.topk.fill_(-7)
+    ws, scale, U_K, U_V = d.workspace, 0.0, d.U_K, d.U_V
+    if bad == "workspace_alignment":
+        big = torch.empty(d.workspace.numel() + 256, device=DEV, dtype=torch.uint8)
+        ws = big[16:16 + d.workspace.numel()]
+    elif bad == "workspace_size":
+        ws = d.workspace[:d.workspace.numel() // 2]
+    elif bad == "nan_scale":
+        scale = float("nan")
+    else:
+        U_K = U_V = None
+    before = {n: t2n(getattr(d, n).view(torch.int16) if getattr(d, n).dtype == torch.bfloat16 else getattr(d, n))
+              for n in ("K", "V", "utility", "n_valid", "topk")}
+    with pytest.raises(pk.PikvError) as err:
+        pk.pikv_decode_step(d.desc, d.q, d.W_r, d.bias, dkn, dvn, d.K_tab, d.V_tab, U_K, U_V, d.n_valid,
+                            d.utility, g.k, pk.COMBINE_LSE, scale, 1.0, d.topk, d.gates, ei, ec, d.y,
+                            d.row_max, d.row_norm, d.scores, d.slot_coef, ws)
+    assert err.value.status == (-3 if bad == "workspace_size" else -1)
+    torch.cuda.synchronize()
+    for n, ref in before.items():
+        t = getattr(d, n)
+        np.testing.assert_array_equal(t2n(t.view(torch.int16) if t.dtype == torch.bfloat16 else t), ref, err_msg=n)
+    assert (t2n(ec) == -5).all() and (t2n(ei) == -1).all()
+
+
 @pytest.mark.parametrize("seed", range(12))
 def test_fused_step_is_bit_identical_to_separate_calls_on_random_geometries(seed):
     """The fused step is defined as the sequence of the separate calls: same bits in every piece of
