@@ -121,6 +121,24 @@ int pikv_sharded_attn(const pikv_desc *desc, const void *q, const void *const *K
                       float *row_norm, float *scores, float *slot_coef, void *workspace,
                       size_t workspace_bytes, void *stream);
 
+/* pikv_sharded_attn for callers that cannot allocate device memory or cannot carry a workspace
+ * (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): same
+ * arguments and results, but the split partials go to a fixed array of
+ * PIKV_NOALLOC_SCRATCH_BYTES inside the library's device image (one copy per GPU, held until
+ * the process ends) instead of a caller workspace.  The call allocates and frees nothing.
+ * All calls on one GPU share that array: calls that overlap on one GPU (different streams,
+ * different threads) race; serialise them.  The first call on each GPU looks the array's
+ * address up (no stream work); make that call outside graph capture.
+ * Errors: as pikv_sharded_attn; WORKSPACE when pikv_attn_workspace_bytes(desc, k) exceeds
+ * PIKV_NOALLOC_SCRATCH_BYTES (use pikv_sharded_attn with a workspace then); HIP if the array's
+ * address cannot be resolved.                                                              */
+#define PIKV_NOALLOC_SCRATCH_BYTES (4u << 20)
+int pikv_sharded_attn_noalloc(const pikv_desc *desc, const void *q, const void *const *K_shards,
+                              const void *const *V_shards, const void *U_K, const void *U_V,
+                              const int32_t *n_valid, const int32_t *topk_idx, const float *gates,
+                              int32_t k, int32_t combine, float scale, float *y, float *row_max,
+                              float *row_norm, float *scores, float *slot_coef, void *stream);
+
 /* Section 3.4, Table 3 row H2O (u_i = a_i, the attention an entry received), kept as a
  * running score: for every shard that at least one query head selected this step and
  * every valid slot i:  u_i <- decay * u_i + sum over those heads of p_{h,i}.

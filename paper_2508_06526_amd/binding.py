@@ -20,7 +20,8 @@ POLICY_H2O, POLICY_SL, POLICY_LRU, POLICY_LRU_PLUS = 0, 1, 2, 3
 EXPORTS = ("pikv_route", "pikv_attn_workspace_bytes", "pikv_sharded_attn", "pikv_update_utility",
            "pikv_evict", "pikv_append", "pikv_strerror", "pikv_version", "pikv_set_attn_split", "pikv_decode_step",
            "pikv_set_profile_events", "pikv_router_penalty", "pikv_compress", "pikv_policy_stamp",
-           "pikv_update_utility_tracked", "pikv_policy_utility", "pikv_policy_compact", "pikv_decode_step_policy", "pikv_route_round_robin")
+           "pikv_update_utility_tracked", "pikv_policy_utility", "pikv_policy_compact", "pikv_decode_step_policy", "pikv_route_round_robin",
+           "pikv_sharded_attn_noalloc")
 
 
 class PikvError(RuntimeError):
@@ -65,6 +66,9 @@ def load_library():
     lib.pikv_sharded_attn.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, f32,
                                       vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
     lib.pikv_sharded_attn.restype = C.c_int
+    lib.pikv_sharded_attn_noalloc.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, f32,
+                                              vp, vp, vp, vp, vp, vp]
+    lib.pikv_sharded_attn_noalloc.restype = C.c_int
     lib.pikv_update_utility.argtypes = [dp, vp, vp, vp, vp, i32, f32, vp, vp]
     lib.pikv_update_utility.restype = C.c_int
     lib.pikv_policy_stamp.argtypes = [dp, vp, i32, vp, vp, i32, vp, i32, vp, vp, vp, vp]
@@ -199,6 +203,18 @@ def pikv_sharded_attn(desc, q, K_shards, V_shards, U_K, U_V, n_valid, topk_idx, 
         _p(topk_idx), _p(gates), k, combine, float(scale), _p(y), _p(row_max), _p(row_norm),
         _p(scores), _p(slot_coef), _p(workspace), ws_bytes, _stream(stream))
     _check(st, "pikv_sharded_attn")
+
+
+NOALLOC_SCRATCH_BYTES = 4 << 20
+
+
+def pikv_sharded_attn_noalloc(desc, q, K_shards, V_shards, U_K, U_V, n_valid, topk_idx, gates, k, combine,
+                              scale, y, row_max, row_norm, scores, slot_coef, stream=None):
+    st = load_library().pikv_sharded_attn_noalloc(
+        C.byref(desc), _p(q), _p(K_shards), _p(V_shards), _p(U_K), _p(U_V), _p(n_valid),
+        _p(topk_idx), _p(gates), k, combine, float(scale), _p(y), _p(row_max), _p(row_norm),
+        _p(scores), _p(slot_coef), _stream(stream))
+    _check(st, "pikv_sharded_attn_noalloc")
 
 
 def pikv_update_utility(desc, scores, slot_coef, n_valid, topk_idx, k, decay, utility, stream=None):

@@ -886,3 +886,48 @@ extern "C" int pikv_sharded_attn(const pikv_desc *desc, const void *q, const voi
     if (rc != PIKV_OK || desc->B == 0) return rc;
     return pikv_sharded_attn_merge(desc, &c, stream);
 }
+
+// ---------------------------------------------------------------------------------------
+// The same call for callers that cannot allocate (code under HIP graph capture, tight serving
+// loops): the split partials live in a file-scope device array instead of a caller workspace.
+namespace {
+
+constexpr size_t kStaticScratchBytes = PIKV_NOALLOC_SCRATCH_BYTES;   // per GPU, held until the process ends
+constexpr int kMaxDevices = 64;
+
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+// Address of this GPU's copy of `scratch` (every device holds its own copy at its own address),
+// looked up once per device with that device current.  In host code the array's name is only a
+// handle for this lookup, never an address to pass to a kernel.
+int static_scratch(void **out) {
+    static void *ptr_of_device[kMaxDevices] = {};
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return PIKV_ERR_HIP;
+    if (ptr_of_device[dev] == nullptr) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || ptr == nullptr) return PIKV_ERR_HIP;
+        ptr_of_device[dev] = ptr;
+    }
+    *out = ptr_of_device[dev];
+    return PIKV_OK;
+}
+
+}  // namespace
+
+extern "C" int pikv_sharded_attn_noalloc(const pikv_desc *desc, const void *q, const void *const *K_shards,
+                                         const void *const *V_shards, const void *U_K, const void *U_V,
+                                         const int32_t *n_valid, const int32_t *topk_idx,
+                                         const float *gates, int32_t k, int32_t combine, float scale,
+                                         float *y, float *row_max, float *row_norm, float *scores,
+                                         float *slot_coef, void *stream) {
+    const size_t need = pikv_attn_workspace_bytes(desc, k);
+    if (need > kStaticScratchBytes) return PIKV_ERR_WORKSPACE;   // geometry too large for the fixed array
+    void *ws = nullptr;
+    const int rc = static_scratch(&ws);
+    if (rc != PIKV_OK) return rc;
+    // Every partial the merge reads is written by the split pass of the same call (empty splits
+    // write an empty partial), so nothing in the array has to start at zero.
+    return pikv_sharded_attn(desc, q, K_shards, V_shards, U_K, U_V, n_valid, topk_idx, gates, k, combine,
+                             scale, y, row_max, row_norm, scores, slot_coef, ws, kStaticScratchBytes, stream);
+}
