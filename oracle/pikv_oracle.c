@@ -112,19 +112,21 @@ int pikv_oracle_route(const void *x, const void *W_r, const float *bias, int row
  * per-entry probabilities.  Row r of a shard's K for kv head hk is
  * K[hk*stride_h + r*stride_s + 0..w), w = D (dense) or rank (codes).                  */
 static void entry_vector(const void *shard, int hk, int row, int64_t stride_h,
-                         int64_t stride_s, int D, int rank, const void *U, int dtype,
-                         double *out /*[D]*/) {
+                         int64_t stride_s, int D, int rank, const void *U, const void *U_bias,
+                         int dtype, double *out /*[D]*/) {
     int64_t base = (int64_t)hk * stride_h + (int64_t)row * stride_s;
     if (rank == 0) {
         for (int d = 0; d < D; ++d) out[d] = load_elem(shard, base + d, dtype);
         return;
     }
-    /* Section 3.3: decoder D(.) of a rank-r code, x_d = sum_c code_c * U[hk][c][d].   */
+    /* Section 3.3: decoder D(.) of a rank-r code, x_d = sum_c code_c * U[hk][c][d]; with the
+     * additive term b of Table 2's LoRA++ row (reconstruction W_d W_u K + b) when given.     */
     for (int d = 0; d < D; ++d) {
         double acc = 0.0;
         for (int c = 0; c < rank; ++c)
             acc += load_elem(shard, base + c, dtype) *
                    load_elem(U, ((int64_t)hk * rank + c) * D + d, dtype);
+        if (U_bias) acc += load_elem(U_bias, (int64_t)hk * D + d, dtype);
         out[d] = acc;
     }
 }
@@ -133,6 +135,7 @@ int pikv_oracle_attend(int B, int Hq, int Hkv, int D, int E, int S, int rank, in
                        int64_t stride_h, int64_t stride_s, int route_rows_per_seq,
                        const void *q, const void *const *K_shards,
                        const void *const *V_shards, const void *U_K, const void *U_V,
+                       const void *V_bias /*[Hkv,D] or NULL: LoRA++ decoder bias of the values*/,
                        const int32_t *n_valid, const int32_t *topk_idx, const float *gates,
                        int k, int combine, double scale, float *y, float *row_max,
                        float *row_norm, double *prob /*[B,Hq,k,S] or NULL*/, double decay,
@@ -180,7 +183,7 @@ int pikv_oracle_attend(int B, int Hq, int Hkv, int D, int E, int S, int rank, in
                 const void *Vs = V_shards[(int64_t)b * E + e];
                 double *s = p + (int64_t)j * S;          /* scores, reused for e^{s-m} */
                 for (int i = 0; i < n; ++i) {
-                    entry_vector(Ks, hk, i, stride_h, stride_s, D, rank, U_K, dtype, kv);
+                    entry_vector(Ks, hk, i, stride_h, stride_s, D, rank, U_K, NULL, dtype, kv);
                     double dot = 0.0;
                     for (int d = 0; d < D; ++d)
                         dot += load_elem(q, ((int64_t)b * Hq + h) * D + d, dtype) * kv[d];
@@ -192,7 +195,7 @@ int pikv_oracle_attend(int B, int Hq, int Hkv, int D, int E, int S, int rank, in
                     Z[j] += s[i];
                 }
                 for (int i = 0; i < n; ++i) {
-                    entry_vector(Vs, hk, i, stride_h, stride_s, D, rank, U_V, dtype, kv);
+                    entry_vector(Vs, hk, i, stride_h, stride_s, D, rank, U_V, V_bias, dtype, kv);
                     for (int d = 0; d < D; ++d) o[(int64_t)j * D + d] += s[i] * kv[d];
                 }
                 for (int d = 0; d < D; ++d) o[(int64_t)j * D + d] /= Z[j];
@@ -396,7 +399,7 @@ int pikv_oracle_append(int B, int E, int S, int Hkv, int width, int dtype, int64
  * formed from the updated counters.  mode 0 = LB, 1 = P (needs `miss`).                   */
 int pikv_oracle_router_penalty(int mode, const int32_t *topk_idx, int rows, int k, int E,
                                int32_t *load, const int32_t *miss, double coef, float *bias) {
-    if (E < 1 || rows < 0 || k < 0 || (mode != 0 && mode != 1) || (mode == 1 && !miss)) return -1;
+    if (E < 1 || rows < 0 || k < 0 || mode < 0 || mode > 2 || (mode == 1 && !miss)) return -1;
     for (int i = 0; i < rows * k; ++i) {
         if (topk_idx[i] < 0 || topk_idx[i] >= E) return -1;
         load[topk_idx[i]] += 1;
@@ -406,8 +409,25 @@ int pikv_oracle_router_penalty(int mode, const int32_t *topk_idx, int rows, int 
         for (int e = 0; e < E; ++e) mean += (double)load[e];
         mean /= (double)E;
         for (int e = 0; e < E; ++e) bias[e] = (float)(-coef * ((double)load[e] - mean));
-    } else {
+    } else if (mode == 1) {
         for (int e = 0; e < E; ++e) bias[e] = (float)(-coef * log(1.0 + (double)miss[e]));
+    } else {
+        /* Table 1 row E, -beta H(p_e): p_e is expert e's share of all selections so far and
+         * H(p_e) = -p_e ln p_e its term of the entropy of that distribution (0 ln 0 = 0).  A
+         * shift common to all experts does not change any routing decision; the term is
+         * centred like the load-balance row's, so that it vanishes under uniform load.       */
+        double total = 0.0, h_avg = 0.0;
+        for (int e = 0; e < E; ++e) total += (double)load[e];
+        for (int e = 0; e < E; ++e) {
+            const double pe = total > 0.0 ? (double)load[e] / total : 0.0;
+            h_avg += pe > 0.0 ? -pe * log(pe) : 0.0;
+        }
+        h_avg /= (double)E;
+        for (int e = 0; e < E; ++e) {
+            const double pe = total > 0.0 ? (double)load[e] / total : 0.0;
+            const double he = pe > 0.0 ? -pe * log(pe) : 0.0;
+            bias[e] = (float)(-coef * (he - h_avg));
+        }
     }
     return 0;
 }

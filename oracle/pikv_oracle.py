@@ -98,7 +98,7 @@ def route(x, W_r, k, bias=None, dtype="f32", want_logits=False):
 
 
 def attend(q, K_shards, V_shards, n_valid, topk_idx, gates, *, Hkv, E, S, dtype="f32",
-           rank=0, U_K=None, U_V=None, combine=COMBINE_LSE, scale=0.0, stride_h=None,
+           rank=0, U_K=None, U_V=None, V_bias=None, combine=COMBINE_LSE, scale=0.0, stride_h=None,
            stride_s=None, utility=None, decay=1.0, want_prob=False):
     """One decode step of routed attention (+ optional in-place utility update).
 
@@ -125,6 +125,7 @@ def attend(q, K_shards, V_shards, n_valid, topk_idx, gates, *, Hkv, E, S, dtype=
     rr = 1 if R == B else Hq
     U_K = _chk(U_K, nd, "U_K")
     U_V = _chk(U_V, nd, "U_V")
+    V_bias = _chk(V_bias, nd, "V_bias")
     utility = _chk(utility, np.float32, "utility")
     y = np.zeros((B, Hq, D), np.float32)
     row_max = np.zeros((B, Hq), np.float32)
@@ -133,7 +134,7 @@ def attend(q, K_shards, V_shards, n_valid, topk_idx, gates, *, Hkv, E, S, dtype=
     kt, vt = _ptr_table(K_shards), _ptr_table(V_shards)
     rc = lib().pikv_oracle_attend(
         B, Hq, Hkv, D, E, S, rank, _dt(dtype), C.c_int64(stride_h), C.c_int64(stride_s), rr,
-        _ptr(q), kt, vt, _ptr(U_K), _ptr(U_V), _ptr(n_valid), _ptr(topk_idx), _ptr(gates), k,
+        _ptr(q), kt, vt, _ptr(U_K), _ptr(U_V), _ptr(V_bias), _ptr(n_valid), _ptr(topk_idx), _ptr(gates), k,
         combine, C.c_double(scale), _ptr(y), _ptr(row_max), _ptr(row_norm), _ptr(prob),
         C.c_double(decay), _ptr(utility))
     if rc:
@@ -200,7 +201,7 @@ def append(K_new, V_new, topk_idx, K_shards, V_shards, utility, n_valid, *, dtyp
         raise ValueError("pikv_oracle_append failed: %d" % rc)
 
 
-LB, CACHE_AWARE = 0, 1
+LB, CACHE_AWARE, ENTROPY = 0, 1, 2
 
 
 def router_penalty(mode, topk_idx, load, coef, miss=None):

@@ -25,8 +25,8 @@ MUTANTS = {
     "local_gates_not_renormalised": ("const double gh = (gsel ? (double)gsel[j] : 1.0) / norm;",
                                      "const double gh = (gsel ? (double)gsel[j] : 1.0);"),
     "shard_max_not_subtracted_consistently": ("s[i] = exp(s[i] - m[j]);", "s[i] = exp(s[i]);"),
-    "value_rows_read_from_keys": ("entry_vector(Vs, hk, i, stride_h, stride_s, D, rank, U_V, dtype, kv);",
-                                  "entry_vector(Ks, hk, i, stride_h, stride_s, D, rank, U_V, dtype, kv);"),
+    "value_rows_read_from_keys": ("entry_vector(Vs, hk, i, stride_h, stride_s, D, rank, U_V, V_bias, dtype, kv);",
+                                  "entry_vector(Ks, hk, i, stride_h, stride_s, D, rank, U_V, V_bias, dtype, kv);"),
     "decoder_transposed": ("load_elem(U, ((int64_t)hk * rank + c) * D + d, dtype)",
                            "load_elem(U, ((int64_t)hk * D + d) * rank + c, dtype)"),
     "utility_decay_dropped": ("u[i] = (float)(decay * (double)u[i] + a);",
@@ -62,6 +62,14 @@ MUTANTS = {
     "stamp_keeps_old_frequency": ("freq[be * S + slot] = 0;", ""),
     "policy_compact_skips_hole_test": ("if (g < cnt && gone[g] == i) { ++g; continue; }", "if (g < cnt && gone[g] == i) { ++g; }"),
     "round_robin_ignores_k_stride": ("(int32_t)(((step + r) * k + j) % E);", "(int32_t)(((step + r) + j) % E);"),
+    "entropy_penalty_not_centred": ("bias[e] = (float)(-coef * (he - h_avg));", "bias[e] = (float)(-coef * he);"),
+    "entropy_penalty_sign_flipped": ("bias[e] = (float)(-coef * (he - h_avg));", "bias[e] = (float)(coef * (he - h_avg));"),
+    "entropy_of_counts_not_shares": ("const double pe = total > 0.0 ? (double)load[e] / total : 0.0;\n            const double he",
+                                     "const double pe = (double)load[e];\n            const double he"),
+    "value_bias_added_to_keys_too": ("entry_vector(Ks, hk, i, stride_h, stride_s, D, rank, U_K, NULL, dtype, kv);",
+                                     "entry_vector(Ks, hk, i, stride_h, stride_s, D, rank, U_K, V_bias, dtype, kv);"),
+    "value_bias_wrong_head": ("acc += load_elem(U_bias, (int64_t)hk * D + d, dtype);",
+                              "acc += load_elem(U_bias, (int64_t)d, dtype);"),
     "empty_shard_counted_in_local_norm": ("if (Z[j] > 0.0) norm += gsel ? (double)gsel[j] : 1.0;",
                                           "norm += gsel ? (double)gsel[j] : 1.0;"),
 }

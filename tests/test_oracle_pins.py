@@ -634,6 +634,42 @@ def test_cache_aware_penalty_is_minus_lambda_log1p_miss():
     assert bias[0] == 0 and list(load) == [0, 0, 1, 1]
 
 
+def test_entropy_penalty_closed_forms():
+    """Table 1 row E, -beta H(p_e) with p_e the running selection share and H(p_e) = -p_e ln p_e,
+    centred over the experts: zero under uniform load, zero-sum, an expert with a larger share
+    (all shares below 1/e) is pushed down, linear in beta, and equal to the formula written
+    with scipy's entr on random counters."""
+    from scipy.special import entr
+    E = 8
+    # uniform load: exactly zero
+    load = np.full(E, 5, np.int32)
+    bias = orc.router_penalty(orc.ENTROPY, np.zeros((0, 1), np.int32), load, 0.9)
+    assert (bias == 0).all()
+    # nothing selected yet: zero (0 ln 0 = 0), and the first selections are absorbed first
+    load = np.zeros(E, np.int32)
+    bias = orc.router_penalty(orc.ENTROPY, np.zeros((0, 2), np.int32), load, 0.9)
+    assert (bias == 0).all()
+    bias = orc.router_penalty(orc.ENTROPY, np.array([[0, 1], [0, 2]], np.int32), load, 1.0)
+    assert list(load) == [2, 1, 1, 0, 0, 0, 0, 0]
+    p = load / load.sum()
+    h = entr(p)
+    np.testing.assert_allclose(bias, -(h - h.mean()), rtol=1e-6, atol=1e-9)
+    # sign: shares 0.3 > 0.1: the busier expert gets the more negative term
+    load = np.array([30, 10, 10, 10, 10, 10, 10, 10], np.int32)
+    b1 = orc.router_penalty(orc.ENTROPY, np.zeros((0, 1), np.int32), load.copy(), 1.0)
+    b3 = orc.router_penalty(orc.ENTROPY, np.zeros((0, 1), np.int32), load.copy(), 3.0)
+    assert b1[0] < 0 < b1[1] and np.allclose(b1[1:], b1[1])
+    np.testing.assert_allclose(b3, 3.0 * b1, rtol=1e-6)
+    assert abs(float(b1.astype(np.float64).sum())) < 1e-6
+    # random counters against the independent routine
+    rng = np.random.default_rng(5)
+    for _ in range(20):
+        load = rng.integers(0, 1000, size=E).astype(np.int32)
+        bias = orc.router_penalty(orc.ENTROPY, np.zeros((0, 1), np.int32), load, 0.37)
+        h = entr(load / load.sum())
+        np.testing.assert_allclose(bias, -0.37 * (h - h.mean()), rtol=1e-5, atol=1e-8)
+
+
 def test_penalty_feeds_the_router_as_bias():
     """Closing the loop: a heavily loaded expert drops out of the top-k."""
     rng = np.random.default_rng(0)
@@ -888,3 +924,46 @@ def test_round_robin_router_is_exactly_balanced_and_selects_distinct_experts():
     np.testing.assert_array_equal(a[1:], b[:2])          # row r at step t = row r-1 at step t+1
     assert list(a[0]) == [(5 * k + j) % E for j in range(k)]
 
+
+
+# ------------------------------------------------------------ decoder bias of the values
+def test_value_decoder_bias_adds_the_same_vector_to_every_output():
+    """Table 2 row LoRA++: reconstruction W_d W_u x + b.  On the value side every decoded entry
+    gains b[h'], and since the attention weights of a row sum to one, so does every output row
+    with a non-empty selection (an empty one stays zero).  Probabilities and utilities do not
+    move.  Against an independent numpy attention over explicitly decoded entries as well."""
+    g = wl.Geometry(B=2, Hq=4, Hkv=2, D=16, E=3, S=10, k=2, dtype="f32", rank=4)
+    case = wl.make_host_case(g, seed=8, n_valid="ragged")
+    case.n_valid[1, :] = 0                                  # sequence 1: every shard empty
+    rng = np.random.default_rng(9)
+    b_V = rng.standard_normal((g.Hkv, g.D)).astype(np.float32)
+    idx = np.array([[0, 2], [1, 2]], np.int32)
+    gates = np.array([[0.7, 0.3], [0.5, 0.5]], np.float32)
+    for combine in (orc.COMBINE_LSE, orc.COMBINE_LOCAL):
+        u0, u1 = case.utility.copy(), case.utility.copy()
+        kw = dict(Hkv=g.Hkv, E=g.E, S=g.S, dtype=g.dtype, rank=g.rank, U_K=case.U_K, U_V=case.U_V,
+                  combine=combine, want_prob=True)
+        plain = orc.attend(case.q, case.K_shards, case.V_shards, case.n_valid, idx, gates, utility=u0, **kw)
+        biased = orc.attend(case.q, case.K_shards, case.V_shards, case.n_valid, idx, gates, utility=u1,
+                            V_bias=b_V, **kw)
+        G = g.Hq // g.Hkv
+        for h in range(g.Hq):
+            np.testing.assert_allclose(biased["y"][0, h] - plain["y"][0, h], b_V[h // G], rtol=1e-5, atol=1e-6)
+        assert (biased["y"][1] == 0).all() and (plain["y"][1] == 0).all()
+        np.testing.assert_array_equal(biased["prob"], plain["prob"])
+        np.testing.assert_array_equal(u0, u1)
+    # independent check of the biased output in LSE mode with unit gates: dense attention over the
+    # concatenation of the two selected shards, entries decoded explicitly
+    ones = np.ones_like(gates)
+    out = orc.attend(case.q, case.K_shards, case.V_shards, case.n_valid, idx, ones, Hkv=g.Hkv, E=g.E, S=g.S,
+                     dtype=g.dtype, rank=g.rank, U_K=case.U_K, U_V=case.U_V, V_bias=b_V)
+    G = g.Hq // g.Hkv
+    for h in range(g.Hq):
+        hk = h // G
+        Kd = np.concatenate([case.K_shards[e][hk, :case.n_valid[0, e]].astype(np.float64) @ case.U_K[hk]
+                             for e in idx[0]])
+        Vd = np.concatenate([case.V_shards[e][hk, :case.n_valid[0, e]].astype(np.float64) @ case.U_V[hk]
+                             + b_V[hk] for e in idx[0]])
+        sc = Kd @ case.q[0, h].astype(np.float64) / np.sqrt(g.D)
+        w = np.exp(sc - sc.max())
+        np.testing.assert_allclose(out["y"][0, h], (w / w.sum()) @ Vd, rtol=1e-5, atol=1e-6)
