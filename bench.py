@@ -61,7 +61,7 @@ def parse_args():
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--balance", action="store_true",
                     help="widened row: keep the load-balance router penalty on the device and feed "
-                         "it back as the routing bias (one extra small launch per step)")
+                         "it back as the routing bias (inside the fused step's last launch)")
     ap.add_argument("--compress", action="store_true",
                     help="widened row (rank > 0 workloads): compress the new token's full-width K/V "
                          "to codes inside the step (one extra small launch)")
@@ -117,22 +117,27 @@ class Layer:
             pk.pikv_compress(self.desc, s["K_full"], s["Wenc_K"], s["K_new"], s["V_full"], s["Wenc_V"],
                              s["V_new"])
         self._step()
-        if s.get("balance"):
+        if s.get("balance") and not self.fused:
             pk.pikv_router_penalty(pk.PENALTY_LOAD_BALANCE, s["topk"], g.route_rows, g.k, g.E,
                                    t["load"], None, 0.01, t["bias"])
 
     def _step(self):
         pk, g, t, s = self.pk, self.geo, self.t, self.sh
-        if self.fused and s.get("policy"):
+        feedback = None
+        if self.fused and s.get("balance"):      # the loop closes inside the step's last launch
+            feedback = pk.make_router_feedback(pk.PENALTY_LOAD_BALANCE, 0.01, t["load"], t["bias"])
+        if self.fused and (s.get("policy") or feedback is not None):
             # the step counter is baked into the captured launch: replays re-stamp with the same
             # value, which costs the same as a running counter
-            args = pk.make_policy_args(s["policy"], 1000, lam=0.5, window=g.S // 2, threshold=1.0 / g.S,
-                                       birth=t["birth"], last_access=t["last_access"], freq=t["freq"])
+            args = None
+            if s.get("policy"):
+                args = pk.make_policy_args(s["policy"], 1000, lam=0.5, window=g.S // 2, threshold=1.0 / g.S,
+                                           birth=t["birth"], last_access=t["last_access"], freq=t["freq"])
             pk.pikv_decode_step_policy(self.desc, t["q"], t["W_r"], t["bias"], s["K_new"], s["V_new"],
                                        self.K_tab, self.V_tab, t["U_K"], t["U_V"], t["n_valid"], t["utility"],
                                        g.k, pk.COMBINE_LSE, 0.0, self.decay, s["topk"], s["gates"], s["eidx"],
                                        s["ecnt"], s["y"], s["row_max"], s["row_norm"], s["scores"],
-                                       s["slot_coef"], s["workspace"], args)
+                                       s["slot_coef"], s["workspace"], args, feedback=feedback)
             return
         if self.fused:
             pk.pikv_decode_step(self.desc, t["q"], t["W_r"], t["bias"], s["K_new"], s["V_new"],

@@ -69,8 +69,15 @@ typedef struct pikv_desc {
     int64_t stride_h; /* elements between kv heads inside a shard buffer                   */
     int64_t stride_s; /* elements between slots (>= width, multiple of 16 bytes)           */
     int32_t route_rows_per_seq; /* 1 or Hq                                                 */
-    int32_t reserved; /* must be 0                                                         */
+    int32_t flags;    /* 0, or PIKV_DESC_VALUE_BIAS (rank > 0 only)                        */
 } pikv_desc;
+
+/* desc->flags.  PIKV_DESC_VALUE_BIAS: the value decoder has the additive term of Table 2's
+ * LoRA++ row (reconstruction W_d W_u x + b): U_V then holds rank + 1 rows of D values per kv
+ * head, [Hkv, rank + 1, D], the last row being b, and every decoded value - hence every output
+ * row with a non-empty selection - gains b[h'].  (The same term on the key side would shift all
+ * scores of a head equally and cancel in the softmax, so U_K never carries one.)             */
+#define PIKV_DESC_VALUE_BIAS 1
 
 /* Section 3.2, Table 1 "TopK softmax" router (with the table's additive per-expert
  * penalty as `bias`): logits = x W_r + bias, p = softmax over the E experts, the mask has
@@ -98,7 +105,8 @@ size_t pikv_attn_workspace_bytes(const pikv_desc *desc, int32_t k);
  * entries are K_i = code_i U_K[h'], V_i = code_i U_V[h'] (Section 3.3, decoder of the
  * rank-r compressor, fused into the kernel: the codes are what is streamed from HBM).
  *   q        [B,Hq,D] dtype
- *   U_K,U_V  [Hkv,rank,D] dtype   (rank > 0 only, else ignored)
+ *   U_K,U_V  [Hkv,rank,D] dtype   (rank > 0 only, else ignored; U_V is [Hkv,rank+1,D] with
+ *                                  PIKV_DESC_VALUE_BIAS)
  *   n_valid  [B,E] int32
  *   topk_idx [rows,k] int32       selected experts per routing row (distinct within a row)
  *   gates    [rows,k] float32 or NULL (NULL: every gate is 1)
@@ -224,13 +232,18 @@ int pikv_route_round_robin(int32_t rows, int32_t E, int32_t k, int64_t step, int
  * routers, kept on the device so that routing feeds back into itself without the host:
  *   PIKV_PENALTY_LOAD_BALANCE (row LB):  bias_e = -coef * (load_e - mean_e' load_e')
  *   PIKV_PENALTY_CACHE_AWARE  (row P):   bias_e = -coef * log(1 + miss_e)
+ *   PIKV_PENALTY_ENTROPY      (row E):   bias_e = -coef * (h_e - mean_e' h_e'), h_e = -p_e ln p_e,
+ *                                        p_e = load_e / sum_e' load_e' the expert's share of all
+ *                                        selections so far (0 ln 0 = 0; zero under uniform load)
  * `load` [E] int32 is a running count of how often each expert was selected; the call first
  * adds this step's selections topk_idx [rows,k] to it (rows*k may be 0), then writes
  * bias [E] float32, to be passed as `bias` to the next pikv_route / pikv_decode_step.
  * `miss` [E] int32 (cache-aware mode only) is maintained by the caller.
  * Errors: INVALID for unknown mode, null load/bias, E not in 1..64, null miss in cache-aware
  * mode, NaN coef.                                                                          */
-typedef enum { PIKV_PENALTY_LOAD_BALANCE = 0, PIKV_PENALTY_CACHE_AWARE = 1 } pikv_penalty;
+typedef enum {
+    PIKV_PENALTY_LOAD_BALANCE = 0, PIKV_PENALTY_CACHE_AWARE = 1, PIKV_PENALTY_ENTROPY = 2
+} pikv_penalty;
 int pikv_router_penalty(int32_t mode, const int32_t *topk_idx, int32_t rows, int32_t k, int32_t E,
                         int32_t *load, const int32_t *miss, float coef, float *bias, void *stream);
 
@@ -290,8 +303,21 @@ int pikv_policy_utility(const pikv_desc *desc, int32_t policy, const int32_t *n_
                         float lambda, int32_t window, int32_t protect, const int32_t *birth,
                         const int32_t *last_access, const int32_t *freq, const float *h2o,
                         float *out, void *stream);
-/* pikv_decode_step with a scheduling policy (same arguments, plus `policy`; NULL = exactly
- * pikv_decode_step).  It is the sequence
+/* Router feedback inside the fused step: with a pikv_router_feedback the step's last launch also
+ * does what pikv_router_penalty(mode, this step's topk_idx, ...) would do after the step - adds
+ * the selections to `load` and writes the penalty for the NEXT step to `bias` - so that closing
+ * the loop costs no launch of its own.  `bias` may be the array the step itself was given as its
+ * routing bias (it is read by the step's first launch and written by its last).              */
+typedef struct {
+    int32_t mode;          /* pikv_penalty */
+    float coef;
+    int32_t *load;         /* [E] device, running selection counts, in place */
+    const int32_t *miss;   /* [E] device, PIKV_PENALTY_CACHE_AWARE only */
+    float *bias;           /* [E] device, out */
+} pikv_router_feedback;
+
+/* pikv_decode_step with a scheduling policy and / or router feedback (same arguments, plus
+ * `policy` and `feedback`; NULL, NULL = exactly pikv_decode_step).  With a policy it is the sequence
  *   pikv_route; pikv_policy_utility(policy, ...) into a scratch utility;
  *   pikv_evict(scratch, capacity = S-1, sel_idx = topk_idx, max_evict = 1, compact = 0);
  *   pikv_policy_stamp; pikv_append; pikv_sharded_attn;
@@ -301,7 +327,8 @@ int pikv_policy_utility(const pikv_desc *desc, int32_t policy, const int32_t *n_
  * Arrays the policy does not read may be NULL; the new entry is stamped in those given; access
  * bookkeeping runs when last_access and freq are both given (threshold >= 0).  `utility` keeps
  * accumulating the attention (H2O) whatever the policy.
- * Errors: as pikv_decode_step and pikv_policy_utility.                                       */
+ * With feedback the sequence ends with pikv_router_penalty (bit-identical to that call).
+ * Errors: as pikv_decode_step, pikv_policy_utility and pikv_router_penalty.                  */
 typedef struct {
     int32_t policy;        /* pikv_policy */
     int32_t now;           /* the caller's step counter */
@@ -320,7 +347,7 @@ int pikv_decode_step_policy(const pikv_desc *desc, const void *q, const void *W_
                             int32_t *topk_idx, float *gates, int32_t *evicted_idx, int32_t *evicted_cnt,
                             float *y, float *row_max, float *row_norm, float *scores, float *slot_coef,
                             void *workspace, size_t workspace_bytes, void *stream,
-                            const pikv_policy_args *policy);
+                            const pikv_policy_args *policy, const pikv_router_feedback *feedback);
 int pikv_policy_compact(const pikv_desc *desc, const int32_t *evicted_idx, const int32_t *evicted_cnt,
                         int32_t max_evict, const int32_t *n_valid, int32_t *birth,
                         int32_t *last_access, int32_t *freq, void *stream);

@@ -14,7 +14,8 @@ _LIB_PATH = os.path.join(_HERE, "libpikv.so")
 
 F32, BF16 = 0, 1
 COMBINE_LSE, COMBINE_LOCAL = 0, 1
-PENALTY_LOAD_BALANCE, PENALTY_CACHE_AWARE = 0, 1
+PENALTY_LOAD_BALANCE, PENALTY_CACHE_AWARE, PENALTY_ENTROPY = 0, 1, 2
+DESC_VALUE_BIAS = 1
 POLICY_H2O, POLICY_SL, POLICY_LRU, POLICY_LRU_PLUS = 0, 1, 2, 3
 
 EXPORTS = ("pikv_route", "pikv_attn_workspace_bytes", "pikv_sharded_attn", "pikv_update_utility",
@@ -34,7 +35,7 @@ class PikvDesc(C.Structure):
     _fields_ = [("B", C.c_int32), ("Hq", C.c_int32), ("Hkv", C.c_int32), ("D", C.c_int32),
                 ("E", C.c_int32), ("S", C.c_int32), ("rank", C.c_int32), ("dtype", C.c_int32),
                 ("stride_h", C.c_int64), ("stride_s", C.c_int64),
-                ("route_rows_per_seq", C.c_int32), ("reserved", C.c_int32)]
+                ("route_rows_per_seq", C.c_int32), ("flags", C.c_int32)]
 
     @property
     def width(self):
@@ -90,7 +91,7 @@ def load_library():
     lib.pikv_decode_step.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, f32, f32,
                                      vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
     lib.pikv_decode_step.restype = C.c_int
-    lib.pikv_decode_step_policy.argtypes = list(lib.pikv_decode_step.argtypes) + [vp]
+    lib.pikv_decode_step_policy.argtypes = list(lib.pikv_decode_step.argtypes) + [vp, vp]
     lib.pikv_decode_step_policy.restype = C.c_int
     lib.pikv_router_penalty.argtypes = [i32, vp, i32, i32, i32, vp, vp, f32, vp, vp]
     lib.pikv_router_penalty.restype = C.c_int
@@ -139,13 +140,13 @@ def _check(status, where):
 
 
 def make_desc(B, Hq, Hkv, D, E, S, rank=0, dtype=BF16, stride_h=None, stride_s=None,
-              route_rows_per_seq=1) -> PikvDesc:
+              route_rows_per_seq=1, flags=0) -> PikvDesc:
     w = rank if rank else D
     if stride_s is None:
         stride_s = w
     if stride_h is None:
         stride_h = S * stride_s
-    return PikvDesc(B, Hq, Hkv, D, E, S, rank, dtype, stride_h, stride_s, route_rows_per_seq, 0)
+    return PikvDesc(B, Hq, Hkv, D, E, S, rank, dtype, stride_h, stride_s, route_rows_per_seq, flags)
 
 
 def shard_table(shards, device=None):
@@ -313,15 +314,30 @@ def make_policy_args(policy, now, lam=0.0, window=0, protect=0, threshold=0.0, b
     return a
 
 
+class PikvRouterFeedback(C.Structure):
+    _fields_ = [("mode", C.c_int32), ("coef", C.c_float), ("load", C.c_void_p), ("miss", C.c_void_p),
+                ("bias", C.c_void_p)]
+
+
+def make_router_feedback(mode, coef, load, bias, miss=None):
+    f = PikvRouterFeedback()
+    f.mode, f.coef = int(mode), float(coef)
+    for name, t in (("load", load), ("miss", miss), ("bias", bias)):
+        ptr = _p(t)
+        setattr(f, name, None if ptr is None else ptr.value)
+    return f
+
+
 def pikv_decode_step_policy(desc, q, W_r, bias, K_new, V_new, K_shards, V_shards, U_K, U_V, n_valid, utility, k,
                             combine, scale, decay, topk_idx, gates, evicted_idx, evicted_cnt, y, row_max,
-                            row_norm, scores, slot_coef, workspace, policy_args, stream=None):
+                            row_norm, scores, slot_coef, workspace, policy_args, feedback=None, stream=None):
     st = load_library().pikv_decode_step_policy(
         C.byref(desc), _p(q), _p(W_r), _p(bias), _p(K_new), _p(V_new), _p(K_shards), _p(V_shards), _p(U_K),
         _p(U_V), _p(n_valid), _p(utility), k, combine, float(scale), float(decay), _p(topk_idx), _p(gates),
         _p(evicted_idx), _p(evicted_cnt), _p(y), _p(row_max), _p(row_norm), _p(scores), _p(slot_coef),
         _p(workspace), workspace.numel() * workspace.element_size(), _stream(stream),
-        None if policy_args is None else C.cast(C.pointer(policy_args), C.c_void_p))
+        None if policy_args is None else C.cast(C.pointer(policy_args), C.c_void_p),
+        None if feedback is None else C.cast(C.pointer(feedback), C.c_void_p))
     _check(st, "pikv_decode_step_policy")
 
 

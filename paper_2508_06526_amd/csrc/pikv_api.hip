@@ -5,12 +5,13 @@ namespace pikv {
 
 int check_desc(const pikv_desc *d) {
     if (!d) return PIKV_ERR_INVALID;
-    if (d->B < 0 || d->Hq < 1 || d->Hkv < 1 || d->E < 1 || d->S < 1 || d->reserved != 0)
+    if (d->B < 0 || d->Hq < 1 || d->Hkv < 1 || d->E < 1 || d->S < 1 || (d->flags & ~PIKV_DESC_VALUE_BIAS) != 0)
         return PIKV_ERR_INVALID;
     if (d->Hq % d->Hkv != 0) return PIKV_ERR_INVALID;
     if (d->dtype != PIKV_F32 && d->dtype != PIKV_BF16) return PIKV_ERR_INVALID;
     if (d->route_rows_per_seq != 1 && d->route_rows_per_seq != d->Hq) return PIKV_ERR_INVALID;
     if (d->rank < 0) return PIKV_ERR_INVALID;
+    if ((d->flags & PIKV_DESC_VALUE_BIAS) && d->rank == 0) return PIKV_ERR_INVALID;
     if (d->Hq > 256 || d->E > 64) return PIKV_ERR_UNSUPPORTED;
     if (d->D != 16 && d->D != 32 && d->D != 64 && d->D != 128) return PIKV_ERR_UNSUPPORTED;
     if (d->rank != 0 && d->rank != 16 && d->rank != 32 && d->rank != 64) return PIKV_ERR_UNSUPPORTED;

@@ -844,6 +844,7 @@ int launch_attn_partial(const pikv_desc *desc, const void *q, const void *const 
     c.k = k;
     c.rr = p.rr;
     c.rank = desc->rank;
+    c.value_bias = (desc->flags & PIKV_DESC_VALUE_BIAS) ? 1 : 0;
     c.nsplit = plan.nsplit;
     c.combine = combine;
     *c_out = c;

@@ -1,50 +1,23 @@
 // Two small stages around the hot path:
 //
 //   router_penalty : the additive per-expert term of PiKV's penalised routers (Section 3.2,
-//                    Table 1, column "Penalty Term"): load balancing, -alpha (mu_e - mean mu)
-//                    with mu_e = how often expert e has been selected, and cache-aware routing,
-//                    -lambda log(1 + miss_e).  One wavefront: lane e owns expert e, absorbs this
-//                    step's selections into the load counter (integer, order-free) and writes
-//                    the bias that the next pikv_route / pikv_decode_step call adds to the logits.
+//                    Table 1, column "Penalty Term", rows LB, P and E), one wavefront
+//                    (pikv_penalty_dev.h): absorbs this step's selections into the load counter
+//                    and writes the bias that the next pikv_route / pikv_decode_step call adds
+//                    to the logits.
 //   compress_rows  : Algorithm 1, (K^, V^) <- C_cmp(K_t, V_t) for the rank-r linear compressor of
 //                    Section 3.3 (Table 2, LoRA rows): code = W_enc x, rounded once to the storage
 //                    type.  One block per (sequence, kv head, K or V); 8 lanes per code element read the
 //                    encoder row and the vector with 16-byte loads and join by an xor butterfly.
 #include "pikv_common.h"
+#include "pikv_penalty_dev.h"
 
 #include <math.h>
 
 namespace pikv {
 namespace {
 
-__global__ __launch_bounds__(kWave) void router_penalty(int mode, const int32_t *topk, int n_sel, int E,
-                                                        int32_t *load, const int32_t *miss, float coef,
-                                                        float *bias) {
-    const int e = threadIdx.x;
-    // lane e counts the selections equal to e: 64 ids per load, each then passed to every lane
-    // through the scalar unit (one round trip per 64 selections instead of one per selection)
-    int cnt = 0;
-    for (int base = 0; base < n_sel; base += kWave) {
-        const int mine_sel = base + e < n_sel ? topk[base + e] : -1;
-#pragma unroll
-        for (int s = 0; s < kWave; ++s) cnt += (__builtin_amdgcn_readlane(mine_sel, s) == e);
-    }
-    int mine = 0;
-    if (e < E) {
-        mine = load[e] + cnt;
-        load[e] = mine;
-    }
-    if (mode == 0) {
-        // exact integer total, then one division: the mean does not depend on lane order
-        int total = mine;
-#pragma unroll
-        for (int off = 32; off >= 1; off >>= 1) total += __shfl_xor(total, off, kWave);
-        const float mean = (float)total / (float)E;
-        if (e < E) bias[e] = -coef * ((float)mine - mean);
-    } else {
-        if (e < E) bias[e] = -coef * log1pf((float)miss[e]);
-    }
-}
+__global__ __launch_bounds__(kWave) void router_penalty(PenaltyParams p) { penalty_wave(p, threadIdx.x); }
 
 // Table 1 row B: the score-free round-robin router.  One thread per (routed row, position).
 __global__ __launch_bounds__(256) void route_round_robin(int n, int E, int k, long long step, int32_t *topk,
@@ -113,14 +86,21 @@ using namespace pikv;
 extern "C" int pikv_router_penalty(int32_t mode, const int32_t *topk_idx, int32_t rows, int32_t k,
                                    int32_t E, int32_t *load, const int32_t *miss, float coef,
                                    float *bias, void *stream) {
-    if (mode != PIKV_PENALTY_LOAD_BALANCE && mode != PIKV_PENALTY_CACHE_AWARE) return PIKV_ERR_INVALID;
-    if (!load || !bias || E < 1 || E > 64 || rows < 0 || k < 0) return PIKV_ERR_INVALID;
+    const int rc = check_penalty(mode, load, miss, coef, bias, E);
+    if (rc != PIKV_OK) return rc;
+    if (rows < 0 || k < 0) return PIKV_ERR_INVALID;
     if ((int64_t)rows * k > 0 && !topk_idx) return PIKV_ERR_INVALID;
-    if (mode == PIKV_PENALTY_CACHE_AWARE && !miss) return PIKV_ERR_INVALID;
-    if (!(coef == coef)) return PIKV_ERR_INVALID;
     if ((int64_t)rows * k > 0x7fffffff) return PIKV_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL(router_penalty, dim3(1), dim3(kWave), 0, as_stream(stream), mode, topk_idx,
-                       rows * k, E, load, miss, coef, bias);
+    PenaltyParams p;
+    p.mode = mode;
+    p.topk = topk_idx;
+    p.n_sel = rows * k;
+    p.E = E;
+    p.load = load;
+    p.miss = miss;
+    p.coef = coef;
+    p.bias = bias;
+    hipLaunchKernelGGL(router_penalty, dim3(1), dim3(kWave), 0, as_stream(stream), p);
     return launch_status();
 }
 

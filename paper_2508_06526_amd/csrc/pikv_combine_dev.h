@@ -19,6 +19,7 @@ struct CombineParams {
     float *row_norm;
     float *slot_coef;
     int Hq, G, D, W, k, rr, rank, nsplit, combine;
+    int value_bias;   // U_V holds rank + 1 rows per kv head, the last one the decoder's additive term
 };
 
 constexpr int kCombinePrefetch = 4;         // partial rows each thread loads before the weights exist
@@ -100,7 +101,7 @@ __device__ __forceinline__ void head_weights(int k, const float *Mj, const float
 // many, and the LDS they reserve decides how many of them a CU holds at once.
 inline __host__ __device__ int combine_np_pad(int np) { return (np + 3) & ~3; }
 inline size_t combine_smem_bytes(int threads, int np) {
-    return (size_t)(2 * combine_np_pad(np) + 6 * 64 + 128) * 4 + (size_t)threads * 16;
+    return (size_t)(2 * combine_np_pad(np) + 6 * 64 + 128 + 4) * 4 + (size_t)threads * 16;
 }
 
 // Block size of the merge: one query head rarely has more than a few dozen partials; a small
@@ -121,6 +122,7 @@ __device__ __forceinline__ void combine_head(const CombineParams &p, int bh, uns
     float *Mj = ls + combine_np_pad(np), *Zj = Mj + 64, *shard_w = Zj + 64;
     float *sh_shift = shard_w + 64, *sh_coef = sh_shift + 64, *g_s = sh_coef + 64;
     float *ycode = g_s + 64;                                         // [128]
+    float *live_s = ycode + 128;                                     // [1] 1 if any selected shard holds entries
 
     const int cgroups = p.W / 4;                 // float4 column groups: 4..32
     const int slices = THREADS / cgroups;        // partial slices
@@ -167,6 +169,7 @@ __device__ __forceinline__ void combine_head(const CombineParams &p, int bh, uns
         }
         if (p.row_max) p.row_max[bh] = M;
         if (p.row_norm) p.row_norm[bh] = norm;
+        *live_s = M > -INFINITY ? 1.0f : 0.0f;
     }
     __syncthreads();
     // weight of every partial: shard weight * exp(m_split - M_shard)
@@ -220,13 +223,14 @@ __device__ __forceinline__ void combine_head(const CombineParams &p, int bh, uns
             ycode[tid * 4 + 3] = t.w;
         }
     }
-    if (p.rank != 0) {  // value decoder: y = ycode U_V[h']
+    if (p.rank != 0) {  // value decoder: y = ycode U_V[h'] (+ b[h'], the weights of a row sum to one)
         __syncthreads();
-        const T *U = static_cast<const T *>(p.U_V) + (int64_t)hk * p.rank * p.D;
+        const T *U = static_cast<const T *>(p.U_V) + (int64_t)hk * (p.rank + p.value_bias) * p.D;
         for (int d = tid; d < p.D; d += THREADS) {
             float a2 = 0.0f;
             for (int cidx = 0; cidx < p.rank; ++cidx)
                 a2 = fmaf(ycode[cidx], load_scalar<T>(U, (int64_t)cidx * p.D + d), a2);
+            if (p.value_bias && *live_s != 0.0f) a2 += load_scalar<T>(U, (int64_t)p.rank * p.D + d);
             p.y[(int64_t)bh * p.D + d] = a2;
         }
     }

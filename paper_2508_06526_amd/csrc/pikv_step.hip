@@ -23,6 +23,7 @@
 #include "pikv_combine_dev.h"
 #include "pikv_route_dev.h"
 #include "pikv_policy_dev.h"
+#include "pikv_penalty_dev.h"
 
 namespace pikv {
 namespace {
@@ -185,6 +186,8 @@ struct PostParams {
     float decay;
     int track;            // access bookkeeping: mass above pol.threshold stamps and counts the entry
     PolicyView pol;
+    int feedback;         // the grid's last block runs the router's penalty update (fb)
+    PenaltyParams fb;
 };
 
 // LDS of a utility block: statistics of the Hq * k (head, shard) pairs, the gates, and two
@@ -208,6 +211,10 @@ __global__ __launch_bounds__(THREADS) void step_post(PostParams p) {
     const int ncomb = p.B * p.c.Hq;
     if ((int)blockIdx.x < ncomb) {
         combine_head<T, THREADS>(p.c, blockIdx.x, smem);
+        return;
+    }
+    if (p.feedback && blockIdx.x == gridDim.x - 1) {   // Table 1 penalty for the next step
+        if (threadIdx.x < kWave) penalty_wave(p.fb, threadIdx.x);
         return;
     }
     const int Hq = p.c.Hq, k = p.c.k, nsplit = p.c.nsplit;
@@ -328,7 +335,7 @@ static int decode_step(const pikv_desc *desc, const void *q, const void *W_r, co
                        int32_t *topk_idx, float *gates, int32_t *evicted_idx, int32_t *evicted_cnt,
                        float *y, float *row_max, float *row_norm, float *scores, float *slot_coef,
                        void *workspace, size_t workspace_bytes, void *stream,
-                       const pikv_policy_args *pa) {
+                       const pikv_policy_args *pa, const pikv_router_feedback *fb) {
     const int rc = check_desc(desc);
     if (rc != PIKV_OK) return rc;
     PolicyView pol = {};
@@ -353,6 +360,19 @@ static int decode_step(const pikv_desc *desc, const void *q, const void *W_r, co
     if (!q || !W_r || !K_shards || !V_shards || !n_valid || !utility || !topk_idx || !gates || !y ||
         !scores || !slot_coef)
         return PIKV_ERR_INVALID;
+    PenaltyParams pen = {};
+    if (fb != nullptr) {
+        const int frc = check_penalty(fb->mode, fb->load, fb->miss, fb->coef, fb->bias, desc->E);
+        if (frc != PIKV_OK) return frc;
+        pen.mode = fb->mode;
+        pen.topk = topk_idx;
+        pen.n_sel = desc->B * k;
+        pen.E = desc->E;
+        pen.load = fb->load;
+        pen.miss = fb->miss;
+        pen.coef = fb->coef;
+        pen.bias = fb->bias;
+    }
     if ((K_new == nullptr) != (V_new == nullptr)) return PIKV_ERR_INVALID;
     if (K_new && (!evicted_idx || !evicted_cnt)) return PIKV_ERR_INVALID;
     if (k < 1 || k > desc->E) return PIKV_ERR_INVALID;
@@ -420,11 +440,15 @@ static int decode_step(const pikv_desc *desc, const void *q, const void *W_r, co
         lrc = pikv_sharded_attn_merge(desc, &c, stream);
         if (lrc != PIKV_OK) return lrc;
         if (track)
-            return pikv_update_utility_tracked(desc, scores, slot_coef, n_valid, topk_idx, k, decay,
-                                               utility, pol.threshold, pol.now, pol.last_access,
-                                               pol.freq, stream);
-        return pikv_update_utility(desc, scores, slot_coef, n_valid, topk_idx, k, decay, utility,
-                                   stream);
+            lrc = pikv_update_utility_tracked(desc, scores, slot_coef, n_valid, topk_idx, k, decay,
+                                              utility, pol.threshold, pol.now, pol.last_access,
+                                              pol.freq, stream);
+        else
+            lrc = pikv_update_utility(desc, scores, slot_coef, n_valid, topk_idx, k, decay, utility,
+                                      stream);
+        if (lrc != PIKV_OK || fb == nullptr) return lrc;
+        return pikv_router_penalty(fb->mode, topk_idx, desc->B, k, desc->E, fb->load, fb->miss, fb->coef,
+                                   fb->bias, stream);
     }
     PostParams pp;
     pp.c = c;
@@ -450,7 +474,9 @@ static int decode_step(const pikv_desc *desc, const void *q, const void *W_r, co
     pp.tiles_per_block = (int)tpb;
     pp.tiles = (int)((slot_tiles + tpb - 1) / tpb);
     pp.decay = decay;
-    const int64_t blocks = (int64_t)desc->B * desc->Hq + (int64_t)desc->B * k * pp.tiles;
+    pp.feedback = fb != nullptr;
+    pp.fb = pen;
+    const int64_t blocks = (int64_t)desc->B * desc->Hq + (int64_t)desc->B * k * pp.tiles + (fb ? 1 : 0);
     if (blocks > 0x7fffffff) return PIKV_ERR_UNSUPPORTED;
     const dim3 grid((unsigned)blocks);
     const bool f32 = desc->dtype == PIKV_F32;
@@ -482,7 +508,7 @@ extern "C" int pikv_decode_step(const pikv_desc *desc, const void *q, const void
                                 void *workspace, size_t workspace_bytes, void *stream) {
     return decode_step(desc, q, W_r, bias, K_new, V_new, K_shards, V_shards, U_K, U_V, n_valid, utility,
                        k, combine, scale, decay, topk_idx, gates, evicted_idx, evicted_cnt, y, row_max,
-                       row_norm, scores, slot_coef, workspace, workspace_bytes, stream, nullptr);
+                       row_norm, scores, slot_coef, workspace, workspace_bytes, stream, nullptr, nullptr);
 }
 
 extern "C" int pikv_decode_step_policy(const pikv_desc *desc, const void *q, const void *W_r,
@@ -493,9 +519,10 @@ extern "C" int pikv_decode_step_policy(const pikv_desc *desc, const void *q, con
                                        float *gates, int32_t *evicted_idx, int32_t *evicted_cnt,
                                        float *y, float *row_max, float *row_norm, float *scores,
                                        float *slot_coef, void *workspace, size_t workspace_bytes,
-                                       void *stream, const pikv_policy_args *policy) {
+                                       void *stream, const pikv_policy_args *policy,
+                                       const pikv_router_feedback *feedback) {
     return decode_step(desc, q, W_r, bias, K_new, V_new, K_shards, V_shards, U_K, U_V, n_valid, utility,
                        k, combine, scale, decay, topk_idx, gates, evicted_idx, evicted_cnt, y, row_max,
-                       row_norm, scores, slot_coef, workspace, workspace_bytes, stream, policy);
+                       row_norm, scores, slot_coef, workspace, workspace_bytes, stream, policy, feedback);
 }
 

@@ -143,6 +143,7 @@ def test_host_side_argument_errors_of_the_widened_entry_points(lib):
 
     rp = lib.pikv_router_penalty
     assert rp(7, fake, 1, 2, 8, fake, None, 0.1, fake, None) == INVALID
+    assert rp(3, fake, 1, 2, 8, fake, None, 0.1, fake, None) == INVALID           # modes are 0, 1, 2
     assert rp(0, fake, 1, 2, 8, None, None, 0.1, fake, None) == INVALID
     assert rp(0, fake, 1, 2, 65, fake, None, 0.1, fake, None) == INVALID
     assert rp(1, fake, 1, 2, 8, fake, None, 0.1, fake, None) == INVALID           # cache-aware needs miss
@@ -169,13 +170,13 @@ def test_host_side_argument_errors_of_the_widened_entry_points(lib):
     assert tr(C.byref(pk.make_desc(0, 4, 4, 64, 8, 256, dtype=1)), fake, fake, fake, fake, 2, 1.0, None, 0.1, 5,
               fake, fake, None) == 0
 
-    lib.pikv_decode_step_policy.argtypes = list(lib.pikv_decode_step.argtypes) + [vp]
+    lib.pikv_decode_step_policy.argtypes = list(lib.pikv_decode_step.argtypes) + [vp, vp]
     lib.pikv_decode_step_policy.restype = C.c_int
 
     def pstep(args):
         return lib.pikv_decode_step_policy(C.byref(d), fake, fake, None, fake, fake, fake, fake, None, None, fake,
                                            fake, 2, 0, 0.0, 1.0, fake, fake, fake, fake, fake, None, None, fake,
-                                           fake, fake, 1 << 30, None, C.cast(C.pointer(args), vp))
+                                           fake, fake, 1 << 30, None, C.cast(C.pointer(args), vp), None)
     fakeptr = 0x1000
     bad = pk.PikvPolicyArgs(policy=9, now=1)
     assert pstep(bad) == INVALID
@@ -185,6 +186,17 @@ def test_host_side_argument_errors_of_the_widened_entry_points(lib):
                                    threshold=-1.0)) == INVALID                                   # tracking threshold
     assert pstep(pk.PikvPolicyArgs(policy=pk.POLICY_LRU_PLUS, now=1, lam=float("nan"), last_access=fakeptr,
                                    freq=fakeptr)) == INVALID
+    def fstep(fb):
+        return lib.pikv_decode_step_policy(C.byref(d), fake, fake, None, fake, fake, fake, fake, None, None, fake,
+                                           fake, 2, 0, 0.0, 1.0, fake, fake, fake, fake, fake, None, None, fake,
+                                           fake, fake, 1 << 30, None, None, C.cast(C.pointer(fb), vp))
+    assert fstep(pk.PikvRouterFeedback(mode=5, coef=0.1, load=fakeptr, bias=fakeptr)) == INVALID
+    assert fstep(pk.PikvRouterFeedback(mode=0, coef=0.1, load=None, bias=fakeptr)) == INVALID
+    assert fstep(pk.PikvRouterFeedback(mode=1, coef=0.1, load=fakeptr, bias=fakeptr)) == INVALID   # needs miss
+    assert fstep(pk.PikvRouterFeedback(mode=2, coef=float("nan"), load=fakeptr, bias=fakeptr)) == INVALID
+    # descriptor flags: only the value-bias bit, and only with codes
+    assert step(desc=pk.make_desc(2, 4, 4, 64, 8, 256, dtype=1, flags=1)) == INVALID
+    assert step(desc=pk.make_desc(2, 4, 4, 64, 8, 256, dtype=1, flags=2)) == INVALID
     pc = lib.pikv_policy_compact
     assert pc(C.byref(d), None, fake, 4, fake, fake, fake, fake, None) == INVALID
     assert pc(C.byref(d), fake, fake, 0, fake, fake, fake, fake, None) == INVALID

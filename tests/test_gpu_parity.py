@@ -624,7 +624,7 @@ def test_fused_decode_step_without_insert_and_unsupported_shapes():
 
 
 # ------------------------------------------------ widened rows: router penalties, compress-on-insert
-@pytest.mark.parametrize("mode", [0, 1], ids=["load_balance", "cache_aware"])
+@pytest.mark.parametrize("mode", [0, 1, 2], ids=["load_balance", "cache_aware", "entropy"])
 def test_router_penalty_matches_oracle_and_closes_the_loop(mode):
     """Table 1 penalty terms kept on the device: counters exact, bias to fp32 rounding, and the
     penalised routing decisions of a 10-step chain equal the oracle's."""
@@ -639,7 +639,7 @@ def test_router_penalty_matches_oracle_and_closes_the_loop(mode):
     miss_d = torch.from_numpy(miss_h).to(DEV)
     bias_d = torch.zeros(g.E, device=DEV)
     dc.bias = bias_d
-    coef = 0.05 if mode == 0 else 0.3
+    coef = (0.05, 0.3, 4.0)[mode]
     bias_h = np.zeros(g.E, np.float32)
     for step in range(10):
         probe = case.clone()
@@ -656,6 +656,104 @@ def test_router_penalty_matches_oracle_and_closes_the_loop(mode):
         np.testing.assert_array_equal(t2n(load_d), load_h)
         np.testing.assert_allclose(t2n(bias_d), bias_h, rtol=1e-5, atol=1e-6)
     assert load_h.sum() == 10 * g.route_rows * g.k
+
+
+@pytest.mark.parametrize("mode", [0, 1, 2], ids=["load_balance", "cache_aware", "entropy"])
+def test_router_feedback_inside_the_fused_step_equals_the_separate_penalty_call(mode):
+    """pikv_decode_step_policy with a pikv_router_feedback: the step's last launch updates the
+    load counters and the next step's bias exactly as pikv_router_penalty after the step would
+    (same bits, every step of a closed loop), and the loop's selections equal the oracle's."""
+    from gpu_harness import dev_storage
+    g = wl.Geometry(B=5, Hq=8, Hkv=4, D=64, E=8, S=40, k=2, dtype="bf16")
+    case = wl.make_host_case(g, seed=52, utility0="exp")
+    dA, dB = DeviceCase(case), DeviceCase(case)
+    rng = np.random.default_rng(4)
+    miss_h = rng.integers(0, 50, size=g.E).astype(np.int32)
+    coef = (0.05, 0.3, 4.0)[mode]
+    state = {}
+    for name, d in (("A", dA), ("B", dB)):
+        state[name] = dict(load=torch.zeros(g.E, device=DEV, dtype=torch.int32), miss=torch.from_numpy(miss_h).to(DEV),
+                           bias=torch.zeros(g.E, device=DEV),
+                           ei=torch.full((g.B, g.E, 1), -1, device=DEV, dtype=torch.int32),
+                           ec=torch.zeros((g.B, g.E), device=DEV, dtype=torch.int32))
+        d.bias = state[name]["bias"]
+    fb = pk.make_router_feedback(mode, coef, state["A"]["load"], state["A"]["bias"], miss=state["A"]["miss"])
+    load_h, bias_h = np.zeros(g.E, np.int32), np.zeros(g.E, np.float32)
+    for step in range(8):
+        probe = case.clone()
+        probe.q = wl.draw_queries(g, 400 + step)
+        probe.bias = bias_h
+        ensure_route_margin(probe, g.k)
+        kn, vn = wl.draw_new_kv(g, 450 + step)
+        dkn, dvn = dev_storage(kn, g.dtype), dev_storage(vn, g.dtype)
+        for d in (dA, dB):
+            d.q.copy_(dev_storage(probe.q, g.dtype))
+        sA, sB = state["A"], state["B"]
+        pk.pikv_decode_step_policy(dA.desc, dA.q, dA.W_r, dA.bias, dkn, dvn, dA.K_tab, dA.V_tab, None, None,
+                                   dA.n_valid, dA.utility, g.k, pk.COMBINE_LSE, 0.0, 0.9, dA.topk, dA.gates,
+                                   sA["ei"], sA["ec"], dA.y, dA.row_max, dA.row_norm, dA.scores, dA.slot_coef,
+                                   dA.workspace, None, feedback=fb)
+        pk.pikv_decode_step(dB.desc, dB.q, dB.W_r, dB.bias, dkn, dvn, dB.K_tab, dB.V_tab, None, None,
+                            dB.n_valid, dB.utility, g.k, pk.COMBINE_LSE, 0.0, 0.9, dB.topk, dB.gates,
+                            sB["ei"], sB["ec"], dB.y, dB.row_max, dB.row_norm, dB.scores, dB.slot_coef,
+                            dB.workspace)
+        pk.pikv_router_penalty(mode, dB.topk, g.route_rows, g.k, g.E, sB["load"], sB["miss"], coef, sB["bias"])
+        for name in ("topk", "y", "utility", "n_valid"):
+            np.testing.assert_array_equal(t2n(getattr(dA, name)), t2n(getattr(dB, name)), err_msg=name)
+        np.testing.assert_array_equal(t2n(sA["load"]), t2n(sB["load"]))
+        np.testing.assert_array_equal(t2n(sA["bias"]).view(np.uint32), t2n(sB["bias"]).view(np.uint32))
+        # the oracle's closed loop
+        x = np.ascontiguousarray(probe.q.reshape(g.route_rows, g.d_r))
+        idx, _, _ = orc.route(x, case.W_r, g.k, bias=bias_h, dtype=g.dtype)
+        np.testing.assert_array_equal(t2n(dA.topk), idx)
+        bias_h = orc.router_penalty(mode, idx, load_h, coef, miss=miss_h)
+        np.testing.assert_array_equal(t2n(sA["load"]), load_h)
+        np.testing.assert_allclose(t2n(sA["bias"]), bias_h, rtol=1e-5, atol=1e-6)
+
+
+@pytest.mark.parametrize("spec", [
+    dict(B=3, Hq=4, Hkv=4, D=128, E=4, S=300, k=2, dtype="bf16", rank=32),
+    dict(B=2, Hq=8, Hkv=2, D=64, E=4, S=130, k=3, dtype="f32", rank=16),
+    dict(B=2, Hq=4, Hkv=4, D=128, E=3, S=200, k=2, dtype="bf16", rank=64),
+], ids=["bf16_r32", "f32_r16_gqa4", "bf16_r64"])
+@pytest.mark.parametrize("combine", [orc.COMBINE_LSE, orc.COMBINE_LOCAL], ids=["lse", "local"])
+def test_value_decoder_bias_matches_oracle(spec, combine):
+    """Table 2 row LoRA++ on the value side: U_V carries one more row per kv head, the additive
+    term of the decoder; outputs against the oracle's explicit decode with that term, an empty
+    selection still gives zero, utilities are those of the run without the term."""
+    from gpu_harness import dev_storage
+    g = wl.Geometry(**spec)
+    case = wl.make_host_case(g, seed=61, n_valid="ragged", utility0="exp")
+    case.n_valid[-1, :] = 0                                   # the last sequence: every shard empty
+    ensure_route_margin(case, g.k)
+    rng = np.random.default_rng(62)
+    b_V = wl.encode(rng.standard_normal((g.Hkv, g.D)), g.dtype)
+    dc = DeviceCase(case)
+    UVb = np.concatenate([case.U_V, b_V[:, None, :]], axis=1)            # [Hkv, rank + 1, D]
+    dc.U_V = dev_storage(np.ascontiguousarray(UVb), g.dtype)
+    dc.desc = pk.make_desc(g.B, g.Hq, g.Hkv, g.D, g.E, g.S, rank=g.rank,
+                           dtype=pk.binding.F32 if g.dtype == "f32" else pk.binding.BF16,
+                           stride_h=dc.stride_h, stride_s=dc.stride_s, flags=pk.DESC_VALUE_BIAS)
+    dc.route()
+    dc.attend(combine=combine)
+    dc.update_utility(1.0)
+    idx, gates = t2n(dc.topk), t2n(dc.gates)
+    u_ref = case.utility.copy()
+    ref = orc.attend(case.q, case.K_shards, case.V_shards, case.n_valid, idx, gates, Hkv=g.Hkv, E=g.E, S=g.S,
+                     dtype=g.dtype, rank=g.rank, U_K=case.U_K, U_V=case.U_V, V_bias=b_V, combine=combine,
+                     utility=u_ref)
+    y = t2n(dc.y)
+    ok, emax, l2 = y_tolerance_ok(y, ref["y"], g.dtype)
+    assert ok, (emax, l2)
+    assert (y[-1] == 0).all()
+    assert_utility_close(t2n(dc.utility), u_ref)
+    # and the difference to the run without the term is the term itself
+    plain = DeviceCase(case)
+    plain.route()
+    plain.attend(combine=combine)
+    diff = y[:-1] - t2n(plain.y)[:-1]
+    want = wl.decode(b_V, g.dtype)[np.arange(g.Hq) // (g.Hq // g.Hkv)][None]
+    np.testing.assert_allclose(diff, np.broadcast_to(want, diff.shape), rtol=1e-5, atol=1e-5)
 
 
 @pytest.mark.parametrize("spec", [
