@@ -84,7 +84,8 @@ def parse_args():
 
 # layer instances so that consecutive steps cannot be served from the 256 MB Infinity Cache
 DEFAULT_LAYERS = {"c1_tiny_f32": 1, "c2_bf16_decode": 2, "c3_long_context": 32, "c4_streaming": 2,
-                  "c5_compressed": 16, "c3_long_context_tq4": 32}
+                  "c5_compressed": 16, "c3_long_context_tq4": 32, "c3_long_context_tq8": 32,
+                  "c3_kv4_tq16": 32}
 RECIPE = {  # how each configuration's inputs are drawn (workloads.make_device_layers arguments)
     "c1_tiny_f32": dict(w_sigma=1.0),
     "c2_bf16_decode": dict(kv="lognormal_token"),
@@ -92,6 +93,8 @@ RECIPE = {  # how each configuration's inputs are drawn (workloads.make_device_l
     "c4_streaming": dict(utility0="exp"),
     "c5_compressed": dict(zipf_s=1.1),
     "c3_long_context_tq4": dict(zipf_s=1.1, w_sigma=0.01),
+    "c3_long_context_tq8": dict(zipf_s=1.1, w_sigma=0.007),
+    "c3_kv4_tq16": dict(zipf_s=1.1, w_sigma=0.007),
 }
 DECAY = {"c4_streaming": 0.9}
 OTHER_WORKLOADS = ("c2_bf16_decode", "c4_streaming", "c5_compressed")
@@ -105,7 +108,8 @@ class Layer:
         g = geo
         self.desc = pk.make_desc(g.B, g.Hq, g.Hkv, g.D, g.E, g.S, rank=g.rank,
                                  dtype=0 if g.dtype == "f32" else 1,
-                                 route_rows_per_seq=g.Hq if g.per_head_routing else 1)
+                                 route_rows_per_seq=g.Hq if g.per_head_routing else 1,
+                                 tq=g.tq if g.token_major else 1)
         self.K_tab = pk.shard_table(tensors["K"])
         self.V_tab = pk.shard_table(tensors["V"])
         self.decay = DECAY.get(g.name, 1.0)
@@ -165,7 +169,8 @@ def make_shared(pk, torch, geo, dev):
     tdt = torch.float32 if g.dtype == "f32" else torch.bfloat16
     R, k = g.route_rows, g.k
     desc = pk.make_desc(g.B, g.Hq, g.Hkv, g.D, g.E, g.S, rank=g.rank, dtype=0 if g.dtype == "f32" else 1,
-                        route_rows_per_seq=g.Hq if g.per_head_routing else 1)
+                        route_rows_per_seq=g.Hq if g.per_head_routing else 1,
+                        tq=g.tq if g.token_major else 1)
     gen = torch.Generator(device=dev)
     gen.manual_seed(12345)
     return dict(
@@ -186,8 +191,8 @@ def make_shared(pk, torch, geo, dev):
 
 def attn_kernel_name(geo):
     g = geo.Hq // geo.Hkv
-    if geo.dtype == "bf16" and geo.rank == 0 and geo.D == 128 and not geo.per_head_routing and 2 <= g <= 16:
-        return "attn_partial_gqa128"
+    if geo.dtype == "bf16" and geo.rank == 0 and geo.D == 128 and not geo.per_head_routing and 2 <= g <= 64:
+        return "attn_partial_gqa128<%d>" % (1 if g <= 16 else 2 if g <= 32 else 4)
     gb = g if (not geo.per_head_routing and g in (2, 4, 8)) else 1
     return "attn_partial<%s, %d, %d>" % ("pikv::bf16" if geo.dtype == "bf16" else "float", geo.width, gb)
 

@@ -70,7 +70,20 @@ typedef struct pikv_desc {
     int64_t stride_s; /* elements between slots (>= width, multiple of 16 bytes)           */
     int32_t route_rows_per_seq; /* 1 or Hq                                                 */
     int32_t flags;    /* 0, or PIKV_DESC_VALUE_BIAS (rank > 0 only)                        */
+    int32_t tq;       /* draft queries per sequence in a multi-query step; 0 or 1: one query */
+    int32_t reserved; /* must be 0                                                         */
 } pikv_desc;
+
+/* Multi-query (speculative decoding) steps: tq > 1 draft queries of a sequence attend the same
+ * selected shards in one pass, so every K/V byte is streamed once for all of them.  Hq then
+ * counts ALL query rows of a sequence, Hq = tq * (query heads of the model), and q, y, row_max
+ * and row_norm are laid out [B, tq, Hq / tq, ...] - the natural layout of tq consecutive
+ * tokens.  One routing decision is made per sequence from the whole [tq * heads * D] vector
+ * (W_r has Hq * D rows).  Each row attends all valid entries of the selected shards; the causal
+ * part among the drafts themselves is the caller's (row_max / row_norm let it merge them).
+ * Supported for bfloat16 rows of D = 128 values (rank 0) with per-token routing and at most 64
+ * query rows per kv head (Hq / Hkv <= 64); UNSUPPORTED otherwise.
+ * scores and slot_coef stay internal scratch in every case.                               */
 
 /* desc->flags.  PIKV_DESC_VALUE_BIAS: the value decoder has the additive term of Table 2's
  * LoRA++ row (reconstruction W_d W_u x + b): U_V then holds rank + 1 rows of D values per kv

@@ -35,7 +35,8 @@ class PikvDesc(C.Structure):
     _fields_ = [("B", C.c_int32), ("Hq", C.c_int32), ("Hkv", C.c_int32), ("D", C.c_int32),
                 ("E", C.c_int32), ("S", C.c_int32), ("rank", C.c_int32), ("dtype", C.c_int32),
                 ("stride_h", C.c_int64), ("stride_s", C.c_int64),
-                ("route_rows_per_seq", C.c_int32), ("flags", C.c_int32)]
+                ("route_rows_per_seq", C.c_int32), ("flags", C.c_int32), ("tq", C.c_int32),
+                ("reserved", C.c_int32)]
 
     @property
     def width(self):
@@ -140,13 +141,13 @@ def _check(status, where):
 
 
 def make_desc(B, Hq, Hkv, D, E, S, rank=0, dtype=BF16, stride_h=None, stride_s=None,
-              route_rows_per_seq=1, flags=0) -> PikvDesc:
+              route_rows_per_seq=1, flags=0, tq=1) -> PikvDesc:
     w = rank if rank else D
     if stride_s is None:
         stride_s = w
     if stride_h is None:
         stride_h = S * stride_s
-    return PikvDesc(B, Hq, Hkv, D, E, S, rank, dtype, stride_h, stride_s, route_rows_per_seq, flags)
+    return PikvDesc(B, Hq, Hkv, D, E, S, rank, dtype, stride_h, stride_s, route_rows_per_seq, flags, tq, 0)
 
 
 def shard_table(shards, device=None):

@@ -10,7 +10,7 @@ int check_desc(const pikv_desc *d) {
     if (d->Hq % d->Hkv != 0) return PIKV_ERR_INVALID;
     if (d->dtype != PIKV_F32 && d->dtype != PIKV_BF16) return PIKV_ERR_INVALID;
     if (d->route_rows_per_seq != 1 && d->route_rows_per_seq != d->Hq) return PIKV_ERR_INVALID;
-    if (d->rank < 0) return PIKV_ERR_INVALID;
+    if (d->rank < 0 || d->tq < 0 || d->reserved != 0) return PIKV_ERR_INVALID;
     if ((d->flags & PIKV_DESC_VALUE_BIAS) && d->rank == 0) return PIKV_ERR_INVALID;
     if (d->Hq > 256 || d->E > 64) return PIKV_ERR_UNSUPPORTED;
     if (d->D != 16 && d->D != 32 && d->D != 64 && d->D != 128) return PIKV_ERR_UNSUPPORTED;

@@ -39,13 +39,17 @@ struct AttnParams {
     int B, Hq, G, D, E, S, k, rr, rank;
     int64_t stride_h, stride_s;
     int nsplit, chunk;
-    int stage_scores;   // plain-ALU kernel: keep the block's scores in LDS, write them at the end
+    int tq;             // draft queries per sequence: q is [B, tq, Hq / tq, D] (1: plain [B, Hq, D])
+    int stage_scores;   // keep the block's scores in LDS, write them in one burst at the end
     int stream_scores;  // ... with non-temporal stores
     float scale;
 };
 
 // Raw scores of at most this many bytes per block are staged in LDS (plain-ALU kernel).
 constexpr int kScoreStageBytes = 16384;
+// LDS the matrix-core kernel's blocks hold for their tile staging (K tile, two P tiles, rescale
+// factors and wave statistics of 4 waves); their score stage comes on top
+constexpr size_t kGqaStaticLds = 4 * (32 * 272 + 2 * 16 * 80 + 16 * 4 + 2 * 16 * 4);
 
 // Resolve the j-th selected shard of a routing row with ONE round trip to memory: the
 // expert id is fetched while lanes 0..E-1 fetch the entry count and the K/V base address of
@@ -72,6 +76,18 @@ __device__ __forceinline__ ShardRef resolve_shard(const AttnParams &p, int b, in
     out.K = reinterpret_cast<const char *>(((uint64_t)khi << 32) | klo);
     out.V = reinterpret_cast<const char *>(((uint64_t)vhi << 32) | vlo);
     return out;
+}
+
+// Where the caller keeps the query of internal row h of sequence b, in rows of D values.
+// Internally the rows of a sequence are ordered (kv head, draft query, head of the group), so
+// that all rows reading one kv head are adjacent; the caller's q is [B, tq, heads, D].
+__device__ __forceinline__ int64_t query_row(const AttnParams &p, int b, int h) {
+    if (p.tq <= 1) return (int64_t)b * p.Hq + h;
+    const int heads = p.Hq / p.tq;             // query heads of one draft query
+    const int g = p.G / p.tq;                  // of them, per kv head
+    const int hk = h / p.G, rem = h - hk * p.G;
+    const int t = rem / g, gg = rem - t * g;
+    return ((int64_t)b * p.tq + t) * heads + hk * g + gg;
 }
 
 template <typename T, int W, int GB>
@@ -382,14 +398,33 @@ __device__ __forceinline__ void wave_lds_order() {
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-__global__ __launch_bounds__(kWavesPerBlock *kWave, 3) void attn_partial_gqa128(AttnParams p) {
+// RT = number of 16-row tiles the query group occupies (group rows = query heads per kv head
+// times the draft queries of a multi-query step): 1, 2 or 4.  Every row tile reuses the K tile
+// staged in LDS and the V rows in registers, so the streamed bytes do not grow with RT; the
+// accumulators do (32 registers per row tile), which is why a CU holds 3 blocks at RT = 1 and 2
+// above.  For RT = 4 the query operands live in LDS instead of registers.
+template <int RT>
+struct GqaShape {
+    static constexpr int kBlocksPerCU = RT == 1 ? 3 : 2;
+    static constexpr bool kQueryInLds = RT > 2;
+    // RT = 4: the 128 accumulator registers leave no room to hold the next K tile across the
+    // whole tile's arithmetic; K is then loaded where it is used and the CU's other waves hide
+    // the latency (at four row tiles the kernel is bound by the matrix cores, not by memory).
+    static constexpr bool kPrefetchK = RT < 4;
+};
+
+template <int RT>
+__global__ __launch_bounds__(kWavesPerBlock *kWave, GqaShape<RT>::kBlocksPerCU) void attn_partial_gqa128(
+    AttnParams p) {
     constexpr int W = 128;
+    constexpr bool QLDS = GqaShape<RT>::kQueryInLds;
+    constexpr bool KPRE = GqaShape<RT>::kPrefetchK;
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
     const int wave = tid >> 6;
     const int c = lane & 15;
     const int r = lane >> 4;
-    const int gb = p.G;                       // heads per block = the whole query group
+    const int gb = p.G;                       // rows per block = the whole query group
 
     // Workgroups go to the 8 XCDs round-robin by id.  Giving each XCD a contiguous range of
     // work items - whole (kv head, shard) units, whose splits share score rows and partial
@@ -415,6 +450,10 @@ __global__ __launch_bounds__(kWavesPerBlock *kWave, 3) void attn_partial_gqa128(
     __shared__ __attribute__((aligned(16))) float lds_corr[kWavesPerBlock][16];
     __shared__ float sm_m[kWavesPerBlock][16];
     __shared__ float sm_l[kWavesPerBlock][16];
+    __shared__ __attribute__((aligned(16))) unsigned char lds_q[QLDS ? RT * 16 * kGqaKPitch : 16];
+    // Raw scores of the block's rows, [rows of the group][chunk], when p.stage_scores (see
+    // attn_partial): written to memory in one contiguous burst per row after the streaming loop.
+    extern __shared__ __attribute__((aligned(16))) float gqa_stage[];
 
     const int64_t part_base = (((int64_t)b * p.Hq + h0) * p.k + j) * p.nsplit + split;
     const int64_t part_head_stride = (int64_t)p.k * p.nsplit;
@@ -453,26 +492,45 @@ __global__ __launch_bounds__(kWavesPerBlock *kWave, 3) void attn_partial_gqa128(
     };
     int t0 = r0 + __builtin_amdgcn_readfirstlane(wave) * kGqaTile;
     if (t0 < r1) {
-        load_tile(kr, Kb, t0);
+        if constexpr (KPRE) load_tile(kr, Kb, t0);
         load_tile(vr, Vb, t0);
     }
 
-    // query operand: lane (head c, group r) holds Q[h0 + c][32 s + 8 r .. +7], s = 0..3
-    bf16x8_t qop[4];
-    {
-        const bf16 *qrow = static_cast<const bf16 *>(p.q) + ((int64_t)b * p.Hq + h0 + min(c, gb - 1)) * W;
+    // query operand of row tile rt: lane (row c, group r) holds Q[row rt*16 + c][32 s + 8 r .. +7],
+    // s = 0..3 (zero for rows past the group).  The group's rows are the query rows
+    // h0 .. h0 + gb - 1 of the sequence; query_row() maps a group row to where the caller keeps it.
+    bf16x8_t qop[QLDS ? 1 : RT][4];
+    if constexpr (QLDS) {
+        for (int idx = tid; idx < RT * 16 * 16; idx += blockDim.x) {     // (row, 16-byte chunk)
+            const int row = idx >> 4, ch = idx & 15;
+            uint4 v = make_uint4(0, 0, 0, 0);
+            if (row < gb) v = load16(static_cast<const bf16 *>(p.q) + query_row(p, b, h0 + row) * W + 8 * ch);
+            *reinterpret_cast<uint4 *>(lds_q + row * kGqaKPitch + 16 * ch) = v;
+        }
+        __syncthreads();
+    } else {
 #pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            uint4 v = load16(qrow + 32 * s + 8 * r);
-            if (c >= gb) v = make_uint4(0, 0, 0, 0);
-            qop[s] = __builtin_bit_cast(bf16x8_t, v);
+        for (int rt = 0; rt < RT; ++rt) {
+            const int row = rt * 16 + c;
+            const bf16 *qrow = static_cast<const bf16 *>(p.q) + query_row(p, b, h0 + min(row, gb - 1)) * W;
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                uint4 v = load16(qrow + 32 * s + 8 * r);
+                if (row >= gb) v = make_uint4(0, 0, 0, 0);
+                qop[rt][s] = __builtin_bit_cast(bf16x8_t, v);
+            }
         }
     }
 
-    float m = -INFINITY, lsum = 0.0f;      // running max / partial sum of head c
-    f32x4_t oacc[8];                        // oacc[i][x] = O[head 4r + x][d = 8c + i]
+    float m[RT], lsum[RT];                  // running max / partial sum of row rt*16 + c
+    f32x4_t oacc[RT][8];                    // oacc[rt][i][x] = O[row rt*16 + 4r + x][d = 8c + i]
 #pragma unroll
-    for (int i = 0; i < 8; ++i) oacc[i] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    for (int rt = 0; rt < RT; ++rt) {
+        m[rt] = -INFINITY;
+        lsum[rt] = 0.0f;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) oacc[rt][i] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    }
 
     unsigned char *kst = lds_k[wave];
     unsigned char *pst_hi = lds_p[wave][0];
@@ -482,156 +540,203 @@ __global__ __launch_bounds__(kWavesPerBlock *kWave, 3) void attn_partial_gqa128(
         const int tnext = t0 + kWavesPerBlock * kGqaTile;
 
         // K rows -> LDS (row-major, padded), then the next tile's K loads reuse the registers
+        if constexpr (!KPRE) load_tile(kr, Kb, t0);
 #pragma unroll
         for (int t = 0; t < 8; ++t)
             *reinterpret_cast<uint4 *>(kst + (8 * r + t) * kGqaKPitch + 16 * c) = kr[t];
-        if (tnext < r1) load_tile(kr, Kb, tnext);
+        if constexpr (KPRE) {
+            if (tnext < r1) load_tile(kr, Kb, tnext);
+        }
         wave_lds_order();
 
-        // S^T = K Q^T for the two 16-entry halves of the tile
-        f32x4_t sc[2];
 #pragma unroll
-        for (int hb = 0; hb < 2; ++hb) {
-            sc[hb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int s = 0; s < 4; ++s) {
-                const uint4 a = *reinterpret_cast<const uint4 *>(kst + (16 * hb + c) * kGqaKPitch + 64 * s + 16 * r);
-                sc[hb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a), qop[s],
-                                                                sc[hb], 0, 0, 0);
-            }
-        }
-        // lane (head c, group r): sc[hb][x] is the score of entry t0 + 16 hb + 4 r + x
-        float sv[8];
-#pragma unroll
-        for (int hb = 0; hb < 2; ++hb)
-#pragma unroll
-            for (int x = 0; x < 4; ++x) {
-                const int row = t0 + 16 * hb + 4 * r + x;
-                sv[hb * 4 + x] = row < r1 ? sc[hb][x] * p.scale : -INFINITY;
-            }
-        if (p.scores != nullptr && c < gb) {
-            float *dst = p.scores + (((int64_t)b * p.Hq + h0 + c) * p.k + j) * p.S + t0 + 4 * r;
+        for (int rt = 0; rt < RT; ++rt) {
+            if (rt * 16 >= gb) break;        // row tiles past the group (wave-uniform)
+            // S^T = K Q^T for the two 16-entry halves of the tile
+            f32x4_t sc[2];
 #pragma unroll
             for (int hb = 0; hb < 2; ++hb) {
-                const int row = t0 + 16 * hb + 4 * r;
-                if (row + 4 <= r1 && (p.S & 3) == 0) {
-                    *reinterpret_cast<float4 *>(dst + 16 * hb) =
-                        make_float4(sv[hb * 4], sv[hb * 4 + 1], sv[hb * 4 + 2], sv[hb * 4 + 3]);
-                } else {
+                sc[hb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                    for (int x = 0; x < 4; ++x)
-                        if (row + x < r1) dst[16 * hb + x] = sv[hb * 4 + x];
+                for (int s = 0; s < 4; ++s) {
+                    const uint4 a = *reinterpret_cast<const uint4 *>(kst + (16 * hb + c) * kGqaKPitch + 64 * s + 16 * r);
+                    bf16x8_t qv;
+                    if constexpr (QLDS)
+                        qv = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4 *>(
+                                                              lds_q + (rt * 16 + c) * kGqaKPitch + 64 * s + 16 * r));
+                    else
+                        qv = qop[rt][s];
+                    sc[hb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a), qv, sc[hb],
+                                                                    0, 0, 0);
                 }
             }
-        }
-
-        // online softmax for head c (entries are spread over the 4 lane groups)
-        float tm = sv[0];
+            // lane (row c, group r): sc[hb][x] is the score of entry t0 + 16 hb + 4 r + x
+            const int row_g = rt * 16 + c;   // row of the group this lane's scores belong to
+            float sv[8];
 #pragma unroll
-        for (int x = 1; x < 8; ++x) tm = fmaxf(tm, sv[x]);
-        tm = fmaxf(tm, __shfl_xor(tm, 16, kWave));
-        tm = fmaxf(tm, __shfl_xor(tm, 32, kWave));
-        const float mn = fmaxf(m, tm);
-        const float corr = __expf(m - mn);
-        m = mn;
-        lsum *= corr;
-        float pv[8];
+            for (int hb = 0; hb < 2; ++hb)
 #pragma unroll
-        for (int x = 0; x < 8; ++x) {
-            pv[x] = __expf(sv[x] - mn);
-            lsum += pv[x];
-        }
-        // probabilities as bf16 high part + bf16 residual, 4 consecutive entries per store
+                for (int x = 0; x < 4; ++x) {
+                    const int row = t0 + 16 * hb + 4 * r + x;
+                    sv[hb * 4 + x] = row < r1 ? sc[hb][x] * p.scale : -INFINITY;
+                }
+            if (p.scores != nullptr && row_g < gb && p.stage_scores) {
+                // [row of the group][row of the block]: chunk is a multiple of the tile, so the
+                // float4 stores stay aligned
+                float *dst = gqa_stage + row_g * p.chunk + (t0 - r0) + 4 * r;
 #pragma unroll
-        for (int hb = 0; hb < 2; ++hb) {
-            uint32_t hi2[2], lo2[2];
+                for (int hb = 0; hb < 2; ++hb)
+                    *reinterpret_cast<float4 *>(dst + 16 * hb) =
+                        make_float4(sv[hb * 4], sv[hb * 4 + 1], sv[hb * 4 + 2], sv[hb * 4 + 3]);
+            } else if (p.scores != nullptr && row_g < gb) {
+                float *dst = p.scores + (((int64_t)b * p.Hq + h0 + row_g) * p.k + j) * p.S + t0 + 4 * r;
 #pragma unroll
-            for (int q2 = 0; q2 < 2; ++q2) {
-                const f32x2_t v = {pv[hb * 4 + 2 * q2], pv[hb * 4 + 2 * q2 + 1]};
-                const bf16x2_t hi = __builtin_convertvector(v, bf16x2_t);
-                const f32x2_t back = {(float)hi[0], (float)hi[1]};
-                const bf16x2_t lo = __builtin_convertvector(v - back, bf16x2_t);
-                hi2[q2] = __builtin_bit_cast(uint32_t, hi);
-                lo2[q2] = __builtin_bit_cast(uint32_t, lo);
+                for (int hb = 0; hb < 2; ++hb) {
+                    const int row = t0 + 16 * hb + 4 * r;
+                    if (row + 4 <= r1 && (p.S & 3) == 0) {
+                        *reinterpret_cast<float4 *>(dst + 16 * hb) =
+                            make_float4(sv[hb * 4], sv[hb * 4 + 1], sv[hb * 4 + 2], sv[hb * 4 + 3]);
+                    } else {
+#pragma unroll
+                        for (int x = 0; x < 4; ++x)
+                            if (row + x < r1) dst[16 * hb + x] = sv[hb * 4 + x];
+                    }
+                }
             }
-            const int off = c * kGqaPPitch + (16 * hb + 4 * r) * 2;
-            *reinterpret_cast<uint2 *>(pst_hi + off) = make_uint2(hi2[0], hi2[1]);
-            *reinterpret_cast<uint2 *>(pst_lo + off) = make_uint2(lo2[0], lo2[1]);
-        }
-        if (r == 0) lds_corr[wave][c] = corr;
-        wave_lds_order();
 
-        // row operands P[head c][entries 8r..8r+7] and the rescale factors of heads 4r..4r+3
-        const bf16x8_t p_hi = __builtin_bit_cast(
-            bf16x8_t, *reinterpret_cast<const uint4 *>(pst_hi + c * kGqaPPitch + 16 * r));
-        const bf16x8_t p_lo = __builtin_bit_cast(
-            bf16x8_t, *reinterpret_cast<const uint4 *>(pst_lo + c * kGqaPPitch + 16 * r));
-        const float4 cr = *reinterpret_cast<const float4 *>(&lds_corr[wave][4 * r]);
+            // online softmax for row c of this tile (entries are spread over the 4 lane groups)
+            float tm = sv[0];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            oacc[i][0] *= cr.x;
-            oacc[i][1] *= cr.y;
-            oacc[i][2] *= cr.z;
-            oacc[i][3] *= cr.w;
-        }
-        // O += P V, output column set i takes the i-th value of each of the lane's 8 V rows
+            for (int x = 1; x < 8; ++x) tm = fmaxf(tm, sv[x]);
+            tm = fmaxf(tm, __shfl_xor(tm, 16, kWave));
+            tm = fmaxf(tm, __shfl_xor(tm, 32, kWave));
+            const float mn = fmaxf(m[rt], tm);
+            const float corr = __expf(m[rt] - mn);
+            m[rt] = mn;
+            lsum[rt] *= corr;
+            float pv[8];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const uint32_t sel = (i & 1) ? 0x07060302u : 0x05040100u;
-            uint32_t w[8];
-#pragma unroll
-            for (int t = 0; t < 8; ++t) {
-                const uint4 &v = vr[t];
-                w[t] = (i >> 1) == 0 ? v.x : (i >> 1) == 1 ? v.y : (i >> 1) == 2 ? v.z : v.w;
+            for (int x = 0; x < 8; ++x) {
+                pv[x] = __expf(sv[x] - mn);
+                lsum[rt] += pv[x];
             }
-            const uint4 packed = make_uint4(__builtin_amdgcn_perm(w[1], w[0], sel),
-                                            __builtin_amdgcn_perm(w[3], w[2], sel),
-                                            __builtin_amdgcn_perm(w[5], w[4], sel),
-                                            __builtin_amdgcn_perm(w[7], w[6], sel));
-            const bf16x8_t vop = __builtin_bit_cast(bf16x8_t, packed);
-            oacc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(p_hi, vop, oacc[i], 0, 0, 0);
-            oacc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(p_lo, vop, oacc[i], 0, 0, 0);
+            // probabilities as bf16 high part + bf16 residual, 4 consecutive entries per store
+#pragma unroll
+            for (int hb = 0; hb < 2; ++hb) {
+                uint32_t hi2[2], lo2[2];
+#pragma unroll
+                for (int q2 = 0; q2 < 2; ++q2) {
+                    const f32x2_t v = {pv[hb * 4 + 2 * q2], pv[hb * 4 + 2 * q2 + 1]};
+                    const bf16x2_t hi = __builtin_convertvector(v, bf16x2_t);
+                    const f32x2_t back = {(float)hi[0], (float)hi[1]};
+                    const bf16x2_t lo = __builtin_convertvector(v - back, bf16x2_t);
+                    hi2[q2] = __builtin_bit_cast(uint32_t, hi);
+                    lo2[q2] = __builtin_bit_cast(uint32_t, lo);
+                }
+                const int off = c * kGqaPPitch + (16 * hb + 4 * r) * 2;
+                *reinterpret_cast<uint2 *>(pst_hi + off) = make_uint2(hi2[0], hi2[1]);
+                *reinterpret_cast<uint2 *>(pst_lo + off) = make_uint2(lo2[0], lo2[1]);
+            }
+            if (r == 0) lds_corr[wave][c] = corr;
+            wave_lds_order();
+
+            // row operands P[row c][entries 8r..8r+7] and the rescale factors of rows 4r..4r+3
+            const bf16x8_t p_hi = __builtin_bit_cast(
+                bf16x8_t, *reinterpret_cast<const uint4 *>(pst_hi + c * kGqaPPitch + 16 * r));
+            const bf16x8_t p_lo = __builtin_bit_cast(
+                bf16x8_t, *reinterpret_cast<const uint4 *>(pst_lo + c * kGqaPPitch + 16 * r));
+            const float4 cr = *reinterpret_cast<const float4 *>(&lds_corr[wave][4 * r]);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                oacc[rt][i][0] *= cr.x;
+                oacc[rt][i][1] *= cr.y;
+                oacc[rt][i][2] *= cr.z;
+                oacc[rt][i][3] *= cr.w;
+            }
+            // O += P V, output column set i takes the i-th value of each of the lane's 8 V rows
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const uint32_t sel = (i & 1) ? 0x07060302u : 0x05040100u;
+                uint32_t w[8];
+#pragma unroll
+                for (int t = 0; t < 8; ++t) {
+                    const uint4 &v = vr[t];
+                    w[t] = (i >> 1) == 0 ? v.x : (i >> 1) == 1 ? v.y : (i >> 1) == 2 ? v.z : v.w;
+                }
+                const uint4 packed = make_uint4(__builtin_amdgcn_perm(w[1], w[0], sel),
+                                                __builtin_amdgcn_perm(w[3], w[2], sel),
+                                                __builtin_amdgcn_perm(w[5], w[4], sel),
+                                                __builtin_amdgcn_perm(w[7], w[6], sel));
+                const bf16x8_t vop = __builtin_bit_cast(bf16x8_t, packed);
+                oacc[rt][i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(p_hi, vop, oacc[rt][i], 0, 0, 0);
+                oacc[rt][i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(p_lo, vop, oacc[rt][i], 0, 0, 0);
+            }
+            wave_lds_order();                // the P tiles are rewritten by the next row tile
         }
         if (tnext < r1) load_tile(vr, Vb, tnext);
-        wave_lds_order();
     }
 
-    // wave result -> LDS (the wave's own K staging area is free now), then merge the waves
-    lsum += __shfl_xor(lsum, 16, kWave);
-    lsum += __shfl_xor(lsum, 32, kWave);
-    float *wacc = reinterpret_cast<float *>(kst);          // [gb][128] floats <= 8 KiB
-#pragma unroll
-    for (int x = 0; x < 4; ++x) {
-        const int head = 4 * r + x;
-        if (head < gb) {
-            *reinterpret_cast<float4 *>(wacc + head * W + 8 * c) =
-                make_float4(oacc[0][x], oacc[1][x], oacc[2][x], oacc[3][x]);
-            *reinterpret_cast<float4 *>(wacc + head * W + 8 * c + 4) =
-                make_float4(oacc[4][x], oacc[5][x], oacc[6][x], oacc[7][x]);
-        }
-    }
-    if (r == 0) {
-        sm_m[wave][c] = m;
-        sm_l[wave][c] = lsum;
-    }
     __syncthreads();
-    for (int idx = tid; idx < gb * W; idx += blockDim.x) {
-        const int g = idx / W, d = idx - g * W;
-        float M = sm_m[0][g];
-#pragma unroll
-        for (int w2 = 1; w2 < kWavesPerBlock; ++w2) M = fmaxf(M, sm_m[w2][g]);
-        float a = 0.0f, L = 0.0f;
-#pragma unroll
-        for (int w2 = 0; w2 < kWavesPerBlock; ++w2) {
-            const float f = sm_m[w2][g] == -INFINITY ? 0.0f : __expf(sm_m[w2][g] - M);
-            a = fmaf(reinterpret_cast<const float *>(lds_k[w2])[g * W + d], f, a);
-            L = fmaf(sm_l[w2][g], f, L);
+    if (p.scores != nullptr && p.stage_scores) {   // the block's scores: one burst per row of the group
+        const int rows = r1 - r0, rows4 = rows & ~3;
+        for (int g = 0; g < gb; ++g) {
+            float *dst = p.scores + (((int64_t)b * p.Hq + h0 + g) * p.k + j) * p.S + r0;
+            const float *src = gqa_stage + g * p.chunk;
+            if ((p.S & 3) == 0 && (reinterpret_cast<uintptr_t>(p.scores) & 15) == 0) {
+                for (int i = tid * 4; i < rows4; i += blockDim.x * 4)
+                    *reinterpret_cast<float4 *>(dst + i) = *reinterpret_cast<const float4 *>(src + i);
+                if (tid < rows - rows4) dst[rows4 + tid] = src[rows4 + tid];
+            } else {
+                for (int i = tid; i < rows; i += blockDim.x) dst[i] = src[i];
+            }
         }
-        p.part_acc[(part_base + g * part_head_stride) * W + d] = a;
-        if (d == 0) {
-            p.part_ml[(part_base + g * part_head_stride) * 2 + 0] = M;
-            p.part_ml[(part_base + g * part_head_stride) * 2 + 1] = L;
+    }
+
+    // per row tile: wave results -> LDS (the wave's own K staging area is free now), then merge
+    // the waves and write the block's partial
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) {
+        if (rt * 16 >= gb) break;
+        const int rows_here = min(16, gb - rt * 16);
+        float ls = lsum[rt];
+        ls += __shfl_xor(ls, 16, kWave);
+        ls += __shfl_xor(ls, 32, kWave);
+        float *wacc = reinterpret_cast<float *>(kst);          // [16][128] floats = 8 KiB
+#pragma unroll
+        for (int x = 0; x < 4; ++x) {
+            const int head = 4 * r + x;
+            if (head < rows_here) {
+                *reinterpret_cast<float4 *>(wacc + head * W + 8 * c) =
+                    make_float4(oacc[rt][0][x], oacc[rt][1][x], oacc[rt][2][x], oacc[rt][3][x]);
+                *reinterpret_cast<float4 *>(wacc + head * W + 8 * c + 4) =
+                    make_float4(oacc[rt][4][x], oacc[rt][5][x], oacc[rt][6][x], oacc[rt][7][x]);
+            }
         }
+        if (r == 0) {
+            sm_m[wave][c] = m[rt];
+            sm_l[wave][c] = ls;
+        }
+        __syncthreads();
+        for (int idx = tid; idx < rows_here * W; idx += blockDim.x) {
+            const int g = idx / W, d = idx - g * W;
+            float M = sm_m[0][g];
+#pragma unroll
+            for (int w2 = 1; w2 < kWavesPerBlock; ++w2) M = fmaxf(M, sm_m[w2][g]);
+            float a = 0.0f, L = 0.0f;
+#pragma unroll
+            for (int w2 = 0; w2 < kWavesPerBlock; ++w2) {
+                const float f = sm_m[w2][g] == -INFINITY ? 0.0f : __expf(sm_m[w2][g] - M);
+                a = fmaf(reinterpret_cast<const float *>(lds_k[w2])[g * W + d], f, a);
+                L = fmaf(sm_l[w2][g], f, L);
+            }
+            const int64_t at = part_base + (rt * 16 + g) * part_head_stride;
+            p.part_acc[at * W + d] = a;
+            if (d == 0) {
+                p.part_ml[at * 2 + 0] = M;
+                p.part_ml[at * 2 + 1] = L;
+            }
+        }
+        if (rt + 1 < RT) __syncthreads();    // the staging areas are rewritten by the next row tile
     }
 }
 
@@ -681,8 +786,12 @@ int make_attn_plan(const pikv_desc *d, int k, AttnPlan *plan) {
     int gb = 1;
     if (d->route_rows_per_seq == 1 && (G == 2 || G == 4 || G == 8)) gb = G;
     const bool gqa_mfma = d->route_rows_per_seq == 1 && d->dtype == PIKV_BF16 && d->rank == 0 &&
-                          d->D == 128 && G >= 2 && G <= 16;
+                          d->D == 128 && G >= 2 && G <= 64;
     if (gqa_mfma) gb = G;
+    const int tq = d->tq > 1 ? d->tq : 1;
+    // draft queries are folded into the query group of the matrix-core kernel only
+    if (tq > 1 && (!gqa_mfma || d->Hq % tq != 0 || G % tq != 0)) return PIKV_ERR_UNSUPPORTED;
+    const int row_tiles = !gqa_mfma ? 0 : (G <= 16 ? 1 : (G <= 32 ? 2 : 4));
     const int epl = 16 / elem_bytes(d->dtype);
     const int lpr = W / epl;
     if (lpr < 1 || lpr > 32) return PIKV_ERR_UNSUPPORTED;
@@ -691,24 +800,54 @@ int make_attn_plan(const pikv_desc *d, int k, AttnPlan *plan) {
     // One round of resident blocks: 256 CUs times the 4-wave blocks a CU holds at this
     // kernel's register footprint.  Fewer, longer blocks keep the per-wave prefetch chain
     // busy and shrink the partials that the combine pass has to merge.
-    const int resident = gqa_mfma ? 3 : (gb >= 8 ? 2 : (gb >= 4 ? 3 : 4));
+    int resident = gqa_mfma ? (row_tiles == 1 ? 3 : 2) : (gb >= 8 ? 2 : (gb >= 4 ? 3 : 4));
+    int64_t nsplit = 1;
+    int chunk = 0;
+    auto split_for = [&](int res) {
+        nsplit = units > 0 ? (int64_t)256 * res / units : 1;
+        if (g_split_override > 0) nsplit = g_split_override;
+        const int64_t max_split = (d->S + tile - 1) / tile;
+        if (nsplit > max_split) nsplit = max_split;
+        if (nsplit > kMaxPartialsPerHead / k) nsplit = kMaxPartialsPerHead / k;
+        if (nsplit < 1) nsplit = 1;
+        chunk = (int)((d->S + nsplit - 1) / nsplit);
+        chunk = (chunk + tile - 1) / tile * tile;
+        nsplit = (d->S + chunk - 1) / chunk;
+    };
+    split_for(resident);
+    size_t stage = (size_t)gb * chunk * sizeof(float);      // the block's raw scores, staged in LDS
+    if (gqa_mfma) {
+        // The matrix-core kernel's tile staging takes kGqaStaticLds per block (plus the query
+        // tile at four row tiles): the score stage must fit beside it as often as a CU holds
+        // blocks - three times with one row tile, or twice with longer blocks - or is left out.
+        const size_t lds_cu = 160 * 1024;
+        const size_t fixed = kGqaStaticLds + (row_tiles == 4 ? (size_t)64 * kGqaKPitch : 0);
+        if ((size_t)resident * (fixed + stage) > lds_cu || stage > 64 * 1024 - 256) {
+            bool fits = false;
+            if (resident == 3) {
+                split_for(2);
+                stage = (size_t)gb * chunk * sizeof(float);
+                fits = 2 * (fixed + stage) <= lds_cu && stage <= 64 * 1024 - 256;
+                if (fits) resident = 2;
+            }
+            if (!fits) {
+                split_for(resident);
+                stage = 0;
+            }
+        }
+    } else if (stage > (size_t)kScoreStageBytes) {
+        stage = 0;
+    }
     const int64_t target_blocks = 256 * resident;
-    int64_t nsplit = units > 0 ? target_blocks / units : 1;
-    if (g_split_override > 0) nsplit = g_split_override;
-    const int64_t max_split = (d->S + tile - 1) / tile;
-    if (nsplit > max_split) nsplit = max_split;
-    if (nsplit > kMaxPartialsPerHead / k) nsplit = kMaxPartialsPerHead / k;
-    if (nsplit < 1) nsplit = 1;
-    int chunk = (int)((d->S + nsplit - 1) / nsplit);
-    chunk = (chunk + tile - 1) / tile * tile;
-    nsplit = (d->S + chunk - 1) / chunk;
     plan->gqa_mfma = gqa_mfma;
     plan->heads_per_block = gb;
+    plan->row_tiles = row_tiles;
     plan->head_blocks = d->Hq / gb;
     plan->tile_rows = tile;
     plan->chunk = chunk;
     plan->nsplit = (int)nsplit;
     plan->resident_blocks = (int)target_blocks;
+    plan->score_stage_bytes = stage;
     plan->acc_floats = (size_t)d->B * d->Hq * k * nsplit * W;
     plan->ml_floats = (size_t)d->B * d->Hq * k * nsplit * 2;
     return PIKV_OK;
@@ -803,12 +942,12 @@ int launch_attn_partial(const pikv_desc *desc, const void *q, const void *const 
     p.k = k;
     p.rr = desc->route_rows_per_seq;
     p.rank = desc->rank;
+    p.tq = desc->tq > 1 ? desc->tq : 1;
     p.stride_h = desc->stride_h;
     p.stride_s = desc->stride_s;
     p.nsplit = plan.nsplit;
     p.chunk = plan.chunk;
-    p.stage_scores = scores != nullptr && !plan.gqa_mfma &&
-                     (size_t)plan.heads_per_block * plan.chunk * sizeof(float) <= kScoreStageBytes;
+    p.stage_scores = scores != nullptr && plan.score_stage_bytes > 0;
     p.scale = scale > 0.0f ? scale : 1.0f / sqrtf((float)desc->D);
 
     const int64_t blocks64 = (int64_t)desc->B * plan.head_blocks * k * plan.nsplit;
@@ -817,8 +956,13 @@ int launch_attn_partial(const pikv_desc *desc, const void *q, const void *const 
     int lrc;
     if (g_prof_start) (void)hipEventRecord(g_prof_start, st);
     if (plan.gqa_mfma) {
-        hipLaunchKernelGGL(attn_partial_gqa128, dim3((unsigned)blocks64), dim3(kWavesPerBlock * kWave),
-                           0, st, p);
+        const size_t lds = p.stage_scores ? plan.score_stage_bytes : 0;
+        const dim3 grid((unsigned)blocks64), block(kWavesPerBlock * kWave);
+        switch (plan.row_tiles) {
+            case 1: hipLaunchKernelGGL(attn_partial_gqa128<1>, grid, block, lds, st, p); break;
+            case 2: hipLaunchKernelGGL(attn_partial_gqa128<2>, grid, block, lds, st, p); break;
+            default: hipLaunchKernelGGL(attn_partial_gqa128<4>, grid, block, lds, st, p); break;
+        }
         lrc = launch_status();
     } else {
         lrc = desc->dtype == PIKV_F32
@@ -845,6 +989,7 @@ int launch_attn_partial(const pikv_desc *desc, const void *q, const void *const 
     c.rr = p.rr;
     c.rank = desc->rank;
     c.value_bias = (desc->flags & PIKV_DESC_VALUE_BIAS) ? 1 : 0;
+    c.tq = p.tq;
     c.nsplit = plan.nsplit;
     c.combine = combine;
     *c_out = c;

@@ -20,6 +20,7 @@ struct CombineParams {
     float *slot_coef;
     int Hq, G, D, W, k, rr, rank, nsplit, combine;
     int value_bias;   // U_V holds rank + 1 rows per kv head, the last one the decoder's additive term
+    int tq;           // draft queries per sequence: y and the row statistics are [B, tq, Hq / tq, ...]
 };
 
 constexpr int kCombinePrefetch = 4;         // partial rows each thread loads before the weights exist
@@ -109,10 +110,21 @@ inline size_t combine_smem_bytes(int threads, int np) {
 // and the stand-alone kernels use the same rule, which keeps their results bit-identical.
 inline int combine_threads(int np) { return np <= 32 ? 256 : 1024; }
 
+// Internal row bh = b * Hq + h (rows ordered kv head, draft query, head of the group) -> the row
+// of the caller's [B, tq, Hq / tq] arrays (y, row_max, row_norm).
+__device__ __forceinline__ int64_t caller_row(const CombineParams &p, int b, int h) {
+    if (p.tq <= 1) return (int64_t)b * p.Hq + h;
+    const int heads = p.Hq / p.tq, g = p.G / p.tq;
+    const int hk = h / p.G, rem = h - hk * p.G;
+    const int t = rem / g, gg = rem - t * g;
+    return ((int64_t)b * p.tq + t) * heads + hk * g + gg;
+}
+
 template <typename T, int THREADS>
 __device__ __forceinline__ void combine_head(const CombineParams &p, int bh, unsigned char *smem) {
     const int b = bh / p.Hq, h = bh - b * p.Hq;
     const int hk = h / p.G;
+    const int64_t out = caller_row(p, b, h);
     const int tid = threadIdx.x;
     const int np = p.k * p.nsplit;
 
@@ -167,8 +179,8 @@ __device__ __forceinline__ void combine_head(const CombineParams &p, int bh, uns
                 p.slot_coef[((int64_t)bh * p.k + j) * 2 + 1] = sh_coef[j];
             }
         }
-        if (p.row_max) p.row_max[bh] = M;
-        if (p.row_norm) p.row_norm[bh] = norm;
+        if (p.row_max) p.row_max[out] = M;
+        if (p.row_norm) p.row_norm[out] = norm;
         *live_s = M > -INFINITY ? 1.0f : 0.0f;
     }
     __syncthreads();
@@ -215,7 +227,7 @@ __device__ __forceinline__ void combine_head(const CombineParams &p, int bh, uns
     if (tid < cgroups) {
         const float4 t = red[tid];
         if (p.rank == 0) {
-            *reinterpret_cast<float4 *>(p.y + (int64_t)bh * p.D + tid * 4) = t;
+            *reinterpret_cast<float4 *>(p.y + out * p.D + tid * 4) = t;
         } else {
             ycode[tid * 4 + 0] = t.x;
             ycode[tid * 4 + 1] = t.y;
@@ -231,7 +243,7 @@ __device__ __forceinline__ void combine_head(const CombineParams &p, int bh, uns
             for (int cidx = 0; cidx < p.rank; ++cidx)
                 a2 = fmaf(ycode[cidx], load_scalar<T>(U, (int64_t)cidx * p.D + d), a2);
             if (p.value_bias && *live_s != 0.0f) a2 += load_scalar<T>(U, (int64_t)p.rank * p.D + d);
-            p.y[(int64_t)bh * p.D + d] = a2;
+            p.y[out * p.D + d] = a2;
         }
     }
 }

@@ -149,11 +149,13 @@ inline int elem_bytes(int dtype) { return dtype == PIKV_F32 ? 4 : 2; }
 struct AttnPlan {
     bool gqa_mfma;        // matrix-core grouped-query kernel (bf16, D = 128, 2..16 heads per kv head)
     int heads_per_block;  // query heads sharing one K/V stream
+    int row_tiles;        // matrix-core kernel: 16-row tiles the query group occupies (1, 2 or 4)
     int head_blocks;      // Hq / heads_per_block
     int tile_rows;        // rows one wave consumes per iteration
     int chunk;            // rows per split (multiple of tile_rows)
     int nsplit;
     int resident_blocks;  // blocks of the split pass the GPU holds at once
+    size_t score_stage_bytes;  // LDS per block for the raw scores (0: written straight to memory)
     size_t acc_floats;    // B*Hq*k*nsplit*width
     size_t ml_floats;     // B*Hq*k*nsplit*2
 };

@@ -54,7 +54,7 @@ __global__ __launch_bounds__(kRouteThreads) void route_kernel(const T *x, const 
         logit[tid] = v;
     }
     __syncthreads();
-    if (tid < 64) select_topk(logit, tid, row, E, k, topk_idx, gates, probs);
+    if (tid < 64) select_topk(logit[tid], tid, row, E, k, topk_idx, gates, probs);
 }
 
 // Fast path: a row of W_r is a whole number (1, 2, 4, 8 or 16) of 16-byte chunks; see
@@ -66,10 +66,11 @@ __global__ __launch_bounds__(kRouteThreads) void route_vec_kernel(const T *x, co
                                                                   int32_t *topk_idx, float *gates,
                                                                   float *probs) {
     __shared__ float red[kRouteThreads / kWave][64];
-    __shared__ float logit[64];
     const int row = blockIdx.x;
-    route_logits_vec<T>(x + (int64_t)row * d_r, W_r, bias, d_r, E, cpr, red, logit);
-    if (threadIdx.x < 64) select_topk(logit, threadIdx.x, row, E, k, topk_idx, gates, probs);
+    route_logits_vec<T>(x + (int64_t)row * d_r, W_r, bias, d_r, E, cpr, red);
+    if (threadIdx.x < 64)
+        select_topk(route_logit_of_lane(red, bias, E, threadIdx.x), threadIdx.x, row, E, k, topk_idx, gates,
+                    probs);
 }
 
 }  // namespace

@@ -12,37 +12,30 @@ namespace pikv {
 
 constexpr int kRouteThreads = 1024;
 
-// Softmax over the E logits, rank-count selection and gate renormalisation, by the first
-// wavefront of the block (lane e owns expert e).  `logit` is in LDS.
-__device__ __forceinline__ void select_topk(const float *logit, int lane, int row, int E, int k,
-                                            int32_t *topk_idx, float *gates, float *probs,
-                                            int *sel_lds = nullptr) {
-    const float mine = logit[lane];
-    float mx = mine;
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, kWave));
+// Softmax over the E logits, rank-count selection and gate renormalisation by one wavefront,
+// from registers: lane e holds expert e's logit (-inf in lanes >= E).  Returns the lane's rank
+// under (logit descending, index ascending); lanes with rank < k are the selection.  Every
+// wavefront that calls it with the same logits gets the same result, so a block may let all
+// its waves call it instead of broadcasting one wave's result through a barrier.
+__device__ __forceinline__ int select_topk(float mine, int lane, int row, int E, int k,
+                                           int32_t *topk_idx, float *gates, float *probs) {
+    const float mx = bits_max<0, 6>(mine);
     const float pe = lane < E ? __expf(mine - mx) : 0.0f;
-    float den = pe;
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) den += __shfl_xor(den, off, kWave);
+    const float den = bits_sum<0, 6>(pe);
     if (probs && lane < E) probs[(int64_t)row * E + lane] = pe / den;
 
     int rank = 0;
-    for (int o = 0; o < E; ++o) {
-        const float other = logit[o];
+    for (int o = 0; o < E; ++o) {      // every lane's logit passes through the scalar unit
+        const float other = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(mine), o));
         rank += (other > mine) || (other == mine && o < lane);
     }
     const bool chosen = lane < E && rank < k;
-    float sel = chosen ? pe : 0.0f;
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) sel += __shfl_xor(sel, off, kWave);
-    if (chosen) {
-        if (topk_idx) {
-            topk_idx[(int64_t)row * k + rank] = lane;
-            gates[(int64_t)row * k + rank] = pe / sel;
-        }
-        if (sel_lds) sel_lds[rank] = lane;
+    const float sel = bits_sum<0, 6>(chosen ? pe : 0.0f);
+    if (chosen && topk_idx) {
+        topk_idx[(int64_t)row * k + rank] = lane;
+        gates[(int64_t)row * k + rank] = pe / sel;
     }
+    return lane < E ? rank : 64;
 }
 
 // Logits of one routed row with the whole 1024-thread block, for a row-major W_r whose rows
@@ -50,17 +43,17 @@ __device__ __forceinline__ void select_topk(const float *logit, int lane, int ro
 // (a wave reads 1 KiB of consecutive bytes per load; all loads of a thread are independent);
 // its chunk-in-row index never changes, so it accumulates the same EPL experts throughout.
 // Lanes with equal chunk index are summed by xor-shuffles, the 16 waves through LDS in fixed
-// order, so the logits do not depend on scheduling.  Ends with logit[0..63] valid in LDS
-// (experts >= E hold -inf; a NaN logit is replaced by -inf) after a block barrier.
+// order, so the logits do not depend on scheduling.  Ends, after one block barrier, with the
+// per-wave sums in `red`; route_logit_of_lane then gives any wavefront its lanes' logits.
 template <typename T>
 __device__ __forceinline__ void route_logits_vec(const T *xr, const T *W_r, const float *bias,
-                                                 int d_r, int E, int cpr,
-                                                 float (*red)[64], float *logit) {
+                                                 int d_r, int E, int cpr, float (*red)[64]) {
     constexpr int EPL = Pack16<T>::N;
-    constexpr int kWaves = kRouteThreads / kWave;
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1), wave = tid >> 6;
     const int cir = tid & (cpr - 1);
+    (void)bias;
+    (void)E;
     const int cshift = ilog2(cpr);
     const int total = d_r * cpr;
 
@@ -99,18 +92,22 @@ __device__ __forceinline__ void route_logits_vec(const T *xr, const T *W_r, cons
         for (int i = 0; i < EPL; ++i) red[wave][cir * EPL + i] = acc[i];
     }
     __syncthreads();
-    if (tid < 64) {
-        float v = -INFINITY;
-        if (tid < E) {
-            v = 0.0f;
+}
+
+// Expert `lane`'s logit from the per-wave sums (waves joined in ascending order; experts >= E
+// hold -inf; a NaN logit is replaced by -inf).  Any wavefront may call it after the barrier.
+__device__ __forceinline__ float route_logit_of_lane(const float (*red)[64], const float *bias, int E,
+                                                     int lane) {
+    constexpr int kWaves = kRouteThreads / kWave;
+    float v = -INFINITY;
+    if (lane < E) {
+        v = 0.0f;
 #pragma unroll
-            for (int w = 0; w < kWaves; ++w) v += red[w][tid];
-            v += bias ? bias[tid] : 0.0f;
-            if (v != v) v = -INFINITY;
-        }
-        logit[tid] = v;
+        for (int w = 0; w < kWaves; ++w) v += red[w][lane];
+        v += bias ? bias[lane] : 0.0f;
+        if (v != v) v = -INFINITY;
     }
-    __syncthreads();
+    return v;
 }
 
 // True when route_logits_vec applies: W_r rows are a power-of-two number of aligned 16-byte

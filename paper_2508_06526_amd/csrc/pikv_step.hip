@@ -48,6 +48,25 @@ struct PreParams {
     PolicyView pol;      // its arrays, when given, are also stamped for the new entry
 };
 
+// Minimum of a 64-bit key over the wavefront, every lane ends with it; the four low lane bits
+// are exchanged inside the 16-lane rows (no LDS traffic).
+__device__ __forceinline__ uint64_t wave_min_u64(uint64_t v) {
+    auto step = [&](auto bit) {
+        constexpr int BIT = decltype(bit)::value;
+        const uint32_t lo = __float_as_uint(lane_xchg<BIT>(__uint_as_float((uint32_t)v)));
+        const uint32_t hi = __float_as_uint(lane_xchg<BIT>(__uint_as_float((uint32_t)(v >> 32))));
+        const uint64_t o = ((uint64_t)hi << 32) | lo;
+        v = o < v ? o : v;
+    };
+    step(std::integral_constant<int, 0>{});
+    step(std::integral_constant<int, 1>{});
+    step(std::integral_constant<int, 2>{});
+    step(std::integral_constant<int, 3>{});
+    step(std::integral_constant<int, 4>{});
+    step(std::integral_constant<int, 5>{});
+    return v;
+}
+
 // Grid: (sequence b, selected position j).  Every block of a sequence recomputes the routing
 // decision (W_r is L2-resident and tiny next to the cache) so that the k evict/insert jobs
 // run on k compute units at once instead of one after the other; block j == 0 publishes the
@@ -60,8 +79,6 @@ __global__ __launch_bounds__(kRouteThreads) void step_pre(PreParams p) {
     const int lane = tid & (kWave - 1), wave = tid >> 6;
 
     __shared__ float red[kWaves][64];
-    __shared__ float logit[64];
-    __shared__ int sel[64];
     __shared__ uint64_t wave_best[kWaves];
 
     // the new rows do not depend on the routing decision: fetch the first chunk now
@@ -73,14 +90,15 @@ __global__ __launch_bounds__(kRouteThreads) void step_pre(PreParams p) {
     }
 
     route_logits_vec<T>(static_cast<const T *>(p.x) + (int64_t)b * p.d_r,
-                        static_cast<const T *>(p.W_r), p.bias, p.d_r, p.E, p.cpr, red, logit);
-    if (tid < 64)
-        select_topk(logit, tid, b, p.E, p.k, j == 0 ? p.topk : nullptr, p.gates, nullptr, sel);
-    __syncthreads();
+                        static_cast<const T *>(p.W_r), p.bias, p.d_r, p.E, p.cpr, red);
+    // every wave makes the selection itself from the same sums (same bits): no wave waits for
+    // another one's result; the first wave of block j == 0 publishes it
+    const int rank = select_topk(route_logit_of_lane(red, p.bias, p.E, lane), lane, b, p.E, p.k,
+                                 (j == 0 && wave == 0) ? p.topk : nullptr, p.gates, nullptr);
     if (!p.do_insert) return;
 
     // one round trip for everything that hangs off the expert id
-    const int e = sel[j];
+    const int e = __builtin_ctzll(__ballot(rank == j));
     const int64_t be = (int64_t)b * p.E + e;
     const int n = p.n_valid[be];
     char *Kd = static_cast<char *>(p.K[be]);
@@ -120,11 +138,7 @@ __global__ __launch_bounds__(kRouteThreads) void step_pre(PreParams p) {
             best = c0 < best ? c0 : best;
         }
     }
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) {
-        const uint64_t o = __shfl_xor(best, off, kWave);
-        best = o < best ? o : best;
-    }
+    best = wave_min_u64(best);
     if (lane == 0) wave_best[wave] = best;
     __syncthreads();
     uint64_t m = wave_best[0];
@@ -157,11 +171,7 @@ __global__ __launch_bounds__(kRouteThreads) void step_pre(PreParams p) {
         if (p.pol.freq) p.pol.freq[be * p.S + slot] = 0;
     }
     // experts nobody selected report "nothing evicted" (block 0 of the sequence)
-    if (j == 0 && tid < p.E) {
-        bool chosen = false;
-        for (int jj = 0; jj < p.k; ++jj) chosen |= sel[jj] == tid;
-        if (!chosen) p.evicted_cnt[(int64_t)b * p.E + tid] = 0;
-    }
+    if (j == 0 && tid < p.E && rank >= p.k) p.evicted_cnt[(int64_t)b * p.E + tid] = 0;
 }
 
 // Post-attention stage of the fused step: the merge of the split partials (one block per

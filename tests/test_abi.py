@@ -42,8 +42,9 @@ def test_version_and_strerror(lib):
 
 
 def test_desc_struct_matches_header_layout():
-    assert C.sizeof(pk.PikvDesc) == 56
+    assert C.sizeof(pk.PikvDesc) == 64
     assert pk.PikvDesc.stride_h.offset == 32 and pk.PikvDesc.route_rows_per_seq.offset == 48
+    assert pk.PikvDesc.flags.offset == 52 and pk.PikvDesc.tq.offset == 56
 
 
 def test_workspace_size_is_zero_for_bad_geometry_and_positive_otherwise(lib):

@@ -30,6 +30,9 @@ FULL = {
     "c5_compressed": (list(range(16)), 1.0),
     # "next" row: 4 draft queries per sequence share the selected shards (group of 16 query rows)
     "c3_long_context_tq4": ([0], 1.0),
+    # wider tiles in the tokens' natural layout (desc.tq): 32 and 64 query rows per kv head
+    "c3_long_context_tq8": ([0], 1.0),
+    "c3_kv4_tq16": ([0], 1.0),
 }
 
 
@@ -99,6 +102,11 @@ def test_full_size_step_matches_oracle(name):
 
     # --- tolerance: attention output and utilities of whole sequences via the oracle
     y_gpu, u_gpu = t2n(shared["y"]), t2n(t["utility"])
+    q_orc = q_host
+    if geo.token_major:       # the oracle takes the same rows in kv-head-first order
+        perm = wl.token_major_rows(geo.Hq, geo.Hkv, geo.tq)
+        q_orc = np.ascontiguousarray(q_host[:, perm])
+        y_gpu = np.ascontiguousarray(y_gpu[:, perm])
     dummy = np.zeros((1,), np.float32 if geo.dtype == "f32" else np.uint16)
     UK = None if t["U_K"] is None else wl.to_host(t["U_K"], geo.dtype)
     UV = None if t["U_V"] is None else wl.to_host(t["U_V"], geo.dtype)
@@ -110,7 +118,7 @@ def test_full_size_step_matches_oracle(name):
         u_seq = u_before[b:b + 1].copy()
         for e in idx[b]:
             u_seq[0, e, int(ridx[b, e, 0])] = 0.0             # the inserted entry starts at 0
-        out = orc.attend(np.ascontiguousarray(q_host[b:b + 1]), Ks, Vs,
+        out = orc.attend(np.ascontiguousarray(q_orc[b:b + 1]), Ks, Vs,
                          np.ascontiguousarray(n_before[b:b + 1]), np.ascontiguousarray(idx[b:b + 1]),
                          np.ascontiguousarray(gates[b:b + 1]), Hkv=geo.Hkv, E=geo.E, S=geo.S,
                          dtype=geo.dtype, rank=geo.rank, U_K=UK, U_V=UV, utility=u_seq, decay=decay)

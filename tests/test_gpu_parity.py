@@ -109,7 +109,11 @@ ATTN_CASES = {
     "gqa3_d128": (dict(B=2, Hq=6, Hkv=2, D=128, E=4, S=333, k=2, dtype="bf16"), "ragged"),
     "gqa16_d128": (dict(B=1, Hq=16, Hkv=1, D=128, E=3, S=1500, k=2, dtype="bf16"), "ragged"),
     "gqa5_d128_tiny": (dict(B=1, Hq=5, Hkv=1, D=128, E=2, S=7, k=2, dtype="bf16"), "full"),
-    "gqa32_falls_back": (dict(B=1, Hq=32, Hkv=1, D=128, E=2, S=70, k=1, dtype="bf16"), "full"),
+    # more than 16 rows per kv head: two and four 16-row tiles sharing every K/V load
+    "gqa32_two_row_tiles": (dict(B=1, Hq=32, Hkv=1, D=128, E=2, S=70, k=1, dtype="bf16"), "full"),
+    "gqa17_d128": (dict(B=2, Hq=34, Hkv=2, D=128, E=3, S=400, k=2, dtype="bf16"), "ragged"),
+    "gqa48_d128": (dict(B=1, Hq=96, Hkv=2, D=128, E=3, S=700, k=2, dtype="bf16"), "ragged"),
+    "gqa64_d128": (dict(B=1, Hq=128, Hkv=2, D=128, E=4, S=1300, k=3, dtype="bf16"), "ragged"),
     # scaled config 5: rank-32 codes
     "c5_scaled": (dict(B=2, Hq=4, Hkv=4, D=128, E=6, S=900, k=2, dtype="bf16", rank=32), "ragged"),
     "rank16_gqa4": (dict(B=1, Hq=8, Hkv=2, D=64, E=4, S=520, k=2, dtype="bf16", rank=16), "ragged"),
@@ -171,6 +175,63 @@ def test_attention_and_utility_match_oracle(name, combine, use_gates):
                 np.testing.assert_allclose(p, ref["prob"][b, h, j, :n], rtol=1e-4, atol=1e-10)
 
 
+@pytest.mark.parametrize("spec", [
+    dict(B=2, Hq=16, Hkv=2, D=128, E=4, S=300, k=2, dtype="bf16", tq=4),      # 8 rows per kv head
+    dict(B=1, Hq=64, Hkv=2, D=128, E=4, S=500, k=2, dtype="bf16", tq=8),      # 32 rows: two row tiles
+    dict(B=2, Hq=128, Hkv=2, D=128, E=3, S=200, k=2, dtype="bf16", tq=16),    # 64 rows: four row tiles
+    dict(B=1, Hq=72, Hkv=3, D=128, E=3, S=150, k=3, dtype="bf16", tq=6),      # 24 rows, three kv heads
+], ids=["tq4", "tq8", "tq16", "tq6_kv3"])
+@pytest.mark.parametrize("combine", [orc.COMBINE_LSE, orc.COMBINE_LOCAL], ids=["lse", "local"])
+def test_multi_query_step_in_token_major_layout(spec, combine):
+    """Draft queries of a multi-query step in their natural layout, q [B, tq, heads, D] with
+    desc.tq = tq: routing on the flat vector, attention of every (draft, head) row over the
+    selected shards, outputs back in [B, tq, heads] order, utilities summed over all rows.  The
+    oracle sees the same rows as Hq = tq * heads plain query heads in kv-head-first order."""
+    from gpu_harness import dev_storage
+    g = wl.Geometry(token_major=True, **spec)
+    case = wl.make_host_case(g, seed=71, n_valid="ragged", utility0="exp", w_sigma=0.02)
+    perm = wl.token_major_rows(g.Hq, g.Hkv, g.tq)           # internal row -> caller row
+    q_caller = np.empty_like(case.q)
+    q_caller[:, perm] = case.q                               # the caller's [B, tq*heads, D]
+    # the router sees the caller's flat vector
+    probe = case.clone()
+    probe.q = q_caller
+    ensure_route_margin(probe, g.k)
+    q_caller = probe.q
+    case.q = np.ascontiguousarray(q_caller[:, perm])        # oracle order of the same rows
+    dc = DeviceCase(case)
+    dc.q = dev_storage(q_caller, g.dtype)
+    dc.desc = pk.make_desc(g.B, g.Hq, g.Hkv, g.D, g.E, g.S, dtype=pk.binding.BF16, stride_h=dc.stride_h,
+                           stride_s=dc.stride_s, tq=g.tq)
+    dc.route()
+    x = np.ascontiguousarray(q_caller.reshape(g.route_rows, g.d_r))
+    idx, gates, _ = orc.route(x, case.W_r, g.k, dtype=g.dtype)
+    np.testing.assert_array_equal(t2n(dc.topk), idx)
+    dc.attend(combine=combine)
+    dc.update_utility(0.9)
+    u_ref = case.utility.copy()
+    ref = oracle_step(case, idx, t2n(dc.gates), combine, utility=u_ref, decay=0.9)
+    y = t2n(dc.y)[:, perm]                                   # back to the oracle's row order
+    ok, emax, l2 = y_tolerance_ok(y, ref["y"], g.dtype)
+    assert ok, (emax, l2)
+    np.testing.assert_allclose(t2n(dc.row_max)[:, perm], ref["row_max"], rtol=1e-4, atol=1e-5)
+    np.testing.assert_allclose(t2n(dc.row_norm)[:, perm], ref["row_norm"], rtol=1e-4, atol=1e-9)
+    assert_utility_close(t2n(dc.utility), u_ref)
+
+
+def test_multi_query_layout_is_refused_where_no_kernel_takes_it():
+    fake = torch.zeros(64, device=DEV)
+    for kw in (dict(D=64), dict(rank=32), dict(dtype=pk.binding.F32)):     # only bf16 rows of 128 values
+        args = dict(D=128, rank=0, dtype=pk.binding.BF16)
+        args.update(kw)
+        desc = pk.make_desc(1, 16, 2, args["D"], 4, 64, rank=args["rank"], dtype=args["dtype"], tq=4)
+        ws = torch.empty(1 << 20, device=DEV, dtype=torch.uint8)
+        with pytest.raises(pk.PikvError) as err:
+            pk.pikv_sharded_attn(desc, fake, fake, fake, fake, fake, fake, fake, None, 2, pk.COMBINE_LSE, 0.0,
+                                 fake, None, None, None, None, ws)
+        assert err.value.status == -2
+
+
 def random_geometry(rng):
     D = int(rng.choice([16, 32, 64, 128]))
     dtype = str(rng.choice(["bf16", "bf16", "f32"]))
@@ -178,7 +239,7 @@ def random_geometry(rng):
     if rank >= D:
         rank = 0
     Hkv = int(rng.choice([1, 2, 3, 4]))
-    G = int(rng.choice([1, 1, 2, 3, 4, 5, 8, 16]))
+    G = int(rng.choice([1, 1, 2, 3, 4, 5, 8, 16, 24, 40]))
     E = int(rng.integers(1, 10))
     k = int(rng.integers(1, E + 1))
     per_head = bool(rng.random() < 0.25)

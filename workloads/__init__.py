@@ -56,6 +56,7 @@ class Geometry:
     per_head_routing: bool = False  # True: one routing decision per (sequence, head)
     name: str = ""
     tq: int = 1                   # draft queries per sequence folded into Hq (multi-query tile)
+    token_major: bool = False     # q / y rows in the caller's [tq, heads] order (else kv head first)
 
     @property
     def G(self) -> int:
@@ -102,11 +103,31 @@ CONFIGS = {
 # (speculative decoding).  Laid out as [B, Hkv, Tq*G, D] the Tq*G query rows of a kv head are
 # simply a larger grouped-query group, so the long-context workload with Tq = 4 is a geometry
 # with Hq = 4*32 query rows over the same 8 kv heads (group 16 = a full MFMA tile).
+# Wider tiles keep the tokens' natural layout, q [B, Tq, heads, D] (token_major): Tq = 8 on the
+# long-context shape (32 rows per kv head, two 16-row tiles) and Tq = 16 on the same shards with
+# 16 query heads over 4 kv heads (64 rows per kv head, four tiles; Hq stays within 256 rows).
 EXTRA_CONFIGS = {
     "c3_long_context_tq4": Geometry(B=1, Hq=128, Hkv=8, D=128, E=16, S=8192, k=4,
                                     name="c3_long_context_tq4", tq=4),
+    "c3_long_context_tq8": Geometry(B=1, Hq=256, Hkv=8, D=128, E=16, S=8192, k=4,
+                                    name="c3_long_context_tq8", tq=8, token_major=True),
+    "c3_kv4_tq16": Geometry(B=1, Hq=256, Hkv=4, D=128, E=16, S=8192, k=4,
+                            name="c3_kv4_tq16", tq=16, token_major=True),
 }
 CONFIGS.update(EXTRA_CONFIGS)
+
+
+def token_major_rows(Hq: int, Hkv: int, tq: int) -> np.ndarray:
+    """perm[h] = row, in the caller's [tq, heads] order, of internal query row h (internal order:
+    kv head, draft query, head of the group).  Layout only."""
+    heads, group = Hq // tq, Hq // Hkv
+    g = heads // Hkv
+    perm = np.empty(Hq, np.int64)
+    for hk in range(Hkv):
+        for t in range(tq):
+            for gg in range(g):
+                perm[hk * group + t * g + gg] = t * heads + hk * g + gg
+    return perm
 
 
 def zipf_bias(E: int, s: float, rng: np.random.Generator) -> np.ndarray:
