@@ -816,7 +816,11 @@ int make_attn_plan(const pikv_desc *d, int k, AttnPlan *plan) {
     };
     split_for(resident);
     size_t stage = (size_t)gb * chunk * sizeof(float);      // the block's raw scores, staged in LDS
-    if (gqa_mfma) {
+    if (gqa_mfma && gb < 8) {
+        // few rows per kv head: the score writes are ~3 % of the bytes and staging them measures
+        // no faster (its LDS stores collide with the tile staging)
+        stage = 0;
+    } else if (gqa_mfma) {
         // The matrix-core kernel's tile staging takes kGqaStaticLds per block (plus the query
         // tile at four row tiles): the score stage must fit beside it as often as a CU holds
         // blocks - three times with one row tile, or twice with longer blocks - or is left out.
