@@ -14,8 +14,8 @@ over 32 independent layer instances (16 GiB), as a 32-layer model does for every
 
 Prints ONE JSON line: `value` = queries/s over the timed steps (B x steps / elapsed), `roofline` =
 the attention pass against the 8 TB/s HBM peak: `frac` uses the kernel's average duration from
-the committed rocprofv3 kernel trace of this same command (profiles/), the live HIP-event
-figures of this run are printed beside it; `cpu_baseline` = the CPU oracle on a bounded sample
+the committed rocprofv3 kernel trace of this workload (profiles/, which names its command), the
+live HIP-event figures of this run are printed beside it; `cpu_baseline` = the CPU oracle on a bounded sample
 of the same workload; `other_workloads` = one short line per remaining workload.
 """
 from __future__ import annotations
@@ -417,7 +417,7 @@ def measure(args, config, steps, warmup, with_cpu, probe_steps, quiet=False):
     kernel = attn_kernel_name(geo)
     prof_ns, prof_file = profile_summary(config, kernel) if not (args.k > 0 or args.rank >= 0) else (None, None)
     if prof_ns is not None:
-        avg_ms, basis = prof_ns * 1e-6, "rocprofv3 kernel trace of this command, " + prof_file
+        avg_ms, basis = prof_ns * 1e-6, "committed rocprofv3 kernel trace of this workload in this launch mode, " + prof_file
     else:
         avg_ms, basis = raw_avg_ms, "uncorrected HIP event pair of this run (no kernel-trace summary for this workload)"
     traffic, traffic_file = measured_traffic(config)
