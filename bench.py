@@ -378,6 +378,9 @@ def measure(args, config, steps, warmup, with_cpu, probe_steps, quiet=False):
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     eager_steps = K - replays * per_replay
+    if elapsed < 0.010 and not quiet:
+        print("bench.py: the timed region of %d steps lasted %.2f ms; use --steps >= 256 for a stable figure"
+              % (K, elapsed * 1e3), file=sys.stderr)
 
     # ---- dominant kernel (the attention pass that streams the K/V bytes): the library records
     # a HIP event pair on the launch stream right around that kernel's launch
@@ -433,6 +436,9 @@ def measure(args, config, steps, warmup, with_cpu, probe_steps, quiet=False):
                    "launch": {"mode": args.mode, "graph_replays": replays, "steps_per_replay": per_replay,
                               "steps_in_replays": replays * per_replay, "steps_launched_eagerly": eager_steps},
                    "timed_region_s": elapsed,
+                   "timed_region_note": None if elapsed >= 0.010 else
+                   "the timed region is under 10 ms: --steps %d is too few for a stable figure "
+                   "(the default run times 4096 steps)" % K,
                    "api": args.api, "balance": bool(args.balance),
                    "compress_on_insert": bool(args.compress and geo.rank), "policy": args.policy,
                    "step": "route+evict1+append+attend+utility"},
