@@ -31,10 +31,30 @@ constexpr int kMaxPartialsPerHead = 2048;   // k * nsplit
 // 8 lane results are joined by an xor butterfly.  Every caller uses this one arrangement, so the
 // stand-alone and the fused kernels produce identical bits.  `get(s)` returns split s's pair;
 // all 8 lanes of a group must call together (pass nsplit = 0 for a padding group).
+// The first kShardPairsHeld pairs of a lane are fetched once and kept (shard_pairs_load), so a
+// caller can issue these loads ahead of other, slower ones; later pairs are fetched again in
+// each of the two passes.
+constexpr int kShardPairsHeld = 4;
+struct ShardPairs {
+    float2 v[kShardPairsHeld];
+};
 template <class F>
-__device__ __forceinline__ void shard_stats8(int nsplit, int sub, F get, float *M_out, float *Z_out) {
+__device__ __forceinline__ ShardPairs shard_pairs_load(int nsplit, int sub, F get) {
+    ShardPairs sp;
+#pragma unroll
+    for (int u = 0; u < kShardPairsHeld; ++u) {
+        const int s = sub + 8 * u;
+        sp.v[u] = s < nsplit ? get(s) : make_float2(-INFINITY, 0.0f);
+    }
+    return sp;
+}
+template <class F>
+__device__ __forceinline__ void shard_stats8(const ShardPairs &sp, int nsplit, int sub, F get, float *M_out,
+                                             float *Z_out) {
     float M = -INFINITY;
-    for (int s = sub; s < nsplit; s += 8) {
+#pragma unroll
+    for (int u = 0; u < kShardPairsHeld; ++u) M = sp.v[u].y > 0.0f ? fmaxf(M, sp.v[u].x) : M;
+    for (int s = sub + 8 * kShardPairsHeld; s < nsplit; s += 8) {
         const float2 v = get(s);
         M = v.y > 0.0f ? fmaxf(M, v.x) : M;
     }
@@ -42,7 +62,9 @@ __device__ __forceinline__ void shard_stats8(int nsplit, int sub, F get, float *
     M = fmaxf(M, __shfl_xor(M, 2, kWave));
     M = fmaxf(M, __shfl_xor(M, 4, kWave));
     float Z = 0.0f;
-    for (int s = sub; s < nsplit; s += 8) {
+#pragma unroll
+    for (int u = 0; u < kShardPairsHeld; ++u) Z += sp.v[u].y > 0.0f ? sp.v[u].y * __expf(sp.v[u].x - M) : 0.0f;
+    for (int s = sub + 8 * kShardPairsHeld; s < nsplit; s += 8) {
         const float2 v = get(s);
         Z += v.y > 0.0f ? v.y * __expf(v.x - M) : 0.0f;
     }
@@ -52,40 +74,48 @@ __device__ __forceinline__ void shard_stats8(int nsplit, int sub, F get, float *
     *M_out = M;
     *Z_out = Z;
 }
+template <class F>
+__device__ __forceinline__ void shard_stats8(int nsplit, int sub, F get, float *M_out, float *Z_out) {
+    shard_stats8(shard_pairs_load(nsplit, sub, get), nsplit, sub, get, M_out, Z_out);
+}
 
 // The k shard weights of one query head in either combine mode, from the per-shard
-// (max, normaliser).  Outputs per shard j: weight w[j] of its un-normalised accumulator and
-// the (shift, coef) pair with p_i = coef * exp(s_i - shift); returns the row max / normaliser.
-__device__ __forceinline__ void head_weights(int k, const float *Mj, const float *Zj, const float *g,
-                                             int combine, float *w, float *shift, float *coef,
-                                             float *M_out, float *norm_out) {
-    float M = -INFINITY, norm = 0.0f;
-    for (int j = 0; j < k; ++j)
-        if (Zj[j] > 0.0f) M = fmaxf(M, Mj[j]);
+// (max, normaliser), computed by an aligned group of `kp` lanes (kp = the power of two >= k, at
+// most 64): lane j of the group holds shard j's values (Zj = 0 in lanes j >= k), the row max and
+// the normaliser are joined by xor butterflies inside the group (fixed order).  Every lane of
+// the group must call.  Outputs for the lane's own shard: weight w of its un-normalised
+// accumulator and the (shift, coef) pair with p_i = coef * exp(s_i - shift); M and norm are the
+// row max / normaliser (the same in every lane of the group).
+struct HeadWeights {
+    float w, shift, coef, M, norm;
+};
+__device__ __forceinline__ HeadWeights head_weights(int kp, float Mj, float Zj, float gj, int combine) {
+    const bool live = Zj > 0.0f;
+    float M = live ? Mj : -INFINITY;
+    for (int off = 1; off < kp; off <<= 1) M = fmaxf(M, __shfl_xor(M, off, kWave));
+    HeadWeights out;
+    out.M = M;
     if (combine == PIKV_COMBINE_LSE) {
-        for (int j = 0; j < k; ++j)
-            if (Zj[j] > 0.0f) norm += (g ? g[j] : 1.0f) * Zj[j] * __expf(Mj[j] - M);
-        for (int j = 0; j < k; ++j) {
-            const bool live = Zj[j] > 0.0f;
-            const float gj = g ? g[j] : 1.0f;
-            if (w) w[j] = live ? gj * __expf(Mj[j] - M) / norm : 0.0f;
-            shift[j] = live ? M : 0.0f;
-            coef[j] = live ? gj / norm : 0.0f;
-        }
+        float norm = live ? gj * Zj * __expf(Mj - M) : 0.0f;
+        for (int off = 1; off < kp; off <<= 1) norm += __shfl_xor(norm, off, kWave);
+        out.norm = norm;
+        out.w = live ? gj * __expf(Mj - M) / norm : 0.0f;
+        out.shift = live ? M : 0.0f;
+        out.coef = live ? gj / norm : 0.0f;
     } else {
-        for (int j = 0; j < k; ++j)
-            if (Zj[j] > 0.0f) norm += g ? g[j] : 1.0f;
-        for (int j = 0; j < k; ++j) {
-            const bool live = Zj[j] > 0.0f;
-            const float gj = g ? g[j] : 1.0f;
-            const float wj = live ? gj / (norm * Zj[j]) : 0.0f;
-            if (w) w[j] = wj;
-            shift[j] = live ? Mj[j] : 0.0f;
-            coef[j] = wj;
-        }
+        float norm = live ? gj : 0.0f;
+        for (int off = 1; off < kp; off <<= 1) norm += __shfl_xor(norm, off, kWave);
+        out.norm = norm;
+        out.w = live ? gj / (norm * Zj) : 0.0f;
+        out.shift = live ? Mj : 0.0f;
+        out.coef = out.w;
     }
-    *M_out = M;
-    *norm_out = norm;
+    return out;
+}
+inline __host__ __device__ int pow2_at_least(int v) {
+    int p = 1;
+    while (p < v) p <<= 1;
+    return p;
 }
 
 // One block (THREADS threads) merges the k * nsplit partials of head `bh`.  The partial
@@ -94,7 +124,7 @@ __device__ __forceinline__ void head_weights(int k, const float *Mj, const float
 //   phase 0: every thread = (slice of partials, float4 column group) issues its first
 //            accumulator loads; (max, sum) of every partial goes to LDS.
 //   phase 1: 8 lanes per selected shard reduce its splits to (max, normaliser).
-//   phase 2: one thread forms the k gate-weighted shard weights in either combine mode.
+//   phase 2: k lanes form the k gate-weighted shard weights in either combine mode.
 //   phase 3: weighted sum of the accumulators, slices reduced through LDS in fixed order,
 //            then (rank > 0) the value decoder y = ycode U_V[h'].
 // Bytes of LDS combine_head<., threads> carves from the buffer it is given (np = k * nsplit
@@ -132,7 +162,7 @@ __device__ __forceinline__ void combine_head(const CombineParams &p, int bh, uns
     float *wt = reinterpret_cast<float *>(smem + THREADS * 16);     // max of every partial, later its weight
     float *ls = wt + combine_np_pad(np);
     float *Mj = ls + combine_np_pad(np), *Zj = Mj + 64, *shard_w = Zj + 64;
-    float *sh_shift = shard_w + 64, *sh_coef = sh_shift + 64, *g_s = sh_coef + 64;
+    float *g_s = shard_w + 3 * 64;
     float *ycode = g_s + 64;                                         // [128]
     float *live_s = ycode + 128;                                     // [1] 1 if any selected shard holds entries
 
@@ -169,19 +199,21 @@ __device__ __forceinline__ void combine_head(const CombineParams &p, int bh, uns
         }
     }
     __syncthreads();
-    if (tid == 0) {
-        float M, norm;
-        head_weights(p.k, Mj, Zj, p.gates ? g_s : nullptr, p.combine, shard_w, sh_shift, sh_coef, &M,
-                     &norm);
-        if (p.slot_coef) {
-            for (int j = 0; j < p.k; ++j) {
-                p.slot_coef[((int64_t)bh * p.k + j) * 2 + 0] = sh_shift[j];
-                p.slot_coef[((int64_t)bh * p.k + j) * 2 + 1] = sh_coef[j];
-            }
+    if (tid < kWave) {   // lane j of the first wave owns selected shard j
+        const bool mine = tid < p.k;
+        const HeadWeights hw = head_weights(pow2_at_least(p.k), mine ? Mj[tid] : 0.0f, mine ? Zj[tid] : 0.0f,
+                                            (mine && p.gates) ? g_s[tid] : 1.0f, p.combine);
+        if (mine) {
+            shard_w[tid] = hw.w;
+            if (p.slot_coef)
+                *reinterpret_cast<float2 *>(p.slot_coef + ((int64_t)bh * p.k + tid) * 2) =
+                    make_float2(hw.shift, hw.coef);
         }
-        if (p.row_max) p.row_max[out] = M;
-        if (p.row_norm) p.row_norm[out] = norm;
-        *live_s = M > -INFINITY ? 1.0f : 0.0f;
+        if (tid == 0) {
+            if (p.row_max) p.row_max[out] = hw.M;
+            if (p.row_norm) p.row_norm[out] = hw.norm;
+            *live_s = hw.M > -INFINITY ? 1.0f : 0.0f;
+        }
     }
     __syncthreads();
     // weight of every partial: shard weight * exp(m_split - M_shard)

@@ -262,29 +262,44 @@ __global__ __launch_bounds__(THREADS) void step_post(PostParams p) {
     };
     float *urow = p.utility + ((int64_t)b * p.E + e) * p.S;
     int i = i0 + slot;
+    // softmax statistics of every (head, selected shard): 8 lanes each, pairs read from L2.  The
+    // pairs of the first pass are requested before the scores: loads come back in order, and the
+    // statistics must not wait for the scores' trip to memory
+    const float *ml = p.c.part_ml + (int64_t)b * Hq * np * 2;
+    const int pair0 = tid / 8;
+    auto pair_of = [&](int t) {
+        return [=](int sp) { return *reinterpret_cast<const float2 *>(ml + 2 * ((int64_t)t * nsplit + sp)); };
+    };
+    const ShardPairs first = shard_pairs_load(pair0 < Hq * k ? nsplit : 0, tid & 7, pair_of(pair0));
+    if (p.c.gates != nullptr && tid < k) g_s[tid] = p.c.gates[(int64_t)b * k + tid];
     fetch(i);
     float u_old = (i < n && hg == 0) ? urow[i] : 0.0f;
-    if (p.c.gates != nullptr && tid < k) g_s[tid] = p.c.gates[(int64_t)b * k + tid];
 
-    // softmax statistics of every (head, selected shard): 8 lanes each, pairs read from L2
-    const float *ml = p.c.part_ml + (int64_t)b * Hq * np * 2;
     for (int t0 = 0; t0 < Hq * k; t0 += THREADS / 8) {
         const int t = t0 + tid / 8;
         const bool real = t < Hq * k;
         float M, Z;
-        shard_stats8(real ? nsplit : 0, tid & 7,
-                     [&](int sp) { return *reinterpret_cast<const float2 *>(ml + 2 * ((int64_t)t * nsplit + sp)); },
-                     &M, &Z);
+        if (t0 == 0)
+            shard_stats8(first, real ? nsplit : 0, tid & 7, pair_of(t), &M, &Z);
+        else
+            shard_stats8(real ? nsplit : 0, tid & 7, pair_of(t), &M, &Z);
         if (real && (tid & 7) == 0) {
             Mj_s[t] = M;
             Zj_s[t] = Z;
         }
     }
     __syncthreads();
-    for (int h = tid; h < Hq; h += THREADS) {
-        float M, norm;
-        head_weights(k, Mj_s + h * k, Zj_s + h * k, p.c.gates ? g_s : nullptr, p.c.combine, nullptr,
-                     shift_s + h * k, coef_s + h * k, &M, &norm);
+    // (shift, coef) of every (head, shard) pair: an aligned group of kp lanes per head
+    const int kp = pow2_at_least(k);
+    for (int h0 = 0; h0 < Hq; h0 += THREADS / kp) {
+        const int h = h0 + tid / kp, jj = tid & (kp - 1);
+        const bool mine = h < Hq && jj < k;
+        const HeadWeights hw = head_weights(kp, mine ? Mj_s[h * k + jj] : 0.0f, mine ? Zj_s[h * k + jj] : 0.0f,
+                                            (mine && p.c.gates) ? g_s[jj] : 1.0f, p.c.combine);
+        if (mine) {
+            shift_s[h * k + jj] = hw.shift;
+            coef_s[h * k + jj] = hw.coef;
+        }
     }
     __syncthreads();
     for (int it = 0; it < ntiles; ++it) {
