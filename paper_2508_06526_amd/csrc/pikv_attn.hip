@@ -90,8 +90,13 @@ __device__ __forceinline__ int64_t query_row(const AttnParams &p, int b, int h) 
     return ((int64_t)b * p.tq + t) * heads + hk * g + gg;
 }
 
+// 4-wave blocks of the plain-ALU kernel that one CU holds: its register footprint grows with the
+// heads per block (about 150 VGPRs at one head, 180-240 at two and four, all 256 at eight).
+// The launch bounds hold the compiler to it and the split plan counts resident blocks with it.
+constexpr int plain_blocks_per_cu(int gb) { return gb == 1 ? 3 : (gb <= 4 ? 2 : 1); }
+
 template <typename T, int W, int GB>
-__global__ __launch_bounds__(kWavesPerBlock *kWave) void attn_partial(AttnParams p) {
+__global__ __launch_bounds__(kWavesPerBlock *kWave, plain_blocks_per_cu(GB)) void attn_partial(AttnParams p) {
     constexpr int EPL = Pack16<T>::N;        // elements per lane per load
     constexpr int LPR = W / EPL;             // lanes covering one row
     constexpr int RPL = kWave / LPR;         // rows covered by one wave load
@@ -800,7 +805,7 @@ int make_attn_plan(const pikv_desc *d, int k, AttnPlan *plan) {
     // One round of resident blocks: 256 CUs times the 4-wave blocks a CU holds at this
     // kernel's register footprint.  Fewer, longer blocks keep the per-wave prefetch chain
     // busy and shrink the partials that the combine pass has to merge.
-    int resident = gqa_mfma ? (row_tiles == 1 ? 3 : 2) : (gb >= 8 ? 2 : (gb >= 4 ? 3 : 4));
+    int resident = gqa_mfma ? (row_tiles == 1 ? 3 : 2) : plain_blocks_per_cu(gb);
     int64_t nsplit = 1;
     int chunk = 0;
     auto split_for = [&](int res) {
