@@ -367,10 +367,11 @@ __global__ __launch_bounds__(kWavesPerBlock *kWave, plain_blocks_per_cu(GB)) voi
 
 // ---------------------------------------------------------------------------------------
 // Grouped-query variant on the matrix cores (bf16 rows of 128 values, one routing decision
-// per token, 2..16 query heads per kv head).  With G query heads sharing every K/V byte the
-// plain-ALU kernel above spends ~G times more instructions per byte and stops being
-// memory-bound; here the G heads (padded to 16) form the second dimension of 16x16x32 bf16
-// MFMA tiles, so the instruction count per byte no longer depends on G.
+// per token, 2..64 query rows per kv head: the heads of the group times the draft queries of
+// a multi-query step).  With G query rows sharing every K/V byte the plain-ALU kernel above
+// spends ~G times more instructions per byte and stops being memory-bound; here the G rows
+// (padded to whole tiles of 16) form the second dimension of 16x16x32 bf16 MFMA tiles, so the
+// instruction count per byte does not depend on G within a row tile.
 //
 // Per wave and per tile of 32 entries:
 //   * K and V rows arrive with the same coalesced 16-byte lane loads as above; lane
@@ -387,7 +388,11 @@ __global__ __launch_bounds__(kWavesPerBlock *kWave, plain_blocks_per_cu(GB)) voi
 //     column operand of lane (c, r) is V[entries 8r..8r+7][d = 8c + i], i.e. the i-th value
 //     of each of its own 8 loaded rows, packed by byte-permutes.
 constexpr int kGqaTile = 32;
-constexpr int kGqaKPitch = 272;   // bytes per staged K row: 256 + 16 keeps b128 reads conflict-free
+// Bytes per staged K row: 256 + 16 of padding, so that the 16 lanes reading one 16-byte column
+// of 16 different rows do not all start in the same bank.  The pass waits on memory, not on LDS:
+// a pitch of 288, which halves the bank-conflict cycles the counters report, runs in the same
+// time to the nanosecond, so the smaller pitch stays.
+constexpr int kGqaKPitch = 272;
 constexpr int kGqaPPitch = 80;    // bytes per staged P row (32 bf16 + 16 pad)
 
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));

@@ -147,7 +147,7 @@ inline int elem_bytes(int dtype) { return dtype == PIKV_F32 ? 4 : 2; }
 
 // Split geometry of the attention pass (also defines the workspace size).
 struct AttnPlan {
-    bool gqa_mfma;        // matrix-core grouped-query kernel (bf16, D = 128, 2..16 heads per kv head)
+    bool gqa_mfma;        // matrix-core grouped-query kernel (bf16, D = 128, 2..64 query rows per kv head)
     int heads_per_block;  // query heads sharing one K/V stream
     int row_tiles;        // matrix-core kernel: 16-row tiles the query group occupies (1, 2 or 4)
     int head_blocks;      // Hq / heads_per_block
