@@ -58,9 +58,7 @@ __device__ __forceinline__ void shard_stats8(const ShardPairs &sp, int nsplit, i
         const float2 v = get(s);
         M = v.y > 0.0f ? fmaxf(M, v.x) : M;
     }
-    M = fmaxf(M, __shfl_xor(M, 1, kWave));
-    M = fmaxf(M, __shfl_xor(M, 2, kWave));
-    M = fmaxf(M, __shfl_xor(M, 4, kWave));
+    M = bits_max<0, 3>(M);      // xor butterfly over the 8 lanes, inside a DPP row
     float Z = 0.0f;
 #pragma unroll
     for (int u = 0; u < kShardPairsHeld; ++u) Z += sp.v[u].y > 0.0f ? sp.v[u].y * __expf(sp.v[u].x - M) : 0.0f;
@@ -68,9 +66,7 @@ __device__ __forceinline__ void shard_stats8(const ShardPairs &sp, int nsplit, i
         const float2 v = get(s);
         Z += v.y > 0.0f ? v.y * __expf(v.x - M) : 0.0f;
     }
-    Z += __shfl_xor(Z, 1, kWave);
-    Z += __shfl_xor(Z, 2, kWave);
-    Z += __shfl_xor(Z, 4, kWave);
+    Z = bits_sum<0, 3>(Z);
     *M_out = M;
     *Z_out = Z;
 }

@@ -183,6 +183,10 @@ __global__ __launch_bounds__(kRouteThreads) void step_pre(PreParams p) {
 constexpr int kPostMaxShards = 2048;   // Hq * k
 constexpr int kPostPrefetchHeads = 8;  // score loads each thread issues before the statistics
 constexpr int kPostMaxTiles = 8;       // slot tiles one utility block walks through
+constexpr int kPostStatsAhead = 4;     // many-pairs shape: passes of statistics whose loads are in flight
+// Shapes of the kernel (template MODE): one slot tile per utility block and straight-line code;
+// several tiles per block; many (head, shard) pairs or many heads per thread.
+constexpr int kPostSingle = 0, kPostMulti = 1, kPostMany = 2;
 
 struct PostParams {
     CombineParams c;
@@ -193,6 +197,7 @@ struct PostParams {
     int B, E, S;
     int tiles;            // utility blocks per selected shard
     int tiles_per_block;  // consecutive slot tiles each of them covers
+    int util_first;       // the utility blocks take the grid's first block ids (they start first)
     float decay;
     int track;            // access bookkeeping: mass above pol.threshold stamps and counts the entry
     PolicyView pol;
@@ -213,32 +218,41 @@ inline size_t post_smem_bytes(int threads, int np, int pairs) {
 // tiles_per_block tiles of THREADS/4 slots of the j-th selected shard of a sequence.  THREADS
 // is the merge's block size (combine_threads), so that the merge is bit-identical to the
 // stand-alone kernel.
-template <typename T, int THREADS, bool MULTI>
+template <typename T, int THREADS, int MODE>
 __global__ __launch_bounds__(THREADS) void step_post(PostParams p) {
     constexpr int kSlots = THREADS / 4;
-    const int ntiles = MULTI ? p.tiles_per_block : 1;   // MULTI = false: straight-line code
+    const int ntiles = MODE != kPostSingle ? p.tiles_per_block : 1;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];   // post_smem_bytes()
-    const int ncomb = p.B * p.c.Hq;
-    if ((int)blockIdx.x < ncomb) {
-        combine_head<T, THREADS>(p.c, blockIdx.x, smem);
+    const int Hq = p.c.Hq, k = p.c.k, nsplit = p.c.nsplit;
+    const int ncomb = p.B * Hq;
+    // Blocks are dispatched in id order.  With hundreds of query rows the utility blocks are
+    // the long ones and a CU holds one block of either kind: they then take the first ids,
+    // so that they do not queue behind the merge blocks (kPostMany only).
+    const bool util_first = MODE == kPostMany && p.util_first;
+    const int mb = util_first ? (int)blockIdx.x - p.B * k * p.tiles : (int)blockIdx.x;
+    if (mb >= 0 && mb < ncomb) {
+        combine_head<T, THREADS>(p.c, mb, smem);
         return;
     }
     if (p.feedback && blockIdx.x == gridDim.x - 1) {   // Table 1 penalty for the next step
         if (threadIdx.x < kWave) penalty_wave(p.fb, threadIdx.x);
         return;
     }
-    const int Hq = p.c.Hq, k = p.c.k, nsplit = p.c.nsplit;
     const int np = k * nsplit;
-    int bid = blockIdx.x - ncomb;
+    int bid = util_first ? (int)blockIdx.x : (int)blockIdx.x - ncomb;
     const int tile = bid % p.tiles;
     bid /= p.tiles;
     const int j = bid % k;
     const int b = bid / k;
     const int tid = threadIdx.x;
+    // Order of the requests: loads come back in the order they were issued, and nothing that
+    // is needed early may queue behind something slow.  The expert id goes first (the entry
+    // count hangs off it), then the (max, sum) pairs of the statistics - which need neither -
+    // then the scores (a trip to memory, with the shard's capacity as the bound: slots past the
+    // entry count are masked when they are used); the entry count is read only after the
+    // statistics, where a block past the shard's end leaves.
     const int e = p.topk[(int64_t)b * k + j];
-    const int n = p.n_valid[(int64_t)b * p.E + e];
     const int i0 = tile * kSlots * ntiles;
-    if (i0 >= n) return;
 
     const int pairs = post_pairs_pad(Hq * k);
     float *Mj_s = reinterpret_cast<float *>(smem), *Zj_s = Mj_s + pairs;
@@ -253,14 +267,13 @@ __global__ __launch_bounds__(THREADS) void step_post(PostParams p) {
     const int gsize = (Hq + 3) / 4;
     const int h_lo = hg * gsize, h_hi = min(Hq, h_lo + gsize);
     float sc[kPostPrefetchHeads];
-    auto fetch = [&](int i) {
+    auto fetch = [&](int i, int limit) {
 #pragma unroll
         for (int t = 0; t < kPostPrefetchHeads; ++t) {
             const int h = h_lo + t;
-            sc[t] = (h < h_hi && i < n) ? p.scores[(((int64_t)b * Hq + h) * k + j) * p.S + i] : 0.0f;
+            sc[t] = (h < h_hi && i < limit) ? p.scores[(((int64_t)b * Hq + h) * k + j) * p.S + i] : 0.0f;
         }
     };
-    float *urow = p.utility + ((int64_t)b * p.E + e) * p.S;
     int i = i0 + slot;
     // softmax statistics of every (head, selected shard): 8 lanes each, pairs read from L2.  The
     // pairs of the first pass are requested before the scores: loads come back in order, and the
@@ -270,24 +283,48 @@ __global__ __launch_bounds__(THREADS) void step_post(PostParams p) {
     auto pair_of = [&](int t) {
         return [=](int sp) { return *reinterpret_cast<const float2 *>(ml + 2 * ((int64_t)t * nsplit + sp)); };
     };
-    const ShardPairs first = shard_pairs_load(pair0 < Hq * k ? nsplit : 0, tid & 7, pair_of(pair0));
+    // With more pairs than groups of 8 lanes the statistics take several passes (kPostMany: 8
+    // at 256 rows and 4 shards), each a round trip to L2 if taken one after the other: the
+    // pairs of kPostStatsAhead passes are requested ahead, and a pass that is done requests
+    // those of the pass kPostStatsAhead later.
+    constexpr int kAhead = MODE == kPostMany ? kPostStatsAhead : 1;
+    constexpr int kPairsPerPass = THREADS / 8;
+    const int npairs = Hq * k;
+    auto load_pass = [&](int pass) {
+        const int t = pass * kPairsPerPass + pair0;
+        return shard_pairs_load(t < npairs ? nsplit : 0, tid & 7, pair_of(min(t, npairs - 1)));
+    };
+    ShardPairs held[kAhead];
+#pragma unroll
+    for (int a = 0; a < kAhead; ++a) held[a] = load_pass(a);
     if (p.c.gates != nullptr && tid < k) g_s[tid] = p.c.gates[(int64_t)b * k + tid];
-    fetch(i);
-    float u_old = (i < n && hg == 0) ? urow[i] : 0.0f;
+    fetch(i, p.S);
+    const int n = p.n_valid[(int64_t)b * p.E + e];
+    float *urow = p.utility + ((int64_t)b * p.E + e) * p.S;
+    float u_old = (i < p.S && hg == 0) ? urow[i] : 0.0f;
 
-    for (int t0 = 0; t0 < Hq * k; t0 += THREADS / 8) {
-        const int t = t0 + tid / 8;
-        const bool real = t < Hq * k;
-        float M, Z;
-        if (t0 == 0)
-            shard_stats8(first, real ? nsplit : 0, tid & 7, pair_of(t), &M, &Z);
-        else
-            shard_stats8(real ? nsplit : 0, tid & 7, pair_of(t), &M, &Z);
-        if (real && (tid & 7) == 0) {
-            Mj_s[t] = M;
-            Zj_s[t] = Z;
+    const int passes = (npairs + kPairsPerPass - 1) / kPairsPerPass;
+    for (int pass0 = 0; pass0 < passes; pass0 += kAhead) {
+#pragma unroll
+        for (int a = 0; a < kAhead; ++a) {
+            const int pass = pass0 + a;
+            if (pass < passes) {                 // block-uniform
+                const int t = pass * kPairsPerPass + pair0;
+                const bool real = t < npairs;
+                float M, Z;
+                if (MODE == kPostMany || pass == 0)
+                    shard_stats8(held[a], real ? nsplit : 0, tid & 7, pair_of(t), &M, &Z);
+                else
+                    shard_stats8(real ? nsplit : 0, tid & 7, pair_of(t), &M, &Z);
+                if (real && (tid & 7) == 0) {
+                    Mj_s[t] = M;
+                    Zj_s[t] = Z;
+                }
+                if (MODE == kPostMany && pass + kAhead < passes) held[a] = load_pass(pass + kAhead);
+            }
         }
     }
+    if (i0 >= n) return;     // block-uniform: no entries in this block's slots
     __syncthreads();
     // (shift, coef) of every (head, shard) pair: an aligned group of kp lanes per head
     const int kp = pow2_at_least(k);
@@ -328,7 +365,7 @@ __global__ __launch_bounds__(THREADS) void step_post(PostParams p) {
         const int i_next = i + kSlots;
         const float u_cur = u_old;
         if (it + 1 < ntiles) {
-            fetch(i_next);
+            fetch(i_next, n);
             u_old = (i_next < n && hg == 0) ? urow[i_next] : 0.0f;
         }
         float *part = part_s + (it & 1) * 4 * kSlots;    // rewritten two tiles later, after a barrier
@@ -498,6 +535,10 @@ static int decode_step(const pikv_desc *desc, const void *q, const void *W_r, co
     if (tpb > kPostMaxTiles) tpb = kPostMaxTiles;
     pp.tiles_per_block = (int)tpb;
     pp.tiles = (int)((slot_tiles + tpb - 1) / tpb);
+    // many (head, shard) pairs per utility block, or many heads per thread: the kernel shape
+    // that keeps several passes of statistics in flight and starts the utility blocks first
+    const bool many = desc->Hq * k > 2 * (threads / 8) || (desc->Hq + 3) / 4 > 2 * kPostPrefetchHeads;
+    pp.util_first = many ? 1 : 0;
     pp.decay = decay;
     pp.feedback = fb != nullptr;
     pp.fb = pen;
@@ -507,10 +548,11 @@ static int decode_step(const pikv_desc *desc, const void *q, const void *W_r, co
     const bool f32 = desc->dtype == PIKV_F32;
     const size_t lds = post_smem_bytes(threads, np, desc->Hq * k);
     const bool multi = tpb > 1;
-#define PIKV_LAUNCH_POST(T, TH)                                                                  \
-    do {                                                                                         \
-        if (multi) hipLaunchKernelGGL((step_post<T, TH, true>), grid, dim3(TH), lds, st, pp);    \
-        else hipLaunchKernelGGL((step_post<T, TH, false>), grid, dim3(TH), lds, st, pp);         \
+#define PIKV_LAUNCH_POST(T, TH)                                                                          \
+    do {                                                                                                 \
+        if (many) hipLaunchKernelGGL((step_post<T, TH, kPostMany>), grid, dim3(TH), lds, st, pp);        \
+        else if (multi) hipLaunchKernelGGL((step_post<T, TH, kPostMulti>), grid, dim3(TH), lds, st, pp); \
+        else hipLaunchKernelGGL((step_post<T, TH, kPostSingle>), grid, dim3(TH), lds, st, pp);           \
     } while (0)
     if (threads == 256) {
         if (f32) PIKV_LAUNCH_POST(float, 256);

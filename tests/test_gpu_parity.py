@@ -920,6 +920,46 @@ def test_strided_shards_on_the_matrix_core_kernel_and_the_fused_step():
         assert_utility_close(t2n(dc.utility), u_ref)
 
 
+@pytest.mark.parametrize("spec", [
+    dict(B=1, Hq=128, Hkv=8, D=128, E=8, S=700, k=4, dtype="bf16"),                    # 16 rows per kv head
+    dict(B=2, Hq=256, Hkv=8, D=128, E=8, S=300, k=3, dtype="bf16", tq=8),             # token-major drafts
+    dict(B=1, Hq=96, Hkv=96, D=64, E=8, S=120, k=5, dtype="bf16"),                     # plain-ALU kernel
+    dict(B=1, Hq=40, Hkv=8, D=32, E=4, S=90, k=2, dtype="f32", rank=16),
+], ids=["gqa16_512pairs", "tq8_768pairs", "g1_480pairs", "f32_80pairs"])
+@pytest.mark.parametrize("combine", [orc.COMBINE_LSE, orc.COMBINE_LOCAL], ids=["lse", "local"])
+def test_fused_step_with_many_head_shard_pairs_equals_separate_calls(spec, combine):
+    """More (head, shard) pairs than a utility block has groups of eight lanes: its statistics
+    come from one thread per pair, and with many heads per thread the utility blocks are
+    dispatched ahead of the merge blocks.  Same bits as the separate calls, two steps in a row."""
+    from gpu_harness import dev_storage
+    token_major = "tq" in spec
+    g = wl.Geometry(token_major=token_major, **spec)
+    case = wl.make_host_case(g, seed=77, n_valid="ragged", utility0="exp", w_sigma=0.02)
+    ensure_route_margin(case, g.k)
+    dA, dB = DeviceCase(case), DeviceCase(case)
+    if token_major:
+        for d in (dA, dB):
+            d.desc = pk.make_desc(g.B, g.Hq, g.Hkv, g.D, g.E, g.S, dtype=pk.binding.BF16, stride_h=d.stride_h,
+                                  stride_s=d.stride_s, tq=g.tq)
+    eiA = torch.full((g.B, g.E, 1), -1, device=DEV, dtype=torch.int32)
+    ecA = torch.full((g.B, g.E), -5, device=DEV, dtype=torch.int32)
+    eiB, ecB = eiA.clone(), ecA.clone()
+    for step in range(2):
+        kn, vn = wl.draw_new_kv(g, 500 + step)
+        dkn, dvn = dev_storage(kn, g.dtype), dev_storage(vn, g.dtype)
+        pk.pikv_decode_step(dA.desc, dA.q, dA.W_r, dA.bias, dkn, dvn, dA.K_tab, dA.V_tab, dA.U_K, dA.U_V,
+                            dA.n_valid, dA.utility, g.k, combine, 0.0, 0.9, dA.topk, dA.gates,
+                            eiA, ecA, dA.y, dA.row_max, dA.row_norm, dA.scores, dA.slot_coef, dA.workspace)
+        dB.route()
+        pk.pikv_evict(dB.desc, dB.utility, dB.n_valid, g.S - 1, dB.topk, g.k, eiB, ecB, 1, False, None, None)
+        pk.pikv_append(dB.desc, dkn, dvn, dB.topk, g.k, eiB, ecB, 1, dB.K_tab, dB.V_tab, dB.utility, dB.n_valid)
+        dB.attend(combine=combine)
+        dB.update_utility(0.9)
+        for name in ("topk", "gates", "n_valid", "utility", "y", "row_max", "row_norm", "slot_coef"):
+            np.testing.assert_array_equal(t2n(getattr(dA, name)), t2n(getattr(dB, name)),
+                                          err_msg="%s differs at step %d" % (name, step))
+
+
 def test_fused_step_with_many_heads_times_shards_uses_the_separate_merge():
     """Hq * k beyond what a utility block restages: the step falls back to separate merge and
     utility launches and still equals the separate calls bit for bit."""
