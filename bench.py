@@ -93,8 +93,8 @@ RECIPE = {  # how each configuration's inputs are drawn (workloads.make_device_l
     "c4_streaming": dict(utility0="exp"),
     "c5_compressed": dict(zipf_s=1.1),
     "c3_long_context_tq4": dict(zipf_s=1.1, w_sigma=0.01),
-    "c3_long_context_tq8": dict(zipf_s=1.1, w_sigma=0.007),
-    "c3_kv4_tq16": dict(zipf_s=1.1, w_sigma=0.007),
+    "c3_long_context_tq8": dict(zipf_s=1.1),     # routed by the tile's first query: the router of c3
+    "c3_kv4_tq16": dict(zipf_s=1.1),
 }
 DECAY = {"c4_streaming": 0.9}
 OTHER_WORKLOADS = ("c2_bf16_decode", "c4_streaming", "c5_compressed")
@@ -114,6 +114,8 @@ class Layer:
         self.V_tab = pk.shard_table(tensors["V"])
         self.decay = DECAY.get(g.name, 1.0)
         self.fused = shared.get("fused", False) and not g.per_head_routing
+        import workloads as wl
+        self.route_x = wl.routing_rows(g, tensors["q"])   # what pikv_route sees (the queries are fixed)
 
     def step(self):
         pk, g, t, s = self.pk, self.geo, self.t, self.sh
@@ -150,7 +152,7 @@ class Layer:
                                 s["ecnt"], s["y"], s["row_max"], s["row_norm"], s["scores"],
                                 s["slot_coef"], s["workspace"])
             return
-        pk.pikv_route(t["q"], t["W_r"], t["bias"], g.route_rows, g.d_r, g.E, g.k, s["topk"],
+        pk.pikv_route(self.route_x, t["W_r"], t["bias"], g.route_rows, g.d_r, g.E, g.k, s["topk"],
                       s["gates"], None)
         if not g.per_head_routing:
             pk.pikv_evict(self.desc, t["utility"], t["n_valid"], g.S - 1, s["topk"], g.k, s["eidx"],
@@ -235,7 +237,7 @@ def cpu_baseline(torch, wl, layers, n_steps):
         q = wl.to_host(t["q"], g.dtype)
         W = wl.to_host(t["W_r"], g.dtype)
         bias = None if t["bias"] is None else t["bias"].cpu().numpy()
-        x = np.ascontiguousarray(q.reshape(g.route_rows, g.d_r))
+        x = np.ascontiguousarray(wl.routing_rows(g, q))
         idx, gates, _ = orc.route(x, W, g.k, bias=bias, dtype=g.dtype)
         Ks, Vs = [dummy] * (g.B * g.E), [dummy] * (g.B * g.E)
         for row in range(idx.shape[0]):

@@ -78,8 +78,11 @@ typedef struct pikv_desc {
  * selected shards in one pass, so every K/V byte is streamed once for all of them.  Hq then
  * counts ALL query rows of a sequence, Hq = tq * (query heads of the model), and q, y, row_max
  * and row_norm are laid out [B, tq, Hq / tq, ...] - the natural layout of tq consecutive
- * tokens.  One routing decision is made per sequence from the whole [tq * heads * D] vector
- * (W_r has Hq * D rows).  Each row attends all valid entries of the selected shards; the causal
+ * tokens.  pikv_decode_step makes one routing decision per sequence, from the FIRST query of
+ * the tile alone - q[b][0], the token that is certain to be kept, the others being drafts -
+ * so W_r keeps the shape it has for single-query steps, [(Hq / tq) * D, E].  (pikv_route is
+ * unaware of tq: it routes whatever rows it is given.)
+ * Each row attends all valid entries of the selected shards; the causal
  * part among the drafts themselves is the caller's (row_max / row_norm let it merge them).
  * Supported for bfloat16 rows of D = 128 values (rank 0) with per-token routing and at most 64
  * query rows per kv head (Hq / Hkv <= 64); UNSUPPORTED otherwise.
@@ -214,7 +217,7 @@ int pikv_append(const pikv_desc *desc, const void *K_new, const void *V_new,
  * (order: utility ascending, then higher slot first) -> insert the new token's rows there
  * (or at slot n_valid if the shard has room) -> attention over the selected shards (new
  * entry included) -> utility update.  Results are exactly those of the call sequence
- *   pikv_route(q as [B, Hq*D], W_r, bias, ...);
+ *   pikv_route(q as [B, Hq*D], W_r, bias, ...);          (tq > 1: q[:, 0] as [B, (Hq/tq)*D])
  *   pikv_evict(capacity = S-1, sel_idx = topk_idx, max_evict = 1, compact = 0);
  *   pikv_append(K_new, V_new, topk_idx, reuse = the evict outputs);
  *   pikv_sharded_attn(...); pikv_update_utility(...);

@@ -43,6 +43,7 @@ struct PreParams {
     int32_t *evicted_idx;
     int32_t *evicted_cnt;
     int64_t stride_h_bytes, stride_s_bytes;
+    int64_t x_stride;    // elements between the routed vectors of consecutive sequences (>= d_r)
     int d_r, E, cpr, k, S, Hkv, row_chunks, do_insert;
     int use_policy;      // the entry to evict is chosen by pol (Table 3) instead of the utility
     PolicyView pol;      // its arrays, when given, are also stamped for the new entry
@@ -89,7 +90,7 @@ __global__ __launch_bounds__(kRouteThreads) void step_pre(PreParams p) {
         vnew = load16(static_cast<const char *>(p.V_new) + ((int64_t)b * new_chunks + tid) * 16);
     }
 
-    route_logits_vec<T>(static_cast<const T *>(p.x) + (int64_t)b * p.d_r,
+    route_logits_vec<T>(static_cast<const T *>(p.x) + (int64_t)b * p.x_stride,
                         static_cast<const T *>(p.W_r), p.bias, p.d_r, p.E, p.cpr, red);
     // every wave makes the selection itself from the same sums (same bits): no wave waits for
     // another one's result; the first wave of block j == 0 publishes it
@@ -475,7 +476,11 @@ static int decode_step(const pikv_desc *desc, const void *q, const void *W_r, co
     const int eb = elem_bytes(desc->dtype);
     p.stride_h_bytes = desc->stride_h * eb;
     p.stride_s_bytes = desc->stride_s * eb;
-    p.d_r = desc->Hq * desc->D;
+    // a multi-query step is routed by its first query alone: the leading d_r values of q[b]
+    const int tq = desc->tq > 1 ? desc->tq : 1;
+    if (desc->Hq % tq != 0) return PIKV_ERR_UNSUPPORTED;
+    p.d_r = desc->Hq / tq * desc->D;
+    p.x_stride = (int64_t)desc->Hq * desc->D;
     p.E = desc->E;
     p.cpr = cpr;
     p.k = k;

@@ -72,7 +72,7 @@ class DeviceCase:
     # ---- the calls, each straight through the binding
     def route(self, x=None):
         g = self.geo
-        x = self.q if x is None else x
+        x = wl.routing_rows(g, self.q) if x is None else x
         pk.pikv_route(x, self.W_r, self.bias, g.route_rows, g.d_r, g.E, self.k, self.topk,
                       self.gates, self.probs)
 
@@ -125,7 +125,7 @@ def ensure_route_margin(case: wl.HostCase, k: int, margin: float = 1e-3, max_red
     if g.E == 1:
         return
     for attempt in range(max_redraw):
-        x = case.q.reshape(g.route_rows, g.d_r)
+        x = wl.routing_rows(g, case.q)
         _, _, _, logits = orc.route(np.ascontiguousarray(x), case.W_r, k, bias=case.bias,
                                     dtype=g.dtype, want_logits=True)
         srt = -np.sort(-logits, axis=1)
@@ -134,8 +134,9 @@ def ensure_route_margin(case: wl.HostCase, k: int, margin: float = 1e-3, max_red
         bad = np.nonzero(gaps < margin)[0]
         if bad.size == 0:
             return
-        fresh = wl.draw_queries(g, 10_000 + attempt).reshape(g.route_rows, g.d_r)
-        x = x.copy()
-        x[bad] = fresh[bad]
-        case.q = np.ascontiguousarray(x.reshape(g.B, g.Hq, g.D))
+        # a routed row is a whole sequence (or one head of it): all its queries are redrawn
+        fresh = wl.draw_queries(g, 10_000 + attempt).reshape(g.route_rows, -1)
+        q = case.q.reshape(g.route_rows, -1).copy()
+        q[bad] = fresh[bad]
+        case.q = np.ascontiguousarray(q.reshape(g.B, g.Hq, g.D))
     raise AssertionError("could not reach the routing margin")

@@ -40,16 +40,16 @@ def redraw_for_margin(geo, q_host, W_host, bias_host, k, seed0=77_000):
     """Host-side margin filter (oracle logits in fp64), see gpu_harness.ensure_route_margin."""
     q = q_host.copy()
     for attempt in range(50):
-        x = np.ascontiguousarray(q.reshape(geo.route_rows, geo.d_r))
+        x = np.ascontiguousarray(wl.routing_rows(geo, q))
         _, _, _, logits = orc.route(x, W_host, k, bias=bias_host, dtype=geo.dtype, want_logits=True)
         srt = -np.sort(-logits, axis=1)
         bad = np.nonzero(np.abs(np.diff(srt[:, :k + 1], axis=1)).min(axis=1) < 1e-3)[0]
         if bad.size == 0:
             return q
-        fresh = wl.draw_queries(geo, seed0 + attempt).reshape(geo.route_rows, geo.d_r)
-        x = x.copy()
-        x[bad] = fresh[bad]
-        q = np.ascontiguousarray(x.reshape(geo.B, geo.Hq, geo.D))
+        fresh = wl.draw_queries(geo, seed0 + attempt).reshape(geo.route_rows, -1)
+        q = q.reshape(geo.route_rows, -1).copy()
+        q[bad] = fresh[bad]
+        q = np.ascontiguousarray(q.reshape(geo.B, geo.Hq, geo.D))
     raise AssertionError("routing margin not reached")
 
 
@@ -77,7 +77,7 @@ def test_full_size_step_matches_oracle(name):
     torch.cuda.synchronize()
 
     # --- exact: routing for every row
-    x = np.ascontiguousarray(q_host.reshape(geo.route_rows, geo.d_r))
+    x = np.ascontiguousarray(wl.routing_rows(geo, q_host))      # q_host is in the caller's layout
     idx, gates, _ = orc.route(x, W_host, geo.k, bias=bias_host, dtype=geo.dtype)
     np.testing.assert_array_equal(t2n(shared["topk"]), idx)
     np.testing.assert_allclose(t2n(shared["gates"]), gates, rtol=2e-5, atol=1e-7)

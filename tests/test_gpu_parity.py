@@ -184,7 +184,7 @@ def test_attention_and_utility_match_oracle(name, combine, use_gates):
 @pytest.mark.parametrize("combine", [orc.COMBINE_LSE, orc.COMBINE_LOCAL], ids=["lse", "local"])
 def test_multi_query_step_in_token_major_layout(spec, combine):
     """Draft queries of a multi-query step in their natural layout, q [B, tq, heads, D] with
-    desc.tq = tq: routing on the flat vector, attention of every (draft, head) row over the
+    desc.tq = tq: routing by the tile's first query, attention of every (draft, head) row over the
     selected shards, outputs back in [B, tq, heads] order, utilities summed over all rows.  The
     oracle sees the same rows as Hq = tq * heads plain query heads in kv-head-first order."""
     from gpu_harness import dev_storage
@@ -204,7 +204,9 @@ def test_multi_query_step_in_token_major_layout(spec, combine):
     dc.desc = pk.make_desc(g.B, g.Hq, g.Hkv, g.D, g.E, g.S, dtype=pk.binding.BF16, stride_h=dc.stride_h,
                            stride_s=dc.stride_s, tq=g.tq)
     dc.route()
-    x = np.ascontiguousarray(q_caller.reshape(g.route_rows, g.d_r))
+    x = np.ascontiguousarray(wl.routing_rows(g, q_caller))   # the tile's first query routes the step
+    assert x.shape == (g.B, g.Hq // g.tq * g.D)
+    np.testing.assert_array_equal(x, q_caller[:, :g.Hq // g.tq].reshape(g.B, -1))
     idx, gates, _ = orc.route(x, case.W_r, g.k, dtype=g.dtype)
     np.testing.assert_array_equal(t2n(dc.topk), idx)
     dc.attend(combine=combine)

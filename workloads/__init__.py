@@ -68,7 +68,11 @@ class Geometry:
 
     @property
     def d_r(self) -> int:
-        return self.D if self.per_head_routing else self.Hq * self.D
+        """Length of the vector the router sees: one head (per-head routing), all heads of the
+        token, or - token-major multi-query step - all heads of the tile's first query."""
+        if self.per_head_routing:
+            return self.D
+        return (self.Hq // self.tq if self.token_major else self.Hq) * self.D
 
     @property
     def route_rows(self) -> int:
@@ -115,6 +119,16 @@ EXTRA_CONFIGS = {
                             name="c3_kv4_tq16", tq=16, token_major=True),
 }
 CONFIGS.update(EXTRA_CONFIGS)
+
+
+def routing_rows(g: "Geometry", q):
+    """The rows the router sees, [route_rows, d_r], of queries q [B, Hq, D] held in the caller's
+    layout (numpy array or torch tensor).  Token-major multi-query step: the heads of the first
+    query of every sequence.  Layout only."""
+    if g.token_major and g.tq > 1 and not g.per_head_routing:
+        x = q.reshape(g.B, g.Hq, g.D)[:, :g.Hq // g.tq].reshape(g.B, g.d_r)
+        return x.contiguous() if hasattr(x, "contiguous") else np.ascontiguousarray(x)
+    return q.reshape(g.route_rows, g.d_r)
 
 
 def token_major_rows(Hq: int, Hkv: int, tq: int) -> np.ndarray:
