@@ -58,6 +58,11 @@ def load_library():
     if not os.path.exists(_LIB_PATH):
         raise OSError("libpikv.so is not built: run `python -m paper_2508_06526_amd.build` "
                       "(there is no fallback path)")
+    # The binding passes torch tensors and torch streams to the library, so both must talk to
+    # ONE HIP runtime: torch brings its own copy of libamdhip64, and a libpikv.so opened before
+    # torch would bind to the system's copy instead - its launches on torch's streams then fail
+    # (PIKV_ERR_HIP).  Importing torch first makes the already-loaded runtime the one libpikv gets.
+    import torch  # noqa: F401
     lib = C.CDLL(_LIB_PATH)
     vp, i32, f32 = C.c_void_p, C.c_int32, C.c_float
     dp = C.POINTER(PikvDesc)
