@@ -221,6 +221,29 @@ def test_multi_query_step_in_token_major_layout(spec, combine):
     assert_utility_close(t2n(dc.utility), u_ref)
 
 
+def test_library_opened_before_torch_still_launches():
+    """A caller may load the binding's library before it ever imports torch; both must end up on
+    one HIP runtime (a kernel launched through a second copy fails on torch's streams).  Runs in
+    a fresh interpreter, because this process has imported torch long ago."""
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    code = (
+        "import sys; sys.path.insert(0, %r)\n"
+        "import paper_2508_06526_amd as pk\n"
+        "assert pk.load_library().pikv_version() >= 300\n"
+        "import torch\n"
+        "x = torch.eye(8, device='cuda:0'); W = torch.eye(8, device='cuda:0')\n"
+        "idx = torch.zeros((8, 1), device='cuda:0', dtype=torch.int32); g = torch.zeros((8, 1), device='cuda:0')\n"
+        "pk.pikv_route(x, W, None, 8, 8, 8, 1, idx, g)\n"
+        "torch.cuda.synchronize()\n"
+        "assert idx.flatten().tolist() == list(range(8)), idx\n"
+        "print('ok')\n" % root)
+    r = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, timeout=110)
+    assert r.returncode == 0 and "ok" in r.stdout, (r.stdout[-500:], r.stderr[-1500:])
+
+
 def test_multi_query_layout_is_refused_where_no_kernel_takes_it():
     fake = torch.zeros(64, device=DEV)
     for kw in (dict(D=64), dict(rank=32), dict(dtype=pk.binding.F32)):     # only bf16 rows of 128 values
