@@ -4,6 +4,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 #include "pikv.h"
 
 namespace pikv {
@@ -71,6 +73,29 @@ __device__ __forceinline__ float lane_xchg(float x) {
         return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x141, 0xf, 0xf, true));
     } else if constexpr (BIT == 3) {
         return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x140, 0xf, 0xf, true));
+    } else {
+        return __shfl_xor(x, 1 << BIT, kWave);
+    }
+}
+
+// Exact exchange: lane i receives the value of lane i ^ (1 << BIT), whatever the lanes hold.
+// Inside a row of 16 lanes two DPP moves compose the xor patterns the hardware lacks: the half
+// mirror (i -> i ^ 7) followed by the reversed quad (i -> i ^ 3) is i ^ 4; the row mirror
+// (i -> i ^ 15) followed by the half mirror is i ^ 8.
+template <int BIT>
+__device__ __forceinline__ float lane_xor(float x) {
+    static_assert(BIT >= 0 && BIT < 6, "wave64");
+    auto dpp = [](float v, auto ctrl) {
+        return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), decltype(ctrl)::value, 0xf, 0xf, true));
+    };
+    if constexpr (BIT == 0) {
+        return dpp(x, std::integral_constant<int, 0xB1>{});
+    } else if constexpr (BIT == 1) {
+        return dpp(x, std::integral_constant<int, 0x4E>{});
+    } else if constexpr (BIT == 2) {
+        return dpp(dpp(x, std::integral_constant<int, 0x141>{}), std::integral_constant<int, 0x1B>{});
+    } else if constexpr (BIT == 3) {
+        return dpp(dpp(x, std::integral_constant<int, 0x140>{}), std::integral_constant<int, 0x141>{});
     } else {
         return __shfl_xor(x, 1 << BIT, kWave);
     }

@@ -67,9 +67,10 @@ __global__ __launch_bounds__(kRouteThreads) void route_vec_kernel(const T *x, co
                                                                   float *probs) {
     __shared__ float red[kRouteThreads / kWave][64];
     const int row = blockIdx.x;
+    const float bias_e = route_bias_of_lane(bias, E, threadIdx.x & (kWave - 1));
     route_logits_vec<T>(x + (int64_t)row * d_r, W_r, bias, d_r, E, cpr, red);
     if (threadIdx.x < 64)
-        select_topk(route_logit_of_lane(red, bias, E, threadIdx.x), threadIdx.x, row, E, k, topk_idx, gates,
+        select_topk(route_logit_of_lane(red, bias_e, E, threadIdx.x), threadIdx.x, row, E, k, topk_idx, gates,
                     probs);
 }
 

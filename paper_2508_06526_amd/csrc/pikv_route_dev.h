@@ -83,10 +83,20 @@ __device__ __forceinline__ void route_logits_vec(const T *xr, const T *W_r, cons
     for (; c + 7 * kRouteThreads < total; c += 8 * kRouteThreads) batch(c, std::integral_constant<int, 8>{});
     for (; c + 3 * kRouteThreads < total; c += 4 * kRouteThreads) batch(c, std::integral_constant<int, 4>{});
     for (; c < total; c += kRouteThreads) batch(c, std::integral_constant<int, 1>{});
-    for (int off = cpr; off < kWave; off <<= 1) {
+    // lanes with the same chunk-in-row index: xor butterfly over the lane bits from log2(cpr) up
+    auto join = [&](auto bit) {
+        constexpr int BIT = decltype(bit)::value;
+        if ((1 << BIT) >= cpr) {
 #pragma unroll
-        for (int i = 0; i < EPL; ++i) acc[i] += __shfl_xor(acc[i], off, kWave);
-    }
+            for (int i = 0; i < EPL; ++i) acc[i] += lane_xor<BIT>(acc[i]);
+        }
+    };
+    join(std::integral_constant<int, 0>{});
+    join(std::integral_constant<int, 1>{});
+    join(std::integral_constant<int, 2>{});
+    join(std::integral_constant<int, 3>{});
+    join(std::integral_constant<int, 4>{});
+    join(std::integral_constant<int, 5>{});
     if (lane < cpr) {
 #pragma unroll
         for (int i = 0; i < EPL; ++i) red[wave][cir * EPL + i] = acc[i];
@@ -94,9 +104,16 @@ __device__ __forceinline__ void route_logits_vec(const T *xr, const T *W_r, cons
     __syncthreads();
 }
 
+// The additive term of expert `lane` (0 without a bias or past the last expert).  Callers read
+// it before the weights: it depends on nothing, and a load issued after the block barrier
+// would put a whole trip to memory between the logits and the selection.
+__device__ __forceinline__ float route_bias_of_lane(const float *bias, int E, int lane) {
+    return (bias != nullptr && lane < E) ? bias[lane] : 0.0f;
+}
+
 // Expert `lane`'s logit from the per-wave sums (waves joined in ascending order; experts >= E
 // hold -inf; a NaN logit is replaced by -inf).  Any wavefront may call it after the barrier.
-__device__ __forceinline__ float route_logit_of_lane(const float (*red)[64], const float *bias, int E,
+__device__ __forceinline__ float route_logit_of_lane(const float (*red)[64], float bias_of_lane, int E,
                                                      int lane) {
     constexpr int kWaves = kRouteThreads / kWave;
     float v = -INFINITY;
@@ -104,7 +121,7 @@ __device__ __forceinline__ float route_logit_of_lane(const float (*red)[64], con
         v = 0.0f;
 #pragma unroll
         for (int w = 0; w < kWaves; ++w) v += red[w][lane];
-        v += bias ? bias[lane] : 0.0f;
+        v += bias_of_lane;
         if (v != v) v = -INFINITY;
     }
     return v;

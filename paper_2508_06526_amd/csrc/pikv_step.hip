@@ -82,7 +82,8 @@ __global__ __launch_bounds__(kRouteThreads) void step_pre(PreParams p) {
     __shared__ float red[kWaves][64];
     __shared__ uint64_t wave_best[kWaves];
 
-    // the new rows do not depend on the routing decision: fetch the first chunk now
+    // neither the router's additive term nor the new rows depend on anything: requested now
+    const float bias_e = route_bias_of_lane(p.bias, p.E, lane);
     const int new_chunks = p.Hkv * p.row_chunks;
     uint4 knew = make_uint4(0, 0, 0, 0), vnew = knew;
     if (p.do_insert && tid < new_chunks) {
@@ -94,7 +95,7 @@ __global__ __launch_bounds__(kRouteThreads) void step_pre(PreParams p) {
                         static_cast<const T *>(p.W_r), p.bias, p.d_r, p.E, p.cpr, red);
     // every wave makes the selection itself from the same sums (same bits): no wave waits for
     // another one's result; the first wave of block j == 0 publishes it
-    const int rank = select_topk(route_logit_of_lane(red, p.bias, p.E, lane), lane, b, p.E, p.k,
+    const int rank = select_topk(route_logit_of_lane(red, bias_e, p.E, lane), lane, b, p.E, p.k,
                                  (j == 0 && wave == 0) ? p.topk : nullptr, p.gates, nullptr);
     if (!p.do_insert) return;
 
