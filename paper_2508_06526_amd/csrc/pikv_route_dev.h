@@ -17,20 +17,47 @@ constexpr int kRouteThreads = 1024;
 // under (logit descending, index ascending); lanes with rank < k are the selection.  Every
 // wavefront that calls it with the same logits gets the same result, so a block may let all
 // its waves call it instead of broadcasting one wave's result through a barrier.
+// Lane i receives the value of lane (i - R) & 15 of its row of 16 lanes (DPP row rotate right).
+template <int R>
+__device__ __forceinline__ float row_rotate(float x) {
+    static_assert(R >= 1 && R <= 15, "rotation inside a row of 16 lanes");
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x120 + R, 0xf, 0xf, true));
+}
+
+// rank += [expert (lane - R) & 15 beats this lane's expert], R = 1 .. 15: with E <= 16 all experts
+// sit in the first row of 16 lanes, and every pair meets in one rotation without the scalar unit.
+template <int R>
+__device__ __forceinline__ void rank_by_rotation(float mine, int lane, int &rank) {
+    if constexpr (R <= 15) {
+        const float other = row_rotate<R>(mine);
+        const int o = (lane - R) & 15;
+        rank += (other > mine) || (other == mine && o < lane);
+        rank_by_rotation<R + 1>(mine, lane, rank);
+    }
+}
+
 __device__ __forceinline__ int select_topk(float mine, int lane, int row, int E, int k,
                                            int32_t *topk_idx, float *gates, float *probs) {
-    const float mx = bits_max<0, 6>(mine);
+    // Lanes >= E hold the identities (-inf, 0), and only lanes < E use the results: with E <= 16
+    // the butterflies stay inside the first row of 16 lanes (same operands, same bits).
+    const bool one_row = E <= 16;
+    const float mx = one_row ? bits_max<0, 4>(mine) : bits_max<0, 6>(mine);
     const float pe = lane < E ? __expf(mine - mx) : 0.0f;
-    const float den = bits_sum<0, 6>(pe);
+    const float den = one_row ? bits_sum<0, 4>(pe) : bits_sum<0, 6>(pe);
     if (probs && lane < E) probs[(int64_t)row * E + lane] = pe / den;
 
     int rank = 0;
-    for (int o = 0; o < E; ++o) {      // every lane's logit passes through the scalar unit
-        const float other = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(mine), o));
-        rank += (other > mine) || (other == mine && o < lane);
+    if (one_row) {
+        rank_by_rotation<1>(mine, lane, rank);
+    } else {
+        for (int o = 0; o < E; ++o) {      // every lane's logit passes through the scalar unit
+            const float other = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(mine), o));
+            rank += (other > mine) || (other == mine && o < lane);
+        }
     }
     const bool chosen = lane < E && rank < k;
-    const float sel = bits_sum<0, 6>(chosen ? pe : 0.0f);
+    const float picked = chosen ? pe : 0.0f;
+    const float sel = one_row ? bits_sum<0, 4>(picked) : bits_sum<0, 6>(picked);
     if (chosen && topk_idx) {
         topk_idx[(int64_t)row * k + rank] = lane;
         gates[(int64_t)row * k + rank] = pe / sel;
