@@ -216,7 +216,8 @@ inline size_t post_smem_bytes(int threads, int np, int pairs) {
     return util > comb ? util : comb;
 }
 
-// Blocks [0, B*Hq) merge one query head each; the others update the utilities of
+// B*Hq blocks merge one query head each (the grid's first ids, or with util_first those after
+// the utility blocks); the others update the utilities of
 // tiles_per_block tiles of THREADS/4 slots of the j-th selected shard of a sequence.  THREADS
 // is the merge's block size (combine_threads), so that the merge is bit-identical to the
 // stand-alone kernel.
