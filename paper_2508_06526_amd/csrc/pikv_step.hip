@@ -82,8 +82,11 @@ __global__ __launch_bounds__(kRouteThreads) void step_pre(PreParams p) {
     __shared__ float red[kWaves][64];
     __shared__ uint64_t wave_best[kWaves];
 
-    // neither the router's additive term nor the new rows depend on anything: requested now
+    // neither the router's additive term, nor the entry counts of the sequence's shards (lane e
+    // takes shard e's; the selected one is picked out of the register once the router has
+    // spoken), nor the new rows depend on anything: requested now
     const float bias_e = route_bias_of_lane(p.bias, p.E, lane);
+    const int n_of_lane = p.n_valid[(int64_t)b * p.E + min(lane, p.E - 1)];
     const int new_chunks = p.Hkv * p.row_chunks;
     uint4 knew = make_uint4(0, 0, 0, 0), vnew = knew;
     if (p.do_insert && tid < new_chunks) {
@@ -99,10 +102,11 @@ __global__ __launch_bounds__(kRouteThreads) void step_pre(PreParams p) {
                                  (j == 0 && wave == 0) ? p.topk : nullptr, p.gates, nullptr);
     if (!p.do_insert) return;
 
-    // one round trip for everything that hangs off the expert id
+    // one round trip for everything that hangs off the expert id (the shard's table entries
+    // and its utilities); its entry count is already here
     const int e = __builtin_ctzll(__ballot(rank == j));
+    const int n = __builtin_amdgcn_readlane(n_of_lane, e);
     const int64_t be = (int64_t)b * p.E + e;
-    const int n = p.n_valid[be];
     char *Kd = static_cast<char *>(p.K[be]);
     char *Vd = static_cast<char *>(p.V[be]);
     const float *u = p.utility + be * p.S;
@@ -125,14 +129,28 @@ __global__ __launch_bounds__(kRouteThreads) void step_pre(PreParams p) {
             }
         }
     } else if ((p.S & 3) == 0) {
-        for (int i = tid * 4; i < p.S; i += kRouteThreads * 4) {
-            const float4 v = *reinterpret_cast<const float4 *>(u + i);
-            uint64_t c0 = evict_composite(v.x, i), c1 = evict_composite(v.y, i + 1);
-            uint64_t c2 = evict_composite(v.z, i + 2), c3 = evict_composite(v.w, i + 3);
-            c0 = c0 < c1 ? c0 : c1;
-            c2 = c2 < c3 ? c2 : c3;
-            c0 = c0 < c2 ? c0 : c2;
-            best = c0 < best ? c0 : best;
+        // two 16-byte loads per thread and pass, both requested before either is used: up to
+        // 8192 slots are one trip to memory, not one per 4096
+        constexpr int kScanLoads = 2;
+        for (int i0 = tid * 4; i0 < p.S; i0 += kRouteThreads * 4 * kScanLoads) {
+            float4 v[kScanLoads];
+#pragma unroll
+            for (int t = 0; t < kScanLoads; ++t) {
+                const int i = i0 + t * kRouteThreads * 4;
+                v[t] = i < p.S ? *reinterpret_cast<const float4 *>(u + i) : make_float4(0.f, 0.f, 0.f, 0.f);
+            }
+#pragma unroll
+            for (int t = 0; t < kScanLoads; ++t) {
+                const int i = i0 + t * kRouteThreads * 4;
+                if (i < p.S) {
+                    uint64_t c0 = evict_composite(v[t].x, i), c1 = evict_composite(v[t].y, i + 1);
+                    uint64_t c2 = evict_composite(v[t].z, i + 2), c3 = evict_composite(v[t].w, i + 3);
+                    c0 = c0 < c1 ? c0 : c1;
+                    c2 = c2 < c3 ? c2 : c3;
+                    c0 = c0 < c2 ? c0 : c2;
+                    best = c0 < best ? c0 : best;
+                }
+            }
         }
     } else {
         for (int i = tid; i < p.S; i += kRouteThreads) {
