@@ -266,13 +266,19 @@ __global__ __launch_bounds__(THREADS) void step_post(PostParams p) {
     const int j = bid % k;
     const int b = bid / k;
     const int tid = threadIdx.x;
-    // Order of the requests: loads come back in the order they were issued, and nothing that
-    // is needed early may queue behind something slow.  The expert id goes first (the entry
-    // count hangs off it), then the (max, sum) pairs of the statistics - which need neither -
-    // then the scores (a trip to memory, with the shard's capacity as the bound: slots past the
-    // entry count are masked when they are used); the entry count is read only after the
-    // statistics, where a block past the shard's end leaves.
-    const int e = p.topk[(int64_t)b * k + j];
+    // Order of the requests: loads come back in the order they were issued, a value the
+    // compiler knows to be the same in all lanes is waited for where it is loaded (it goes to a
+    // scalar register at once), and nothing that is needed early may queue behind something
+    // slow.  So the sequence's selections, entry counts and gates are read one per lane, first
+    // (lane l takes selection l, shard l's count and gate l; the block's own are picked out of
+    // the registers after the statistics); then the (max, sum) pairs of the statistics; then
+    // the scores - a trip to memory, with the shard's capacity as the bound: slots past the
+    // entry count are masked when they are used, and a block past the shard's end leaves after
+    // the statistics.
+    const int lane_id = tid & (kWave - 1);
+    const int sel_of_lane = p.topk[(int64_t)b * k + min(lane_id, k - 1)];
+    const int n_of_lane = p.n_valid[(int64_t)b * p.E + min(lane_id, p.E - 1)];
+    const float gate_of_thread = (p.c.gates != nullptr && tid < k) ? p.c.gates[(int64_t)b * k + tid] : 1.0f;
     const int i0 = tile * kSlots * ntiles;
 
     const int pairs = post_pairs_pad(Hq * k);
@@ -288,11 +294,15 @@ __global__ __launch_bounds__(THREADS) void step_post(PostParams p) {
     const int gsize = (Hq + 3) / 4;
     const int h_lo = hg * gsize, h_hi = min(Hq, h_lo + gsize);
     float sc[kPostPrefetchHeads];
+    // (unconditional loads from clamped, always valid addresses: heads past the group's end and
+    // slots past the limit are masked where the values are used.  Loads under a lane-dependent
+    // branch would make every later wait a wait for ALL loads in flight.)
     auto fetch = [&](int i, int limit) {
+        const int ic = min(i, limit - 1);
 #pragma unroll
         for (int t = 0; t < kPostPrefetchHeads; ++t) {
-            const int h = h_lo + t;
-            sc[t] = (h < h_hi && i < limit) ? p.scores[(((int64_t)b * Hq + h) * k + j) * p.S + i] : 0.0f;
+            const int h = min(h_lo + t, Hq - 1);
+            sc[t] = p.scores[(((int64_t)b * Hq + h) * k + j) * p.S + ic];
         }
     };
     int i = i0 + slot;
@@ -318,11 +328,7 @@ __global__ __launch_bounds__(THREADS) void step_post(PostParams p) {
     ShardPairs held[kAhead];
 #pragma unroll
     for (int a = 0; a < kAhead; ++a) held[a] = load_pass(a);
-    if (p.c.gates != nullptr && tid < k) g_s[tid] = p.c.gates[(int64_t)b * k + tid];
     fetch(i, p.S);
-    const int n = p.n_valid[(int64_t)b * p.E + e];
-    float *urow = p.utility + ((int64_t)b * p.E + e) * p.S;
-    float u_old = (i < p.S && hg == 0) ? urow[i] : 0.0f;
 
     const int passes = (npairs + kPairsPerPass - 1) / kPairsPerPass;
     for (int pass0 = 0; pass0 < passes; pass0 += kAhead) {
@@ -345,7 +351,12 @@ __global__ __launch_bounds__(THREADS) void step_post(PostParams p) {
             }
         }
     }
+    const int e = __builtin_amdgcn_readlane(sel_of_lane, j);
+    const int n = __builtin_amdgcn_readlane(n_of_lane, e);
     if (i0 >= n) return;     // block-uniform: no entries in this block's slots
+    float *urow = p.utility + ((int64_t)b * p.E + e) * p.S;
+    float u_old = (i < n && hg == 0) ? urow[i] : 0.0f;
+    if (p.c.gates != nullptr && tid < k) g_s[tid] = gate_of_thread;
     __syncthreads();
     // (shift, coef) of every (head, shard) pair: an aligned group of kp lanes per head
     const int kp = pow2_at_least(k);
