@@ -23,8 +23,15 @@ namespace pikv {
 
 namespace {
 
-constexpr int kLoadsPerTile = 8;   // 16-byte loads each lane keeps in flight per K (or V) tile
 constexpr int kWavesPerBlock = 4;
+
+// Shape of the plain-ALU kernel by row size and heads per block.  16-byte loads each lane keeps
+// in flight per K (or V) tile: 8, or kShortRowLoads for one head over rows of at most 128 bytes (rank-r codes):
+// that kernel then fits 128 registers, a CU holds four of its 4-wave blocks instead of three, and
+// 1024 (sequence, head, shard) units run in one round of resident blocks instead of one and a third.
+constexpr int kShortRowLoads = 4;
+constexpr bool plain_short_rows(int row_bytes, int gb) { return gb == 1 && row_bytes <= 128; }
+constexpr int plain_loads_per_tile(int row_bytes, int gb) { return plain_short_rows(row_bytes, gb) ? kShortRowLoads : 8; }
 
 struct AttnParams {
     const void *q;
@@ -93,14 +100,17 @@ __device__ __forceinline__ int64_t query_row(const AttnParams &p, int b, int h) 
 // 4-wave blocks of the plain-ALU kernel that one CU holds: its register footprint grows with the
 // heads per block (about 150 VGPRs at one head, 180-240 at two and four, all 256 at eight).
 // The launch bounds hold the compiler to it and the split plan counts resident blocks with it.
-constexpr int plain_blocks_per_cu(int gb) { return gb == 1 ? 3 : (gb <= 4 ? 2 : 1); }
+constexpr int plain_blocks_per_cu(int row_bytes, int gb) {
+    return plain_short_rows(row_bytes, gb) ? 4 : gb == 1 ? 3 : (gb <= 4 ? 2 : 1);
+}
 
 template <typename T, int W, int GB>
-__global__ __launch_bounds__(kWavesPerBlock *kWave, plain_blocks_per_cu(GB)) void attn_partial(AttnParams p) {
+__global__ __launch_bounds__(kWavesPerBlock *kWave, plain_blocks_per_cu(W * (int)sizeof(T), GB)) void attn_partial(
+    AttnParams p) {
     constexpr int EPL = Pack16<T>::N;        // elements per lane per load
     constexpr int LPR = W / EPL;             // lanes covering one row
     constexpr int RPL = kWave / LPR;         // rows covered by one wave load
-    constexpr int NL = kLoadsPerTile;
+    constexpr int NL = plain_loads_per_tile(W * (int)sizeof(T), GB);
     constexpr int TILE = RPL * NL;           // rows per wave iteration
     constexpr int CB = ilog2(LPR);           // lane bits that index the column chunk
     static_assert(LPR >= 1 && LPR <= 32 && (LPR & (LPR - 1)) == 0, "row must be 16..512 bytes");
@@ -805,12 +815,13 @@ int make_attn_plan(const pikv_desc *d, int k, AttnPlan *plan) {
     const int epl = 16 / elem_bytes(d->dtype);
     const int lpr = W / epl;
     if (lpr < 1 || lpr > 32) return PIKV_ERR_UNSUPPORTED;
-    const int tile = gqa_mfma ? kGqaTile : (kWave / lpr) * kLoadsPerTile;
+    const int row_bytes = W * elem_bytes(d->dtype);
+    const int tile = gqa_mfma ? kGqaTile : (kWave / lpr) * plain_loads_per_tile(row_bytes, gb);
     const int64_t units = (int64_t)d->B * (d->Hq / gb) * k;
     // One round of resident blocks: 256 CUs times the 4-wave blocks a CU holds at this
     // kernel's register footprint.  Fewer, longer blocks keep the per-wave prefetch chain
     // busy and shrink the partials that the combine pass has to merge.
-    int resident = gqa_mfma ? (row_tiles == 1 ? 3 : 2) : plain_blocks_per_cu(gb);
+    int resident = gqa_mfma ? (row_tiles == 1 ? 3 : 2) : plain_blocks_per_cu(row_bytes, gb);
     int64_t nsplit = 1;
     int chunk = 0;
     auto split_for = [&](int res) {
