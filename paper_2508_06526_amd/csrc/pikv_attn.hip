@@ -433,7 +433,13 @@ struct GqaShape {
     static constexpr bool kPrefetchK = RT < 4;
 };
 
-template <int RT>
+// SC: what happens to the raw scores - kScoresNone (not asked for), kScoresStaged (kept in LDS,
+// one burst per row at the block's end) or kScoresDirect (written from the loop).  A template
+// parameter and not a run-time branch: each form costs registers, and a value spilled for one
+// of them is reloaded inside the loop by a scratch load, which the wait counters cannot tell
+// from the tile loads in flight - the wave then waits for all of them.
+constexpr int kScoresNone = 0, kScoresStaged = 1, kScoresDirect = 2;
+template <int RT, int SC>
 __global__ __launch_bounds__(kWavesPerBlock *kWave, GqaShape<RT>::kBlocksPerCU) void attn_partial_gqa128(
     AttnParams p) {
     constexpr int W = 128;
@@ -560,7 +566,16 @@ __global__ __launch_bounds__(kWavesPerBlock *kWave, GqaShape<RT>::kBlocksPerCU) 
         const int tnext = t0 + kWavesPerBlock * kGqaTile;
 
         // K rows -> LDS (row-major, padded), then the next tile's K loads reuse the registers
-        if constexpr (!KPRE) load_tile(kr, Kb, t0);
+        if constexpr (!KPRE) {
+            // K where it is used: the clamped form for every tile (one code path, no branch
+            // between the loads and their use), with 32-bit byte offsets from the kv head's base
+            // (the host admits this kernel only for less than 4 GiB per kv head of a shard)
+#pragma unroll
+            for (int t = 0; t < 8; ++t) {
+                const unsigned row = (unsigned)min(t0 + 8 * r + t, r1 - 1);
+                kr[t] = load16_stream(Kb + (size_t)(row * (unsigned)row_bytes + 16u * (unsigned)c));
+            }
+        }
 #pragma unroll
         for (int t = 0; t < 8; ++t)
             *reinterpret_cast<uint4 *>(kst + (8 * r + t) * kGqaKPitch + 16 * c) = kr[t];
@@ -600,7 +615,7 @@ __global__ __launch_bounds__(kWavesPerBlock *kWave, GqaShape<RT>::kBlocksPerCU) 
                     const int row = t0 + 16 * hb + 4 * r + x;
                     sv[hb * 4 + x] = row < r1 ? sc[hb][x] * p.scale : -INFINITY;
                 }
-            if (p.scores != nullptr && row_g < gb && p.stage_scores) {
+            if (SC == kScoresStaged && row_g < gb) {
                 // [row of the group][row of the block]: chunk is a multiple of the tile, so the
                 // float4 stores stay aligned
                 float *dst = gqa_stage + row_g * p.chunk + (t0 - r0) + 4 * r;
@@ -608,7 +623,7 @@ __global__ __launch_bounds__(kWavesPerBlock *kWave, GqaShape<RT>::kBlocksPerCU) 
                 for (int hb = 0; hb < 2; ++hb)
                     *reinterpret_cast<float4 *>(dst + 16 * hb) =
                         make_float4(sv[hb * 4], sv[hb * 4 + 1], sv[hb * 4 + 2], sv[hb * 4 + 3]);
-            } else if (p.scores != nullptr && row_g < gb) {
+            } else if (SC == kScoresDirect && row_g < gb) {
                 float *dst = p.scores + (((int64_t)b * p.Hq + h0 + row_g) * p.k + j) * p.S + t0 + 4 * r;
 #pragma unroll
                 for (int hb = 0; hb < 2; ++hb) {
@@ -693,11 +708,22 @@ __global__ __launch_bounds__(kWavesPerBlock *kWave, GqaShape<RT>::kBlocksPerCU) 
             }
             wave_lds_order();                // the P tiles are rewritten by the next row tile
         }
-        if (tnext < r1) load_tile(vr, Vb, tnext);
+        if constexpr (KPRE) {
+            if (tnext < r1) load_tile(vr, Vb, tnext);
+        } else {
+            // the next tile's V rows, requested on the loop's own path (its exit test comes first)
+            // rather than under a condition inside it
+            if (tnext >= r1) break;
+#pragma unroll
+            for (int t = 0; t < 8; ++t) {
+                const unsigned row = (unsigned)min(tnext + 8 * r + t, r1 - 1);
+                vr[t] = load16_stream(Vb + (size_t)(row * (unsigned)row_bytes + 16u * (unsigned)c));
+            }
+        }
     }
 
     __syncthreads();
-    if (p.scores != nullptr && p.stage_scores) {   // the block's scores: one burst per row of the group
+    if (SC == kScoresStaged) {   // the block's scores: one burst per row of the group
         const int rows = r1 - r0, rows4 = rows & ~3;
         for (int g = 0; g < gb; ++g) {
             float *dst = p.scores + (((int64_t)b * p.Hq + h0 + g) * p.k + j) * p.S + r0;
@@ -806,7 +832,8 @@ int make_attn_plan(const pikv_desc *d, int k, AttnPlan *plan) {
     int gb = 1;
     if (d->route_rows_per_seq == 1 && (G == 2 || G == 4 || G == 8)) gb = G;
     const bool gqa_mfma = d->route_rows_per_seq == 1 && d->dtype == PIKV_BF16 && d->rank == 0 &&
-                          d->D == 128 && G >= 2 && G <= 64;
+                          d->D == 128 && G >= 2 && G <= 64 &&
+                          (int64_t)d->S * d->stride_s * 2 < ((int64_t)1 << 32);
     if (gqa_mfma) gb = G;
     const int tq = d->tq > 1 ? d->tq : 1;
     // draft queries are folded into the query group of the matrix-core kernel only
@@ -984,9 +1011,19 @@ int launch_attn_partial(const pikv_desc *desc, const void *q, const void *const 
         const size_t lds = p.stage_scores ? plan.score_stage_bytes : 0;
         const dim3 grid((unsigned)blocks64), block(kWavesPerBlock * kWave);
         switch (plan.row_tiles) {
-            case 1: hipLaunchKernelGGL(attn_partial_gqa128<1>, grid, block, lds, st, p); break;
-            case 2: hipLaunchKernelGGL(attn_partial_gqa128<2>, grid, block, lds, st, p); break;
-            default: hipLaunchKernelGGL(attn_partial_gqa128<4>, grid, block, lds, st, p); break;
+#define PIKV_LAUNCH_GQA(RT)                                                                                 \
+    do {                                                                                                    \
+        if (p.scores == nullptr)                                                                            \
+            hipLaunchKernelGGL((attn_partial_gqa128<RT, kScoresNone>), grid, block, lds, st, p);            \
+        else if (p.stage_scores)                                                                            \
+            hipLaunchKernelGGL((attn_partial_gqa128<RT, kScoresStaged>), grid, block, lds, st, p);          \
+        else                                                                                                \
+            hipLaunchKernelGGL((attn_partial_gqa128<RT, kScoresDirect>), grid, block, lds, st, p);          \
+    } while (0)
+            case 1: PIKV_LAUNCH_GQA(1); break;
+            case 2: PIKV_LAUNCH_GQA(2); break;
+            default: PIKV_LAUNCH_GQA(4); break;
+#undef PIKV_LAUNCH_GQA
         }
         lrc = launch_status();
     } else {
