@@ -194,7 +194,8 @@ def make_shared(pk, torch, geo, dev):
 def attn_kernel_name(geo):
     g = geo.Hq // geo.Hkv
     if geo.dtype == "bf16" and geo.rank == 0 and geo.D == 128 and not geo.per_head_routing and 2 <= g <= 64:
-        return "attn_partial_gqa128<%d>" % (1 if g <= 16 else 2 if g <= 32 else 4)
+        # (row tiles, form of the score output: the second template argument is the library's choice)
+        return "attn_partial_gqa128<%d, *>" % (1 if g <= 16 else 2 if g <= 32 else 4)
     gb = g if (not geo.per_head_routing and g in (2, 4, 8)) else 1
     return "attn_partial<%s, %d, %d>" % ("pikv::bf16" if geo.dtype == "bf16" else "float", geo.width, gb)
 
