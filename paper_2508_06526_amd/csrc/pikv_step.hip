@@ -362,6 +362,9 @@ __global__ __launch_bounds__(THREADS) void step_post(PostParams p) {
     const int kp = pow2_at_least(k);
     for (int h0 = 0; h0 < Hq; h0 += THREADS / kp) {
         const int h = h0 + tid / kp, jj = tid & (kp - 1);
+        // a wave holds 64 / kp whole heads: one whose first head is past the end has nothing to
+        // do and leaves the SIMD to the waves that have (wave-uniform branch)
+        if (__builtin_amdgcn_readfirstlane(h) >= Hq) break;
         const bool mine = h < Hq && jj < k;
         const HeadWeights hw = head_weights(kp, mine ? Mj_s[h * k + jj] : 0.0f, mine ? Zj_s[h * k + jj] : 0.0f,
                                             (mine && p.c.gates) ? g_s[jj] : 1.0f, p.c.combine);
@@ -374,12 +377,17 @@ __global__ __launch_bounds__(THREADS) void step_post(PostParams p) {
     for (int it = 0; it < ntiles; ++it) {
         const bool live = i < n;
         float a = 0.0f;
-        if (live) {
+        // the prefetched heads, without branches: the group's head range is the same in the whole
+        // wave (a scalar compare picks the sum or leaves it), heads past its end read a clamped,
+        // valid pair, and lanes past the entry count compute on their clamped scores for nothing
+        const int held_heads = __builtin_amdgcn_readfirstlane(h_hi - h_lo);
 #pragma unroll
-            for (int t = 0; t < kPostPrefetchHeads; ++t) {
-                const int h = h_lo + t;
-                if (h < h_hi) a = fmaf(coef_s[h * k + j], __expf(sc[t] - shift_s[h * k + j]), a);
-            }
+        for (int t = 0; t < kPostPrefetchHeads; ++t) {
+            const int h = min(h_lo + t, Hq - 1);
+            const float with = fmaf(coef_s[h * k + j], __expf(sc[t] - shift_s[h * k + j]), a);
+            a = t < held_heads ? with : a;
+        }
+        if (live) {
             // more heads per group than were prefetched: batches of loads, same ascending order
             for (int hb = h_lo + kPostPrefetchHeads; hb < h_hi; hb += kPostPrefetchHeads) {
                 float more[kPostPrefetchHeads];
