@@ -36,18 +36,15 @@ __device__ __forceinline__ void rank_by_rotation(float mine, int lane, int &rank
     }
 }
 
-__device__ __forceinline__ int select_topk(float mine, int lane, int row, int E, int k,
-                                           int32_t *topk_idx, float *gates, float *probs) {
-    // Lanes >= E hold the identities (-inf, 0), and only lanes < E use the results: with E <= 16
-    // the butterflies stay inside the first row of 16 lanes (same operands, same bits).
-    const bool one_row = E <= 16;
-    const float mx = one_row ? bits_max<0, 4>(mine) : bits_max<0, 6>(mine);
-    const float pe = lane < E ? __expf(mine - mx) : 0.0f;
-    const float den = one_row ? bits_sum<0, 4>(pe) : bits_sum<0, 6>(pe);
-    if (probs && lane < E) probs[(int64_t)row * E + lane] = pe / den;
-
+// The selection in two parts, so that a caller can start what depends on the selected experts
+// alone (their ranks) before the gates exist: the rank needs the logits only, the gates need the
+// softmax as well.
+//   route_rank : the lane's rank under (logit descending, index ascending), 64 in lanes >= E.
+//   route_gates: softmax over the E logits, the gates of the k selected experts renormalised
+//                over the selection; writes topk_idx / gates (and probs) when given.
+__device__ __forceinline__ int route_rank(float mine, int lane, int E) {
     int rank = 0;
-    if (one_row) {
+    if (E <= 16) {
         rank_by_rotation<1>(mine, lane, rank);
     } else {
         for (int o = 0; o < E; ++o) {      // every lane's logit passes through the scalar unit
@@ -55,6 +52,17 @@ __device__ __forceinline__ int select_topk(float mine, int lane, int row, int E,
             rank += (other > mine) || (other == mine && o < lane);
         }
     }
+    return lane < E ? rank : 64;
+}
+__device__ __forceinline__ void route_gates(float mine, int rank, int lane, int row, int E, int k,
+                                            int32_t *topk_idx, float *gates, float *probs) {
+    // Lanes >= E hold the identities (-inf, 0), and only lanes < E use the results: with E <= 16
+    // the butterflies stay inside the first row of 16 lanes (same operands, same bits).
+    const bool one_row = E <= 16;
+    const float mx = one_row ? bits_max<0, 4>(mine) : bits_max<0, 6>(mine);
+    const float pe = lane < E ? __expf(mine - mx) : 0.0f;
+    const float den = one_row ? bits_sum<0, 4>(pe) : bits_sum<0, 6>(pe);
+    if (probs && lane < E) probs[(int64_t)row * E + lane] = pe / den;
     const bool chosen = lane < E && rank < k;
     const float picked = chosen ? pe : 0.0f;
     const float sel = one_row ? bits_sum<0, 4>(picked) : bits_sum<0, 6>(picked);
@@ -62,7 +70,12 @@ __device__ __forceinline__ int select_topk(float mine, int lane, int row, int E,
         topk_idx[(int64_t)row * k + rank] = lane;
         gates[(int64_t)row * k + rank] = pe / sel;
     }
-    return lane < E ? rank : 64;
+}
+__device__ __forceinline__ int select_topk(float mine, int lane, int row, int E, int k,
+                                           int32_t *topk_idx, float *gates, float *probs) {
+    const int rank = route_rank(mine, lane, E);
+    route_gates(mine, rank, lane, row, E, k, topk_idx, gates, probs);
+    return rank;
 }
 
 // Logits of one routed row with the whole 1024-thread block, for a row-major W_r whose rows

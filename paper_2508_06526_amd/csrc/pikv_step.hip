@@ -96,15 +96,29 @@ __global__ __launch_bounds__(kRouteThreads) void step_pre(PreParams p) {
 
     route_logits_vec<T>(static_cast<const T *>(p.x) + (int64_t)b * p.x_stride,
                         static_cast<const T *>(p.W_r), p.bias, p.d_r, p.E, p.cpr, red);
-    // every wave makes the selection itself from the same sums (same bits): no wave waits for
-    // another one's result; the first wave of block j == 0 publishes it
-    const int rank = select_topk(route_logit_of_lane(red, bias_e, p.E, lane), lane, b, p.E, p.k,
-                                 (j == 0 && wave == 0) ? p.topk : nullptr, p.gates, nullptr);
-    if (!p.do_insert) return;
-
-    // one round trip for everything that hangs off the expert id (the shard's table entries
-    // and its utilities); its entry count is already here
-    const int e = __builtin_ctzll(__ballot(rank == j));
+    // The first wave ranks the experts and tells the others which shard is the block's (one LDS
+    // word and a barrier): sixteen waves doing it side by side, four to a SIMD, take twice as
+    // long as one wave alone plus the barrier.  The ranks come first - the shard to scan hangs
+    // off them alone - and the softmax and the gates are formed, by that wave of the sequence's
+    // first block, while the scan's requests are in flight.
+    __shared__ int block_expert;
+    float logit = 0.0f;
+    int rank = 64;
+    if (wave == 0) {
+        logit = route_logit_of_lane(red, bias_e, p.E, lane);
+        rank = route_rank(logit, lane, p.E);
+        const uint64_t owner = __ballot(rank == j);      // taken with every lane of the wave active
+        if (lane == 0) block_expert = __builtin_ctzll(owner);
+    }
+    auto publish = [&]() {
+        if (j == 0 && wave == 0) route_gates(logit, rank, lane, b, p.E, p.k, p.topk, p.gates, nullptr);
+    };
+    if (!p.do_insert) {
+        publish();
+        return;
+    }
+    __syncthreads();
+    const int e = __builtin_amdgcn_readfirstlane(block_expert);
     const int n = __builtin_amdgcn_readlane(n_of_lane, e);
     const int64_t be = (int64_t)b * p.E + e;
     char *Kd = static_cast<char *>(p.K[be]);
@@ -112,6 +126,7 @@ __global__ __launch_bounds__(kRouteThreads) void step_pre(PreParams p) {
     const float *u = p.utility + be * p.S;
     uint64_t best = ~0ull;
     if (p.use_policy) {
+        publish();
         if (policy_vec_ok(p.pol, p.utility, p.S)) {
             for (int i = tid * 4; i < p.S; i += kRouteThreads * 4) {
                 float v[4];
@@ -131,14 +146,20 @@ __global__ __launch_bounds__(kRouteThreads) void step_pre(PreParams p) {
     } else if ((p.S & 3) == 0) {
         // two 16-byte loads per thread and pass, both requested before either is used: up to
         // 8192 slots are one trip to memory, not one per 4096
+        // (the first pass's requests are in flight while the gates are formed and published)
         constexpr int kScanLoads = 2;
-        for (int i0 = tid * 4; i0 < p.S; i0 += kRouteThreads * 4 * kScanLoads) {
-            float4 v[kScanLoads];
+        float4 v[kScanLoads];
+        auto request = [&](int i0) {
 #pragma unroll
             for (int t = 0; t < kScanLoads; ++t) {
                 const int i = i0 + t * kRouteThreads * 4;
                 v[t] = i < p.S ? *reinterpret_cast<const float4 *>(u + i) : make_float4(0.f, 0.f, 0.f, 0.f);
             }
+        };
+        request(tid * 4);
+        publish();
+        for (int i0 = tid * 4; i0 < p.S; i0 += kRouteThreads * 4 * kScanLoads) {
+            if (i0 != tid * 4) request(i0);
 #pragma unroll
             for (int t = 0; t < kScanLoads; ++t) {
                 const int i = i0 + t * kRouteThreads * 4;
@@ -153,6 +174,7 @@ __global__ __launch_bounds__(kRouteThreads) void step_pre(PreParams p) {
             }
         }
     } else {
+        publish();
         for (int i = tid; i < p.S; i += kRouteThreads) {
             const uint64_t c0 = evict_composite(u[i], i);
             best = c0 < best ? c0 : best;
@@ -161,9 +183,11 @@ __global__ __launch_bounds__(kRouteThreads) void step_pre(PreParams p) {
     best = wave_min_u64(best);
     if (lane == 0) wave_best[wave] = best;
     __syncthreads();
-    uint64_t m = wave_best[0];
-#pragma unroll
-    for (int w = 1; w < kWaves; ++w) m = wave_best[w] < m ? wave_best[w] : m;
+    // what is left - the new rows and the bookkeeping - takes the block's first waves only: the
+    // others leave, and with them their share of the SIMDs' issue slots
+    if (wave != 0 && wave * kWave >= new_chunks) return;
+    static_assert(kWaves <= 16, "one LDS word per lane of a row");
+    uint64_t m = wave_min_u64(wave_best[lane & (kWaves - 1)]);
     const bool full = n >= p.S;
     const int slot = full ? evict_composite_slot(m) : n;
 
