@@ -869,6 +869,20 @@ int make_attn_plan(const pikv_desc *d, int k, AttnPlan *plan) {
         chunk = (int)((d->S + nsplit - 1) / nsplit);
         chunk = (chunk + tile - 1) / tile * tile;
         nsplit = (d->S + chunk - 1) / chunk;
+        // Matrix-core kernel: when that leaves the waves of a block uneven tile counts (c3: 11
+        // tiles, 3 + 3 + 3 + 2) and blocks of exactly two tiles per wave are at most a third more
+        // blocks, in whole multiples of the 256 CUs, take those.  The extra blocks form a short
+        // last round, and a wave whose first tile is served late has one tile left instead of two
+        // (c3: 24 -> 32 splits, pass 23.4 -> 23.1 us).  Longer even blocks in a partial round
+        // measured slower (k = 16: 8 splits of 8 tiles per wave against 6 splits, +3.7 %).
+        const int even = 2 * kWavesPerBlock * tile;
+        const int64_t fine = d->S / even;
+        if (gqa_mfma && g_split_override == 0 && chunk % (kWavesPerBlock * tile) != 0 && d->S % even == 0 &&
+            fine > nsplit && fine * 3 <= nsplit * 4 && fine <= kMaxPartialsPerHead / k &&
+            (units * fine) % 256 == 0) {
+            nsplit = fine;
+            chunk = even;
+        }
     };
     split_for(resident);
     size_t stage = (size_t)gb * chunk * sizeof(float);      // the block's raw scores, staged in LDS
