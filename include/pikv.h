@@ -212,7 +212,8 @@ int pikv_append(const pikv_desc *desc, const void *K_new, const void *V_new,
                 const int32_t *reuse_cnt, int32_t max_evict, void *const *K_shards,
                 void *const *V_shards, float *utility, int32_t *n_valid, void *stream);
 
-/* One iteration of Algorithm 1's loop in three launches instead of six (per-token routing
+/* One iteration of Algorithm 1's loop in three launches instead of six (four from 256 query
+ * rows per sequence on, where the merge and the utility update are faster apart; per-token routing
  * only): route q -> for every selected shard that is full evict its minimum-utility entry
  * (order: utility ascending, then higher slot first) -> insert the new token's rows there
  * (or at slot n_valid if the shard has room) -> attention over the selected shards (new

@@ -225,6 +225,12 @@ __global__ __launch_bounds__(kRouteThreads) void step_pre(PreParams p) {
 // the partials - a few KiB from L2 and the same arithmetic, hence the same bits - while its
 // score loads are already in flight.
 constexpr int kPostMaxShards = 2048;   // Hq * k
+// From this many query rows per sequence on (a multi-query step of 8 drafts x 32 heads) the merge
+// and the utility update run as two launches: every utility block of the single launch re-derives
+// the statistics of all Hq * k (head, shard) pairs from their partials - 128 KiB per block at 256
+// rows and 4 shards - while the stand-alone utility kernel reads the merge's (shift, coef) pairs.
+// Measured, 256 rows: 18.2 us in one launch, 5.3 + 9.4 us in two; 128 rows: 11.4 us either way.
+constexpr int kPostSplitRows = 256;
 constexpr int kPostPrefetchHeads = 8;  // score loads each thread issues before the statistics
 constexpr int kPostMaxTiles = 8;       // slot tiles one utility block walks through
 constexpr int kPostStatsAhead = 4;     // many-pairs shape: passes of statistics whose loads are in flight
@@ -565,7 +571,7 @@ static int decode_step(const pikv_desc *desc, const void *q, const void *W_r, co
                               combine, scale, y, row_max, row_norm, scores, slot_coef, workspace,
                               workspace_bytes, stream, &plan, &c);
     if (lrc != PIKV_OK) return lrc;
-    if ((int64_t)desc->Hq * k > kPostMaxShards) {
+    if ((int64_t)desc->Hq * k > kPostMaxShards || desc->Hq >= kPostSplitRows) {
         // too many partials to restage per utility block: separate merge and utility launches
         lrc = pikv_sharded_attn_merge(desc, &c, stream);
         if (lrc != PIKV_OK) return lrc;

@@ -17,8 +17,15 @@
 namespace pikv {
 namespace {
 
-constexpr int kUtilThreads = 256;   // one slot per thread: a wave reads 256 contiguous bytes
-constexpr int kUtilTile = kUtilThreads;
+constexpr int kUtilThreads = 256;
+// Two block shapes.  One slot per thread (256 slots per block, a wave reads 256 contiguous
+// bytes, every thread walks through all the heads): few heads per entry.  Or one (slot, quarter
+// of the heads) per thread (64 slots per block, one wave per quarter): with hundreds of query
+// rows per entry - a multi-query step - the walk through the heads is four times shorter, four
+// times as many blocks share the score bytes, and each thread keeps 8 loads in flight.  The
+// heads are summed in the same four ascending groups joined as (g0 + g1) + (g2 + g3) either way.
+constexpr int kUtilManyHeads = 128;     // from this many query rows per sequence on: the second shape
+constexpr int kUtilBatch = 8;           // loads in flight per thread in the second shape
 
 struct UtilParams {
     const float *scores;
@@ -36,8 +43,9 @@ struct UtilParams {
     int now;
 };
 
-template <bool TRACK>
+template <bool TRACK, bool SPREAD>
 __global__ __launch_bounds__(kUtilThreads) void utility_kernel(UtilParams p) {
+    constexpr int kUtilTile = SPREAD ? kUtilThreads / 4 : kUtilThreads;
     int bid = blockIdx.x;
     const int tile = bid % p.tiles;
     bid /= p.tiles;
@@ -80,12 +88,45 @@ __global__ __launch_bounds__(kUtilThreads) void utility_kernel(UtilParams p) {
     }
     __syncthreads();
 
+    const int gsize = (nact + 3) / 4;
+    if constexpr (SPREAD) {
+        // thread = (slot, group): wave g walks through group g's heads, kUtilBatch loads at a time
+        // from clamped addresses (no load under a lane-dependent condition), the sums meet in LDS
+        __shared__ float part_s[4][kUtilTile];
+        const int slot = tid & (kUtilTile - 1), g = tid / kUtilTile;
+        const int i = i0 + slot, ic = min(i, n - 1);
+        const int lo = g * gsize, hi = min(nact, lo + gsize);
+        float a = 0.0f;
+        for (int t0 = lo; t0 < hi; t0 += kUtilBatch) {
+            float sc[kUtilBatch];
+#pragma unroll
+            for (int u = 0; u < kUtilBatch; ++u)
+                sc[u] = p.scores[(int64_t)head_off[min(t0 + u, hi - 1)] * p.S + ic];
+            const int left = __builtin_amdgcn_readfirstlane(hi - t0);   // the group is the wave's
+#pragma unroll
+            for (int u = 0; u < kUtilBatch; ++u) {
+                const int t = min(t0 + u, hi - 1);
+                const float with = fmaf(head_coef[t], __expf(sc[u] - head_shift[t]), a);
+                a = u < left ? with : a;
+            }
+        }
+        part_s[g][slot] = a;
+        __syncthreads();
+        if (g != 0 || i >= n) return;
+        const float mass = (part_s[0][slot] + part_s[1][slot]) + (part_s[2][slot] + part_s[3][slot]);
+        const int64_t at = ((int64_t)b * p.E + e) * p.S + i;
+        if (!TRACK || p.utility) p.utility[at] = fmaf(p.decay, p.utility[at], mass);
+        if (TRACK && mass > p.threshold) {
+            p.last_access[at] = p.now;
+            p.freq[at] += 1;
+        }
+        return;
+    }
     const int i = i0 + tid;
     if (i >= n) return;
     // the active heads are cut into 4 consecutive groups, each summed in ascending order, the
     // groups joined as (g0 + g1) + (g2 + g3): the fused step kernel spreads the groups over
     // threads and must reproduce these bits
-    const int gsize = (nact + 3) / 4;
     float part[4];
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
@@ -130,7 +171,9 @@ int launch_utility(const pikv_desc *desc, const float *scores, const float *slot
     p.S = desc->S;
     p.k = k;
     p.rr = desc->route_rows_per_seq;
-    p.tiles = (desc->S + kUtilTile - 1) / kUtilTile;
+    const bool spread = desc->Hq >= kUtilManyHeads;
+    const int tile_slots = spread ? kUtilThreads / 4 : kUtilThreads;
+    p.tiles = (desc->S + tile_slots - 1) / tile_slots;
     p.decay = decay;
     p.last_access = last_access;
     p.freq = freq;
@@ -138,12 +181,12 @@ int launch_utility(const pikv_desc *desc, const float *scores, const float *slot
     p.now = now;
     const int64_t blocks = (int64_t)desc->B * desc->E * p.tiles;
     if (blocks > 0x7fffffff) return PIKV_ERR_UNSUPPORTED;
-    if (track)
-        hipLaunchKernelGGL(utility_kernel<true>, dim3((unsigned)blocks), dim3(kUtilThreads), 0,
-                           as_stream(stream), p);
-    else
-        hipLaunchKernelGGL(utility_kernel<false>, dim3((unsigned)blocks), dim3(kUtilThreads), 0,
-                           as_stream(stream), p);
+    const dim3 grid((unsigned)blocks), block(kUtilThreads);
+    hipStream_t st = as_stream(stream);
+    if (track && spread) hipLaunchKernelGGL((utility_kernel<true, true>), grid, block, 0, st, p);
+    else if (track) hipLaunchKernelGGL((utility_kernel<true, false>), grid, block, 0, st, p);
+    else if (spread) hipLaunchKernelGGL((utility_kernel<false, true>), grid, block, 0, st, p);
+    else hipLaunchKernelGGL((utility_kernel<false, false>), grid, block, 0, st, p);
     return launch_status();
 }
 
