@@ -128,6 +128,10 @@ ATTN_CASES = {
     "long_shard_g1_40k": (dict(B=1, Hq=2, Hkv=2, D=64, E=2, S=40000, k=1, dtype="bf16"), "full"),
     "hq256": (dict(B=1, Hq=256, Hkv=32, D=64, E=2, S=64, k=2, dtype="bf16"), "ragged"),
     "e64_k64": (dict(B=1, Hq=2, Hkv=2, D=32, E=64, S=40, k=64, dtype="bf16"), "ragged"),
+    # the utility kernel's shape for hundreds of query rows: heads chosen per head (an expert's
+    # active heads differ in number, down to none), slot tiles with a ragged end
+    "hq160_perhead": (dict(B=2, Hq=160, Hkv=4, D=32, E=3, S=150, k=2, dtype="bf16", per_head_routing=True), "ragged"),
+    "hq128_k1": (dict(B=1, Hq=128, Hkv=2, D=128, E=5, S=333, k=1, dtype="bf16"), "ragged"),
 }
 
 
