@@ -200,6 +200,50 @@ def attn_kernel_name(geo):
     return "attn_partial<%s, %d, %d>" % ("pikv::bf16" if geo.dtype == "bf16" else "float", geo.width, gb)
 
 
+def read_ceiling(pk, torch, geo, layers, stream):
+    """What a pass that only READS a step's K/V bytes reaches here: the library's measurement
+    kernel (pikv_stream_read_probe: the attention pass's load shape, no arithmetic) over k shards'
+    K and V buffers of every sequence, one launch per layer instance in the same rotation as the
+    steps, replayed as a HIP graph.  Context for the roofline fraction, not part of `value`."""
+    g = geo
+    dev = layers[0].t["K"].device
+    elt = 4 if g.dtype == "f32" else 2
+    bytes_each = g.Hkv * g.S * g.width * elt
+    n = g.B * g.k * 2
+    parts = max(1, min(1024 // max(n, 1), bytes_each // 65536))
+    tables, outs = [], []
+    for L in layers:
+        K, V = L.t["K"], L.t["V"]                      # [B, E, Hkv, S, w]
+        bufs = [T[b, e] for T in (K, V) for b in range(g.B) for e in range(g.k)]
+        tables.append(pk.shard_table(bufs))
+        outs.append(torch.zeros(n * parts, device=dev, dtype=torch.int32))
+    def launch(i):
+        pk.pikv_stream_read_probe(tables[i], n, bytes_each, parts, outs[i], stream=stream.cuda_stream)
+    with torch.cuda.stream(stream):
+        for i in range(len(layers)):
+            launch(i)
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=stream):
+            for i in range(len(layers)):
+                launch(i)
+        graph.replay()
+    stream.synchronize()
+    launches = max(512, len(layers))
+    replays = -(-launches // len(layers))
+    t0 = time.perf_counter()
+    with torch.cuda.stream(stream):
+        for _ in range(replays):
+            graph.replay()
+    stream.synchronize()
+    per_launch = (time.perf_counter() - t0) / (replays * len(layers))
+    nbytes = n * bytes_each
+    return {"GBps": nbytes / per_launch / 1e9, "frac_of_peak": nbytes / per_launch / 1e9 / HBM_PEAK_GBS,
+            "us_per_launch": per_launch * 1e6, "bytes_per_launch": nbytes, "blocks": n * parts,
+            "launches_timed": replays * len(layers),
+            "what": "pikv_stream_read_probe: K and V buffers of k shards per sequence read once with the "
+                    "attention pass's load shape and no arithmetic, one launch per layer instance, graph replay"}
+
+
 def profile_summary(config, kernel):
     """Average duration (ns) of `kernel` in the committed rocprofv3 kernel-trace summary of this
     workload (profiles/<config>_kernel_stats.txt: a table `name calls avg_ns min_ns max_ns pct`)."""
@@ -463,6 +507,7 @@ def measure(args, config, steps, warmup, with_cpu, probe_steps, quiet=False):
                               "timed_with": "HIP event pair recorded by the library on the launch stream "
                                             "around the kernel, in eager steps of this run"}},
     }
+    out["roofline"]["read_only_probe"] = read_ceiling(pk, torch, geo, layers, run.main)
     if with_cpu:
         n_cpu = args.cpu_steps if args.cpu_steps > 0 else min(n_layers, 8)
         per_step, n_done, secs = cpu_baseline(torch, wl, layers, n_cpu)

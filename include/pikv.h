@@ -384,6 +384,18 @@ void pikv_set_attn_split(int32_t nsplit);
  * would replay with the graph.                                                             */
 void pikv_set_profile_events(void *start_event, void *stop_event);
 
+/* Measurement hook, no part of the method: reads n device buffers of bytes_each bytes once,
+ * each cut into `parts` spans (one block of 4 waves per span), with the attention pass's load
+ * shape (1 KiB of consecutive bytes per wave load, non-temporal, 16 loads of a wave in flight)
+ * and no arithmetic, and writes the xor of each span's 32-bit words to out [n * parts] (buffer-major;
+ * span = bytes_each / parts rounded up to 4096 bytes, the last one shorter).  bench.py times
+ * it over the same K/V bytes as a step to report what a pass that only has to read them reaches
+ * on the machine at hand.  bufs: device array of n device pointers, 16-byte aligned buffers.
+ * Errors: INVALID for null pointers, n < 1, parts < 1, bytes_each not a positive multiple of
+ * 16, or so many parts that one would be empty.                                              */
+int pikv_stream_read_probe(const void *const *bufs, int32_t n, size_t bytes_each, int32_t parts,
+                           uint32_t *out, void *stream);
+
 /* Static description of a status code (host string, never NULL).                          */
 const char *pikv_strerror(int status);
 

@@ -20,6 +20,7 @@ POLICY_H2O, POLICY_SL, POLICY_LRU, POLICY_LRU_PLUS = 0, 1, 2, 3
 
 EXPORTS = ("pikv_route", "pikv_attn_workspace_bytes", "pikv_sharded_attn", "pikv_update_utility",
            "pikv_evict", "pikv_append", "pikv_strerror", "pikv_version", "pikv_set_attn_split", "pikv_decode_step",
+           "pikv_stream_read_probe",
            "pikv_set_profile_events", "pikv_router_penalty", "pikv_compress", "pikv_policy_stamp",
            "pikv_update_utility_tracked", "pikv_policy_utility", "pikv_policy_compact", "pikv_decode_step_policy", "pikv_route_round_robin",
            "pikv_sharded_attn_noalloc")
@@ -99,6 +100,8 @@ def load_library():
     lib.pikv_decode_step.restype = C.c_int
     lib.pikv_decode_step_policy.argtypes = list(lib.pikv_decode_step.argtypes) + [vp, vp]
     lib.pikv_decode_step_policy.restype = C.c_int
+    lib.pikv_stream_read_probe.argtypes = [vp, i32, C.c_size_t, i32, vp, vp]
+    lib.pikv_stream_read_probe.restype = C.c_int
     lib.pikv_router_penalty.argtypes = [i32, vp, i32, i32, i32, vp, vp, f32, vp, vp]
     lib.pikv_router_penalty.restype = C.c_int
     lib.pikv_compress.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp]
@@ -257,6 +260,11 @@ def pikv_decode_step(desc, q, W_r, bias, K_new, V_new, K_shards, V_shards, U_K, 
         _p(topk_idx), _p(gates), _p(evicted_idx), _p(evicted_cnt), _p(y), _p(row_max), _p(row_norm),
         _p(scores), _p(slot_coef), _p(workspace), ws_bytes, _stream(stream))
     _check(st, "pikv_decode_step")
+
+
+def pikv_stream_read_probe(bufs, n, bytes_each, parts, out, stream=None):
+    st = load_library().pikv_stream_read_probe(_p(bufs), n, bytes_each, parts, _p(out), _stream(stream))
+    _check(st, "pikv_stream_read_probe")
 
 
 def pikv_router_penalty(mode, topk_idx, rows, k, E, load, miss, coef, bias, stream=None):

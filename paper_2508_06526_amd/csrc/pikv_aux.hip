@@ -29,6 +29,43 @@ __global__ __launch_bounds__(256) void route_round_robin(int n, int E, int k, lo
     gates[i] = 1.0f / (float)k;
 }
 
+// Measurement kernel: reads `parts` spans of each of n buffers once, the way the attention pass
+// reads K/V rows (4 waves per block, a wave load = 1 KiB of consecutive bytes, non-temporal,
+// 16 loads of a wave in flight), folds the words (xor) and writes one per block.  No arithmetic
+// besides the fold: what it reaches is the most any pass that has to read these bytes can.
+__global__ __launch_bounds__(256) void stream_read_probe(const char *const *bufs, size_t bytes_each, size_t span,
+                                                         int parts, uint32_t *out) {
+    const int buf = blockIdx.x / parts, part = blockIdx.x - buf * parts;
+    const char *base = bufs[buf];
+    const size_t lo = (size_t)part * span, hi = lo + span < bytes_each ? lo + span : bytes_each;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    uint4 acc = make_uint4(0, 0, 0, 0);
+    constexpr size_t kWaveBytes = 16 * 1024;           // per wave and iteration: 16 loads of 1 KiB
+    for (size_t at = lo + (size_t)wave * kWaveBytes; at < hi; at += 4 * kWaveBytes) {
+        uint4 v[16];
+#pragma unroll
+        for (int t = 0; t < 16; ++t) {
+            const size_t a = at + (size_t)t * 1024 + (size_t)lane * 16;
+            const bool in = a + 16 <= hi;
+            v[t] = load16_stream(base + (in ? a : hi - 16));   // clamped onto the span's last 16 bytes,
+            if (!in) v[t] = make_uint4(0, 0, 0, 0);            // which then do not count
+        }
+#pragma unroll
+        for (int t = 0; t < 16; ++t) {
+            acc.x ^= v[t].x;
+            acc.y ^= v[t].y;
+            acc.z ^= v[t].z;
+            acc.w ^= v[t].w;
+        }
+    }
+    uint32_t w = acc.x ^ acc.y ^ acc.z ^ acc.w;
+    for (int off = 1; off < 64; off <<= 1) w ^= __shfl_xor(w, off, 64);
+    __shared__ uint32_t ws[4];
+    if (lane == 0) ws[wave] = w;
+    __syncthreads();
+    if (threadIdx.x == 0) out[blockIdx.x] = ws[0] ^ ws[1] ^ ws[2] ^ ws[3];
+}
+
 typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 typedef float f32x2_t __attribute__((ext_vector_type(2)));
 
@@ -140,3 +177,15 @@ extern "C" int pikv_route_round_robin(int32_t rows, int32_t E, int32_t k, int64_
     return launch_status();
 }
 
+
+extern "C" int pikv_stream_read_probe(const void *const *bufs, int32_t n, size_t bytes_each, int32_t parts,
+                                      uint32_t *out, void *stream) {
+    if (!bufs || !out || n < 1 || parts < 1 || bytes_each < 16 || bytes_each % 16 != 0) return PIKV_ERR_INVALID;
+    if ((int64_t)n * parts > 0x7fffffff) return PIKV_ERR_INVALID;
+    size_t span = (bytes_each + parts - 1) / parts;
+    span = (span + 4095) / 4096 * 4096;
+    if (span * (size_t)(parts - 1) >= bytes_each) return PIKV_ERR_INVALID;      // a part would be empty
+    hipLaunchKernelGGL(stream_read_probe, dim3((unsigned)(n * parts)), dim3(256), 0, as_stream(stream),
+                       reinterpret_cast<const char *const *>(bufs), bytes_each, span, parts, out);
+    return launch_status();
+}

@@ -1102,3 +1102,22 @@ def test_attention_with_very_peaked_scores(spec):
         u = t2n(dc.utility)
         assert np.isfinite(u).all()
         np.testing.assert_allclose(u, u_ref, rtol=1e-4 + 8 * ulp, atol=1e-9)
+
+
+def test_stream_read_probe_folds_every_word_once():
+    """The measurement kernel behind bench.py's read-ceiling figure reads every byte it is given
+    exactly once: its per-span xor of 32-bit words equals numpy's, for spans with ragged ends."""
+    rng = np.random.default_rng(3)
+    for n, words, parts in ((3, 70000, 5), (1, 4, 1), (2, 1024 * 37 + 12, 7), (4, 16384 * 4, 4)):
+        host = rng.integers(0, 2 ** 32, size=(n, words), dtype=np.uint64).astype(np.uint32)
+        bufs = [torch.from_numpy(host[i].view(np.int32).copy()).to(DEV) for i in range(n)]
+        table = pk.shard_table(bufs)
+        out = torch.zeros(n * parts, device=DEV, dtype=torch.int32)
+        pk.pikv_stream_read_probe(table, n, words * 4, parts, out)
+        got = t2n(out).view(np.uint32).reshape(n, parts)
+        span = -(-(words * 4) // parts)
+        span = -(-span // 4096) * 4096 // 4
+        for i in range(n):
+            for pt in range(parts):
+                want = np.bitwise_xor.reduce(host[i, pt * span:(pt + 1) * span]) if pt * span < words else 0
+                assert got[i, pt] == want, (n, words, parts, i, pt)
