@@ -36,4 +36,4 @@ extern "C" const char *pikv_strerror(int status) {
     }
 }
 
-extern "C" int pikv_version(void) { return 300; }
+extern "C" int pikv_version(void) { return 301; }
