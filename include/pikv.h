@@ -227,8 +227,9 @@ int pikv_append(const pikv_desc *desc, const void *K_new, const void *V_new,
  * slot_coef are required.  Errors: as for the separate calls, every one of them detected
  * before the first launch (a rejected call leaves the cache untouched); INVALID while a
  * profiling event pair is installed (pikv_set_profile_events) and `stream` is being captured
- * into a graph; UNSUPPORTED when route_rows_per_seq != 1 or a row of W_r is not a power-of-two
- * number of aligned 16-byte chunks (E * sizeof(element) in {16,32,64,128,256}).            */
+ * into a graph; UNSUPPORTED when route_rows_per_seq != 1.  (Rows of W_r that are a power-of-two
+ * number of aligned 16-byte chunks - E * sizeof(element) in {16,32,64,128,256} - take the fast
+ * form of the router, any other E the generic one, as in pikv_route.)                       */
 int pikv_decode_step(const pikv_desc *desc, const void *q, const void *W_r, const float *bias,
                      const void *K_new, const void *V_new, void *const *K_shards,
                      void *const *V_shards, const void *U_K, const void *U_V, int32_t *n_valid,

@@ -26,35 +26,10 @@ __global__ __launch_bounds__(kRouteThreads) void route_kernel(const T *x, const 
                                                               float *gates, float *probs) {
     const int row = blockIdx.x;
     const int tid = threadIdx.x;
-    const int e = tid % EP;           // EP = E rounded up to a power of two
-    const int js = tid / EP;
-    const int JS = kRouteThreads / EP;
-
     __shared__ float red[kRouteThreads];
-    __shared__ float logit[64];
-
-    float acc = 0.0f;
-    if (e < E) {
-        const T *xr = x + (int64_t)row * d_r;
-        for (int j = js; j < d_r; j += JS)
-            acc = fmaf(load_scalar<T>(xr, j), load_scalar<T>(W_r, (int64_t)j * E + e), acc);
-    }
-    red[tid] = acc;
-    __syncthreads();
-    for (int half = JS >> 1; half >= 1; half >>= 1) {
-        if (js < half) red[tid] += red[tid + half * EP];
-        __syncthreads();
-    }
-    if (tid < 64) {
-        float v = -INFINITY;
-        if (tid < E) {
-            v = red[tid] + (bias ? bias[tid] : 0.0f);
-            if (v != v) v = -INFINITY;          // a NaN logit ranks last
-        }
-        logit[tid] = v;
-    }
-    __syncthreads();
-    if (tid < 64) select_topk(logit[tid], tid, row, E, k, topk_idx, gates, probs);
+    const float bias_e = route_bias_of_lane(bias, E, tid & (kWave - 1));
+    route_logits_generic<T>(x + (int64_t)row * d_r, W_r, d_r, E, EP, red);   // EP = E rounded up to a power of two
+    if (tid < 64) select_topk(route_logit_generic_of_lane(red, bias_e, E, tid), tid, row, E, k, topk_idx, gates, probs);
 }
 
 // Fast path: a row of W_r is a whole number (1, 2, 4, 8 or 16) of 16-byte chunks; see

@@ -144,6 +144,40 @@ __device__ __forceinline__ void route_logits_vec(const T *xr, const T *W_r, cons
     __syncthreads();
 }
 
+// Logits of one routed row for any E <= 64 and any alignment (scalar element loads): thread =
+// (expert e = tid % EP, row slice tid / EP) with EP = E rounded up to a power of two, the slices
+// joined by a fixed-order LDS tree.  Ends, after a block barrier, with expert e's sum in red[e];
+// `red` holds kRouteThreads floats.
+template <typename T>
+__device__ __forceinline__ void route_logits_generic(const T *xr, const T *W_r, int d_r, int E, int EP,
+                                                     float *red) {
+    const int tid = threadIdx.x;
+    const int e = tid % EP;
+    const int js = tid / EP;
+    const int JS = kRouteThreads / EP;
+    float acc = 0.0f;
+    if (e < E) {
+        for (int j = js; j < d_r; j += JS)
+            acc = fmaf(load_scalar<T>(xr, j), load_scalar<T>(W_r, (int64_t)j * E + e), acc);
+    }
+    red[tid] = acc;
+    __syncthreads();
+    for (int half = JS >> 1; half >= 1; half >>= 1) {
+        if (js < half) red[tid] += red[tid + half * EP];
+        __syncthreads();
+    }
+}
+// Expert `lane`'s logit after route_logits_generic (experts >= E hold -inf; a NaN logit ranks last).
+__device__ __forceinline__ float route_logit_generic_of_lane(const float *red, float bias_of_lane, int E,
+                                                             int lane) {
+    float v = -INFINITY;
+    if (lane < E) {
+        v = red[lane] + bias_of_lane;
+        if (v != v) v = -INFINITY;
+    }
+    return v;
+}
+
 // The additive term of expert `lane` (0 without a bias or past the last expert).  Callers read
 // it before the weights: it depends on nothing, and a load issued after the block barrier
 // would put a whole trip to memory between the logits and the selection.

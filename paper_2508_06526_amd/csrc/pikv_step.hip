@@ -45,6 +45,7 @@ struct PreParams {
     int64_t stride_h_bytes, stride_s_bytes;
     int64_t x_stride;    // elements between the routed vectors of consecutive sequences (>= d_r)
     int d_r, E, cpr, k, S, Hkv, row_chunks, do_insert;
+    int EP;              // 0: rows of W_r are aligned 16-byte chunks (cpr of them); else E rounded up to a power of two
     int use_policy;      // the entry to evict is chosen by pol (Table 3) instead of the utility
     PolicyView pol;      // its arrays, when given, are also stamped for the new entry
 };
@@ -94,8 +95,12 @@ __global__ __launch_bounds__(kRouteThreads) void step_pre(PreParams p) {
         vnew = load16(static_cast<const char *>(p.V_new) + ((int64_t)b * new_chunks + tid) * 16);
     }
 
-    route_logits_vec<T>(static_cast<const T *>(p.x) + (int64_t)b * p.x_stride,
-                        static_cast<const T *>(p.W_r), p.bias, p.d_r, p.E, p.cpr, red);
+    if (p.EP == 0)
+        route_logits_vec<T>(static_cast<const T *>(p.x) + (int64_t)b * p.x_stride,
+                            static_cast<const T *>(p.W_r), p.bias, p.d_r, p.E, p.cpr, red);
+    else      // any E, any alignment: the stand-alone router's generic form, same bits
+        route_logits_generic<T>(static_cast<const T *>(p.x) + (int64_t)b * p.x_stride,
+                                static_cast<const T *>(p.W_r), p.d_r, p.E, p.EP, &red[0][0]);
     // The first wave ranks the experts and tells the others which shard is the block's (one LDS
     // word and a barrier): sixteen waves doing it side by side, four to a SIMD, take twice as
     // long as one wave alone plus the barrier.  The ranks come first - the shard to scan hangs
@@ -105,7 +110,8 @@ __global__ __launch_bounds__(kRouteThreads) void step_pre(PreParams p) {
     float logit = 0.0f;
     int rank = 64;
     if (wave == 0) {
-        logit = route_logit_of_lane(red, bias_e, p.E, lane);
+        logit = p.EP == 0 ? route_logit_of_lane(red, bias_e, p.E, lane)
+                          : route_logit_generic_of_lane(&red[0][0], bias_e, p.E, lane);
         rank = route_rank(logit, lane, p.E);
         const uint64_t owner = __ballot(rank == j);      // taken with every lane of the wave active
         if (lane == 0) block_expert = __builtin_ctzll(owner);
@@ -511,8 +517,11 @@ static int decode_step(const pikv_desc *desc, const void *q, const void *W_r, co
     if (!(decay >= 0.0f) || decay > 3.0e38f) return PIKV_ERR_INVALID;
     if (combine != PIKV_COMBINE_LSE && combine != PIKV_COMBINE_LOCAL) return PIKV_ERR_INVALID;
     if (desc->route_rows_per_seq != 1) return PIKV_ERR_UNSUPPORTED;
-    int cpr = 0;
-    if (!route_vec_ok(W_r, desc->E, desc->dtype, &cpr)) return PIKV_ERR_UNSUPPORTED;
+    int cpr = 0, EP = 0;
+    if (!route_vec_ok(W_r, desc->E, desc->dtype, &cpr)) {
+        EP = 1;
+        while (EP < desc->E) EP <<= 1;
+    }
     // the attention pass's own checks come before the first launch as well: a rejected call
     // leaves the cache (rows, utilities, entry counts, policy arrays) exactly as it was
     AttnPlan checked;
@@ -552,6 +561,7 @@ static int decode_step(const pikv_desc *desc, const void *q, const void *W_r, co
     p.x_stride = (int64_t)desc->Hq * desc->D;
     p.E = desc->E;
     p.cpr = cpr;
+    p.EP = EP;
     p.k = k;
     p.S = desc->S;
     p.Hkv = desc->Hkv;

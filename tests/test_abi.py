@@ -131,7 +131,7 @@ def test_host_side_argument_errors_of_the_widened_entry_points(lib):
     assert step(scale=float("nan")) == INVALID
     assert step(desc=pk.make_desc(2, 4, 4, 64, 8, 256, rank=32, dtype=1)) == INVALID   # codes without decoders
     assert step(desc=pk.make_desc(2, 4, 4, 64, 8, 256, dtype=1, route_rows_per_seq=4)) == UNSUPPORTED
-    assert step(desc=pk.make_desc(2, 4, 4, 64, 4, 256, dtype=1)) == UNSUPPORTED   # W_r rows of 8 bytes
+    assert step(desc=pk.make_desc(0, 4, 4, 64, 4, 256, dtype=1)) == 0   # W_r rows of 8 bytes: accepted (nothing to launch)
     assert step(desc=pk.make_desc(0, 4, 4, 64, 8, 256, dtype=1)) == 0
 
     rr = lib.pikv_route_round_robin

@@ -547,7 +547,9 @@ def test_streaming_steps_route_evict_append_attend_update():
     dict(B=2, Hq=8, Hkv=2, D=128, E=16, S=200, k=4, dtype="bf16"),
     dict(B=3, Hq=4, Hkv=4, D=128, E=8, S=64, k=5, dtype="bf16", rank=32),
     dict(B=2, Hq=4, Hkv=2, D=64, E=4, S=50, k=2, dtype="f32"),
-], ids=["g1", "gqa4", "rank32_k5", "f32"])
+    dict(B=2, Hq=8, Hkv=2, D=128, E=12, S=120, k=3, dtype="bf16"),       # W_r rows of 24 bytes: generic router
+    dict(B=1, Hq=4, Hkv=4, D=64, E=2, S=70, k=2, dtype="bf16"),          # ... of 4 bytes
+], ids=["g1", "gqa4", "rank32_k5", "f32", "e12", "e2"])
 def test_fused_decode_step_equals_separate_calls_and_oracle(spec):
     """pikv_decode_step (3 launches) vs the five separate calls (bit-identical state) vs oracle."""
     from gpu_harness import dev_storage
@@ -651,7 +653,9 @@ def test_fused_step_is_bit_identical_to_separate_calls_on_random_geometries(seed
     from gpu_harness import dev_storage
     rng = np.random.default_rng(2000 + seed)
     dtype = str(rng.choice(["bf16", "bf16", "f32"]))
-    E = int(rng.choice([8, 16, 32] if dtype == "bf16" else [4, 8, 16]))
+    # (expert counts whose W_r rows are whole aligned 16-byte chunks, and others: the router's
+    # generic form inside the step)
+    E = int(rng.choice([8, 16, 32, 5, 12, 24, 33] if dtype == "bf16" else [4, 8, 16, 3, 6, 13]))
     D = int(rng.choice([32, 64, 128]))
     rank = int(rng.choice([0, 0, 16, 32]))
     if rank >= D:
