@@ -166,6 +166,39 @@ __global__ __launch_bounds__(kRouteThreads) void step_pre(PreParams p) {
         publish();
         for (int i0 = tid * 4; i0 < p.S; i0 += kRouteThreads * 4 * kScanLoads) {
             if (i0 != tid * 4) request(i0);
+            // The block's 16 waves share 4 vector units, so this phase costs its instruction
+            // count times 16 cycles.  Where no value of the wave has its sign bit set (utilities
+            // are sums of probabilities), the keys' order is the order of the raw bits and the
+            // thread's slots ascend: one compare and two selects per value ("<=": of equal
+            // values the higher slot goes) instead of building and comparing 64-bit composites
+            // - the same minimum.  (Loads past the shard's end hold zeros and are left out; the
+            // thread's first load is always inside.)
+            uint32_t signs = 0;
+#pragma unroll
+            for (int t = 0; t < kScanLoads; ++t)
+                signs |= (__float_as_uint(v[t].x) | __float_as_uint(v[t].y)) |
+                         (__float_as_uint(v[t].z) | __float_as_uint(v[t].w));
+            if (!__any((int)signs < 0)) {
+                uint32_t low = 0xffffffffu;
+                int at = 0;              // offset of the lowest value's slot from i0
+                auto take = [&](bool inside, float value, int offset) {
+                    const uint32_t bits = __float_as_uint(value);
+                    const bool le = inside && bits <= low;
+                    low = le ? bits : low;
+                    at = le ? offset : at;
+                };
+#pragma unroll
+                for (int t = 0; t < kScanLoads; ++t) {
+                    const bool inside = i0 + t * kRouteThreads * 4 < p.S;
+                    take(inside, v[t].x, t * kRouteThreads * 4);
+                    take(inside, v[t].y, t * kRouteThreads * 4 + 1);
+                    take(inside, v[t].z, t * kRouteThreads * 4 + 2);
+                    take(inside, v[t].w, t * kRouteThreads * 4 + 3);
+                }
+                const uint64_t c0 = evict_composite(__uint_as_float(low), i0 + at);
+                best = c0 < best ? c0 : best;
+                continue;
+            }
 #pragma unroll
             for (int t = 0; t < kScanLoads; ++t) {
                 const int i = i0 + t * kRouteThreads * 4;

@@ -549,7 +549,10 @@ def test_streaming_steps_route_evict_append_attend_update():
     dict(B=2, Hq=4, Hkv=2, D=64, E=4, S=50, k=2, dtype="f32"),
     dict(B=2, Hq=8, Hkv=2, D=128, E=12, S=120, k=3, dtype="bf16"),       # W_r rows of 24 bytes: generic router
     dict(B=1, Hq=4, Hkv=4, D=64, E=2, S=70, k=2, dtype="bf16"),          # ... of 4 bytes
-], ids=["g1", "gqa4", "rank32_k5", "f32", "e12", "e2"])
+    # many sequences: more blocks in the step's first kernel than the GPU has compute units
+    dict(B=36, Hq=4, Hkv=4, D=64, E=8, S=40, k=2, dtype="bf16"),
+    dict(B=90, Hq=2, Hkv=2, D=32, E=3, S=24, k=2, dtype="f32"),
+], ids=["g1", "gqa4", "rank32_k5", "f32", "e12", "e2", "b36_e8", "b90_e3_f32"])
 def test_fused_decode_step_equals_separate_calls_and_oracle(spec):
     """pikv_decode_step (3 launches) vs the five separate calls (bit-identical state) vs oracle."""
     from gpu_harness import dev_storage
@@ -644,6 +647,49 @@ def test_rejected_fused_step_leaves_the_cache_untouched(bad):
         t = getattr(d, n)
         np.testing.assert_array_equal(t2n(t.view(torch.int16) if t.dtype == torch.bfloat16 else t), ref, err_msg=n)
     assert (t2n(ec) == -5).all() and (t2n(ei) == -1).all()
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("S", [8, 260, 4096 + 8, 2 * 8192 + 4], ids=lambda S: "S%d" % S)
+def test_fused_step_evicts_the_oracles_victim_on_ties_zeros_and_negative_utilities(S):
+    """The fused step's scan against the eviction rule on values chosen to separate its cases: every
+    shard full; per shard all utilities equal, zeros of both signs, duplicated minima at the ends of
+    the threads' ranges, negative values and infinities, ordinary positive ones (S: less than one
+    load per thread, a partial pass, one pass and a bit, two passes and a bit)."""
+    from gpu_harness import dev_storage
+    g = wl.Geometry(B=2, Hq=2, Hkv=2, D=32, E=8, S=S, k=8, dtype="bf16")      # every shard is visited
+    case = wl.make_host_case(g, seed=77, utility0="exp")
+    rng = np.random.default_rng(S)
+    u = np.abs(rng.standard_normal((g.B, g.E, S))).astype(np.float32) + 0.5
+    u[0, 0, :] = 0.25                                  # all equal: the highest slot goes
+    u[0, 1, ::3] = 0.0
+    u[0, 1, 1::6] = -0.0                               # a sign bit, and equal to +0 in the order
+    lo = np.float32(0.125)
+    u[0, 2, [0, S // 2, S - 1]] = lo                   # the minimum three times
+    u[0, 3, :] = rng.standard_normal(S).astype(np.float32)         # negative values
+    u[0, 4, S // 3] = -np.inf
+    u[0, 5, :] = np.inf
+    u[0, 5, S // 2] = 3.0e38
+    u[0, 6, [3, 4 % S]] = np.float32(1e-45)            # denormals, adjacent slots of two loads
+    u[1, 0, S - 1] = lo
+    u[1, 1, 0] = lo
+    u[1, 2, :] = 0.0                                   # all zero, as after a run of inserts
+    u[1, 3, S - 4:] = lo                               # the last load, all four
+    case.utility[:] = u
+    case.n_valid[:] = S
+    dc = DeviceCase(case)
+    ei = torch.full((g.B, g.E, 1), -1, device=DEV, dtype=torch.int32)
+    ec = torch.full((g.B, g.E), -5, device=DEV, dtype=torch.int32)
+    kn, vn = wl.draw_new_kv(g, 5)
+    pk.pikv_decode_step(dc.desc, dc.q, dc.W_r, dc.bias, dev_storage(kn, g.dtype), dev_storage(vn, g.dtype),
+                        dc.K_tab, dc.V_tab, dc.U_K, dc.U_V, dc.n_valid, dc.utility, g.k, pk.COMBINE_LSE, 0.0, 1.0,
+                        dc.topk, dc.gates, ei, ec, dc.y, dc.row_max, dc.row_norm, dc.scores, dc.slot_coef,
+                        dc.workspace)
+    ridx, rcnt = orc.evict(u.copy(), np.full((g.B, g.E), S, np.int32), S - 1, max_evict=1)
+    assert (rcnt == 1).all()
+    np.testing.assert_array_equal(t2n(ec), rcnt)
+    np.testing.assert_array_equal(t2n(ei), ridx)
+    assert ridx[0, 0, 0] == S - 1 and ridx[0, 2, 0] == S - 1 and ridx[1, 1, 0] == 0 and ridx[1, 2, 0] == S - 1
 
 
 @pytest.mark.parametrize("seed", range(12))

@@ -258,7 +258,8 @@ def test_policy_arrays_follow_a_compacting_eviction(S, cap):
     dict(B=3, Hq=4, Hkv=2, D=64, E=8, S=48, k=2, dtype="bf16"),
     dict(B=2, Hq=8, Hkv=2, D=128, E=16, S=70, k=3, dtype="bf16"),          # matrix-core attention kernel
     dict(B=2, Hq=4, Hkv=4, D=128, E=8, S=40, k=2, dtype="bf16", rank=32),
-], ids=["d64", "gqa4_d128", "rank32"])
+    dict(B=33, Hq=2, Hkv=2, D=32, E=8, S=24, k=2, dtype="bf16"),           # many sequences
+], ids=["d64", "gqa4_d128", "rank32", "b33_e8"])
 def test_fused_step_with_a_policy_is_bit_identical_to_the_separate_calls(name, spec):
     """pikv_decode_step_policy against the sequence it is defined as: route, policy utility, evict,
     stamp, append, attend, tracked update - all state equal bit for bit over several steps."""
